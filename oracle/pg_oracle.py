@@ -1,0 +1,320 @@
+"""fp64 CPU oracle for the multi-turn policy-gradient head (TEST INFRASTRUCTURE).
+
+This file is the yardstick the HIP library is measured against.  It is plain
+numpy in float64, written from the paper's statement of the method, and shares
+no code, table or helper with the GPU path.  Nothing outside tests/, the smoke
+check and the benchmark's CPU-baseline leg may import it.
+
+What follows the paper directly
+  * turn returns            -- Sec. 4.2, Eq. (2)  (reward-to-go, discount gamma)
+  * GRPO mean baseline      -- Sec. 4.2, Eq. (3)  (kept as a cross-check)
+  * TRLOO advantages        -- Sec. 4.2, Eq. (5)  (leave-one-out over the valid
+                               rollouts of one prompt at one turn)
+  * mismatch rejection      -- Sec. 5.1 (geometric-mean ratio window and the
+                               token-level veto)
+  * gradient direction      -- App. A: grad of log pi(y|s) times the advantage;
+                               for a softmax head d log pi(y) / d z = onehot - p.
+
+What the paper does not write down and is fixed here by definition (each is a
+stated reading, "parity unpinned" beyond self-consistency): the PPO-style
+clipped surrogate and its epsilon, token-mean normalisation, the truncated
+importance weight of mode 2, the temperature, and A = 0 for groups of fewer
+than two valid rollouts.  Everything else in this file is pinned by the tests
+under tests/ that do not need a GPU (closed forms, brute force, a library
+log-softmax, autograd cross-entropy, finite differences, exact enumeration).
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+
+import numpy as np
+
+
+# --------------------------------------------------------------------------
+# parameters (names follow the C header; values follow the paper where given)
+# --------------------------------------------------------------------------
+@dataclass
+class Params:
+    temperature: float = 1.0
+    clip_eps_lo: float = 0.2
+    clip_eps_hi: float = 0.2
+    mismatch_mode: int = 0        # 0 none, 1 geometric rejection (Sec. 5.1), 2 token truncation
+    geo_lo: float = 0.999         # Sec. 5.1: keep iff w in [0.999, 1.001]
+    geo_hi: float = 1.001
+    veto_ratio: float = 1e-4      # Sec. 5.1: reject the sample if any token ratio < 1e-4
+    trunc_c: float = 2.0
+    norm_override: float = 0.0
+
+
+def _f32(x: float) -> float:
+    """Thresholds cross the C boundary as float32; use the same value here."""
+    return float(np.float32(x))
+
+
+# --------------------------------------------------------------------------
+# Sec. 4.2, Eq. (1): R = C + C * min(T_reference / T_kernel, 3)
+# (the stage before the path; here so the paper's worked example can be replayed)
+# --------------------------------------------------------------------------
+def reward_eq1(correct, speedup, cap: float = 3.0) -> np.ndarray:
+    C = np.asarray(correct, dtype=np.float64)
+    return C + C * np.minimum(np.asarray(speedup, dtype=np.float64), cap)
+
+
+# --------------------------------------------------------------------------
+# Sec. 4.2, Eq. (2): G_{i,t} = sum_{t' >= t} gamma^(t'-t) R_{i,t'}
+# --------------------------------------------------------------------------
+def returns(rewards: np.ndarray, gamma: float = 1.0) -> np.ndarray:
+    R = np.asarray(rewards, dtype=np.float64)
+    P, K, Tm = R.shape
+    g = float(np.float32(gamma))
+    G = np.zeros_like(R)
+    for p in range(P):
+        for k in range(K):
+            for t in range(Tm):
+                acc = 0.0
+                for tp in range(t, Tm):
+                    acc += (g ** (tp - t)) * R[p, k, tp]
+                G[p, k, t] = acc
+    return G
+
+
+# --------------------------------------------------------------------------
+# Sec. 4.2, Eq. (3): A = G - mean over the valid rollouts of the turn group
+# --------------------------------------------------------------------------
+def grpo_advantage(rewards, valid, gamma: float = 1.0) -> np.ndarray:
+    G = returns(rewards, gamma)
+    valid = np.asarray(valid).astype(bool)
+    P, K, Tm = G.shape
+    A = np.zeros_like(G)
+    for p in range(P):
+        for t in range(Tm):
+            members = [k for k in range(K) if valid[p, k, t]]
+            if not members:
+                continue
+            mean = sum(G[p, j, t] for j in members) / len(members)
+            for k in members:
+                A[p, k, t] = G[p, k, t] - mean
+    return A
+
+
+# --------------------------------------------------------------------------
+# Sec. 4.2, Eq. (5): A_{i,t} = G_{i,t} - 1/(N_t-1) * sum_{j in group, j != i} G_{j,t}
+# Groups with fewer than two valid rollouts have no leave-one-out baseline:
+# their advantages are 0 (a reading; the equation is stated for N_t > 1 only).
+# --------------------------------------------------------------------------
+def trloo_advantage(rewards, valid, gamma: float = 1.0):
+    G = returns(rewards, gamma)
+    valid = np.asarray(valid).astype(bool)
+    P, K, Tm = G.shape
+    A = np.zeros_like(G)
+    N = np.zeros((P, Tm), dtype=np.int32)
+    for p in range(P):
+        for t in range(Tm):
+            members = [k for k in range(K) if valid[p, k, t]]
+            N[p, t] = len(members)
+            if len(members) < 2:
+                continue
+            for i in members:
+                others = 0.0
+                for j in members:
+                    if j != i:
+                        others += G[p, j, t]
+                A[p, i, t] = G[p, i, t] - others / (len(members) - 1)
+    return G, A, N
+
+
+# --------------------------------------------------------------------------
+# LM head: z = H W^T / tau, log-softmax, sampled-token log-prob, entropy.
+# pi_train(a_t | s_t) of Sec. 5.1 is softmax(z)[y_t]; entropy is the monitor
+# the paper plots (nats, of the temperature-scaled distribution).
+# --------------------------------------------------------------------------
+def logits(H, W, tau: float = 1.0) -> np.ndarray:
+    H = np.asarray(H, dtype=np.float64)
+    W = np.asarray(W, dtype=np.float64)
+    return (H @ W.T) / _f32(tau)
+
+
+def logprob_entropy_from_logits(z: np.ndarray, y: np.ndarray):
+    M = z.max(axis=1, keepdims=True)
+    e = np.exp(z - M)
+    s = e.sum(axis=1, keepdims=True)
+    lse = (M + np.log(s))[:, 0]
+    p = e / s
+    logp = z[np.arange(z.shape[0]), y] - lse
+    ent = lse - (p * z).sum(axis=1)
+    return logp, ent, lse, p
+
+
+def lm_head_logprob(H, W, y, tau: float = 1.0, row_mask=None, block: int = 512):
+    """Per-row log-prob of y, entropy and logsumexp; masked rows give 0."""
+    H = np.asarray(H, dtype=np.float64)
+    y = np.asarray(y, dtype=np.int64)
+    T = H.shape[0]
+    act = np.ones(T, bool) if row_mask is None else np.asarray(row_mask).astype(bool)
+    logp = np.zeros(T)
+    ent = np.zeros(T)
+    lse = np.zeros(T)
+    rows = np.nonzero(act)[0]
+    for a in range(0, len(rows), block):
+        r = rows[a:a + block]
+        z = logits(H[r], W, tau)
+        lp, en, ls, _ = logprob_entropy_from_logits(z, y[r])
+        logp[r], ent[r], lse[r] = lp, en, ls
+    return logp, ent, lse
+
+
+def merge_softmax_partials(parts):
+    """Combine partial (m, s, u) states of a row, s = sum e^(z-m), u = sum e^(z-m)(z-m).
+
+    Not used by the oracle itself (which takes the whole row at once); it states
+    the algebra a blocked implementation must obey and is unit-tested against the
+    direct formula.  Returns (lse, entropy).
+    """
+    m, s, u = parts[0]
+    for (m2, s2, u2) in parts[1:]:
+        mm = max(m, m2)
+        a1, a2 = np.exp(m - mm), np.exp(m2 - mm)
+        u = a1 * (u + (m - mm) * s) + a2 * (u2 + (m2 - mm) * s2)
+        s = a1 * s + a2 * s2
+        m = mm
+    lse = m + np.log(s)
+    ent = np.log(s) - u / s
+    return lse, ent
+
+
+# --------------------------------------------------------------------------
+# Sec. 5.1: mismatch correction from trainer-vs-rollout log-probs of the sampled
+# tokens.  One segment = one training sample = one (prompt, rollout, turn); |T|
+# is the number of its loss (response) tokens.  No gradient flows through it.
+# --------------------------------------------------------------------------
+def mismatch_weights(old_logp, rollout_logp, loss_mask, cu_seqlens, prm: Params):
+    """Returns c[T] (weight per token), active[T], seg_keep[S], counters dict."""
+    loss_mask = np.asarray(loss_mask).astype(bool)
+    T = loss_mask.shape[0]
+    cu = np.asarray(cu_seqlens, dtype=np.int64)
+    S = len(cu) - 1
+    c = np.zeros(T)
+    keep = np.ones(S, bool)
+    n_geo = n_veto = n_trunc = 0
+    if prm.mismatch_mode == 0:
+        c[loss_mask] = 1.0
+        return c, loss_mask.copy(), keep, dict(geo=0, veto=0, trunc=0)
+    delta = np.asarray(old_logp, np.float64) - np.asarray(rollout_logp, np.float64)
+    veto = _f32(prm.veto_ratio)
+    for s in range(S):
+        idx = np.arange(cu[s], cu[s + 1])
+        idx = idx[loss_mask[idx]]
+        if len(idx) == 0:
+            continue
+        d = delta[idx]
+        vetoed = veto > 0.0 and np.exp(d.min()) < veto          # "drops below 1e-4"
+        if vetoed:
+            n_veto += 1
+        if prm.mismatch_mode == 1:
+            w = np.exp(d.sum() / len(idx))                       # geometric-mean ratio
+            in_window = (_f32(prm.geo_lo) <= w) and (w <= _f32(prm.geo_hi))
+            if not in_window:
+                n_geo += 1
+            keep[s] = in_window and not vetoed
+            if keep[s]:
+                c[idx] = 1.0
+        else:                                                    # mode 2: truncated token weight
+            keep[s] = not vetoed
+            if keep[s]:
+                ratio = np.exp(d)
+                n_trunc += int((ratio > _f32(prm.trunc_c)).sum())
+                c[idx] = np.minimum(ratio, _f32(prm.trunc_c))
+    active = np.zeros(T, bool)
+    for s in range(S):
+        if keep[s]:
+            sl = slice(cu[s], cu[s + 1])
+            active[sl] = loss_mask[sl]
+    return c, active, keep, dict(geo=n_geo, veto=n_veto, trunc=n_trunc)
+
+
+# --------------------------------------------------------------------------
+# Clipped surrogate on r = pi_theta / pi_old with advantage A (per token).
+#   l = -min(r A, clip(r, 1-eps_lo, 1+eps_hi) A);   g = dl / dlogp.
+# With one update per rollout batch r = 1 and g = -A: App. A's estimator.
+# --------------------------------------------------------------------------
+def surrogate(logp, old_logp, A, prm: Params):
+    r = np.ones_like(logp) if old_logp is None else np.exp(logp - old_logp)
+    lo, hi = 1.0 - _f32(prm.clip_eps_lo), 1.0 + _f32(prm.clip_eps_hi)
+    loss = -np.minimum(r * A, np.clip(r, lo, hi) * A)
+    flows = ((A >= 0) & (r <= hi)) | ((A < 0) & (r >= lo))
+    g = np.where(flows, -A * r, 0.0)
+    clip_hi = (A >= 0) & (r > hi)
+    clip_lo = (A < 0) & (r < lo)
+    return loss, g, r, clip_hi, clip_lo
+
+
+def pg_loss_fwd_bwd(H, W, y, loss_mask, cu_seqlens, adv_seg, old_logp, rollout_logp,
+                    prm: Params, dW_prev=None, block: int = 256):
+    """Loss, dH, dW, per-token log-prob/entropy and counters, all float64.
+
+    adv_seg[s] is the advantage of segment s, broadcast to its loss tokens.
+    """
+    H = np.asarray(H, dtype=np.float64)
+    W = np.asarray(W, dtype=np.float64)
+    y = np.asarray(y, dtype=np.int64)
+    T, d = H.shape
+    V = W.shape[0]
+    tau = _f32(prm.temperature)
+    cu = np.asarray(cu_seqlens, dtype=np.int64)
+    S = len(cu) - 1
+    loss_mask = np.asarray(loss_mask).astype(bool)
+    old = None if old_logp is None else np.asarray(old_logp, np.float64)
+
+    c, active, keep, mm = mismatch_weights(old, rollout_logp, loss_mask, cu, prm)
+    n_active = int(active.sum())
+    norm = _f32(prm.norm_override) if prm.norm_override > 0 else float(max(1, n_active))
+
+    A_tok = np.zeros(T)
+    for s in range(S):
+        A_tok[cu[s]:cu[s + 1]] = float(adv_seg[s])
+
+    logp = np.zeros(T)
+    ent = np.zeros(T)
+    dH = np.zeros((T, d))
+    dW = np.zeros((V, d)) if dW_prev is None else np.array(dW_prev, dtype=np.float64)
+    total = 0.0
+    n_hi = n_lo = 0
+    rows = np.nonzero(active)[0]
+    for a in range(0, len(rows), block):
+        r_ = rows[a:a + block]
+        z = logits(H[r_], W, tau)
+        lp, en, _, p = logprob_entropy_from_logits(z, y[r_])
+        logp[r_], ent[r_] = lp, en
+        l, g, _, chi, clo = surrogate(lp, None if old is None else old[r_], A_tok[r_], prm)
+        total += float((c[r_] * l).sum())
+        n_hi += int(chi.sum())
+        n_lo += int(clo.sum())
+        coef = c[r_] * g / norm                       # d(loss)/d(logp_t)
+        dS = -p * (coef / tau)[:, None]               # (coef/tau) * (onehot - p)
+        dS[np.arange(len(r_)), y[r_]] += coef / tau
+        dH[r_] = dS @ W
+        dW += dS.T @ H[r_]
+    counters = np.array([n_active, n_hi, n_lo, mm["geo"], mm["veto"], mm["trunc"],
+                         int(loss_mask.sum()), 0], dtype=np.int64)
+    return dict(loss=total / norm, dH=dH, dW=dW, logp=logp, entropy=ent,
+                counters=counters, active=active, c=c, norm=norm)
+
+
+def loss_value_only(H, W, y, loss_mask, cu_seqlens, adv_seg, old_logp, rollout_logp, prm: Params):
+    """The scalar loss as a function of (H, W) with everything else held fixed."""
+    return pg_loss_fwd_bwd(H, W, y, loss_mask, cu_seqlens, adv_seg, old_logp,
+                           rollout_logp, prm)["loss"]
+
+
+# --------------------------------------------------------------------------
+# Row-sampled variants for sizes where the whole problem is too slow in fp64:
+# every per-row quantity (log-prob, entropy, dH row) depends on that row alone
+# once the token weights c, the advantages and the normaliser are known.
+# --------------------------------------------------------------------------
+def dH_rows(H_rows, W, y_rows, coef_rows, tau: float):
+    z = logits(H_rows, W, tau)
+    _, _, _, p = logprob_entropy_from_logits(z, np.asarray(y_rows, np.int64))
+    k = np.asarray(coef_rows, np.float64) / _f32(tau)
+    dS = -p * k[:, None]
+    dS[np.arange(len(k)), np.asarray(y_rows, np.int64)] += k
+    return dS @ np.asarray(W, np.float64)
