@@ -1,0 +1,160 @@
+/*
+ * pg_head.h -- C ABI of the MI355X policy-gradient head.
+ *
+ * The library computes, for one packed microbatch of a multi-turn RL step, the
+ * per-token policy-gradient quantities over the vocabulary without ever writing
+ * the [tokens x vocab] logits to device memory:
+ *
+ *   trloo_advantage   turn returns and leave-one-out advantages   (Sec. 4.2, Eq. 2 and 5)
+ *   pg_logprob_fwd    LM-head log-prob / entropy / logsumexp of the sampled tokens
+ *                     (pi_train(a_t|s_t) of Sec. 5.1; entropy is the monitor of Sec. 5.1)
+ *   pg_loss_fwd_bwd   mismatch correction (Sec. 5.1), clipped surrogate whose gradient is
+ *                     grad log pi * A (App. A), backward to dH and dW
+ *
+ * Conventions
+ *   - Every pointer is a DEVICE pointer unless its name starts with h_ (pg_params is
+ *     passed by host pointer).  The caller owns all buffers; the library allocates
+ *     and frees nothing and keeps no state between calls except lazily initialised
+ *     kernel attributes.
+ *   - All work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the
+ *     default stream).  No call synchronises with the host; scalar results are
+ *     written to device memory.
+ *   - Arguments are validated on the host before anything is enqueued.  On error
+ *     the return value is negative, nothing has been enqueued and nothing is written;
+ *     pg_last_error() gives a thread-local message.
+ *   - H is [T,d] row-major, W is [V,d] row-major (LM-head weight, no bias), y[t] is
+ *     the token whose log-prob row t predicts (the caller has already shifted).
+ *     dtype 0: H, W, dH are bf16 (fp32 accumulation); dtype 1: H, W, dH are fp32.
+ *   - Shapes: d must be a multiple of 64, 1 <= d, 1 <= V, 0 <= T; each operand and
+ *     each scratch matrix must stay below 4 GiB; otherwise PG_ERR_UNSUPPORTED_SHAPE.
+ *     H, W, dH, dW and workspace must be 16-byte aligned.
+ *   - y[t] outside [0,V) on an active row is not detected: that row's log-prob is
+ *     then -logsumexp and its gradient has no one-hot term.  No memory is addressed
+ *     through y.
+ */
+#ifndef PG_HEAD_H
+#define PG_HEAD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define PG_OK 0
+#define PG_ERR_INVALID_ARG (-1)
+#define PG_ERR_UNSUPPORTED_SHAPE (-2)
+#define PG_ERR_WORKSPACE_TOO_SMALL (-3)
+#define PG_ERR_HIP (-4)
+
+#define PG_DTYPE_BF16 0
+#define PG_DTYPE_F32 1
+
+#define PG_MISMATCH_NONE 0      /* c_t = 1 */
+#define PG_MISMATCH_GEOMETRIC 1 /* Sec. 5.1: keep a sample iff exp(mean log-ratio) in [geo_lo, geo_hi] */
+#define PG_MISMATCH_TRUNCATE 2  /* c_t = min(pi_train/pi_rollout, trunc_c) per token */
+
+#define PG_CALL_LOGPROB_FWD 0
+#define PG_CALL_LOSS_FWD_BWD 1
+
+/* indices into counters_out[8] */
+#define PG_CNT_ACTIVE 0      /* loss tokens of kept samples */
+#define PG_CNT_CLIP_HI 1     /* A >= 0 and ratio > 1 + eps_hi (no gradient) */
+#define PG_CNT_CLIP_LO 2     /* A <  0 and ratio < 1 - eps_lo (no gradient) */
+#define PG_CNT_SEG_GEO 3     /* samples outside the geometric window (mode 1) */
+#define PG_CNT_SEG_VETO 4    /* samples with a token ratio below veto_ratio */
+#define PG_CNT_TRUNCATED 5   /* tokens whose weight was capped (mode 2) */
+#define PG_CNT_LOSS_TOKENS 6 /* rows with loss_mask = 1 */
+
+typedef struct pg_params {
+  int32_t dtype;         /* PG_DTYPE_* of H, W and dH */
+  float temperature;     /* tau > 0: logits are divided by tau before the softmax */
+  float clip_eps_lo;     /* clip range of pi_theta/pi_old is [1-eps_lo, 1+eps_hi] */
+  float clip_eps_hi;
+  int32_t mismatch_mode; /* PG_MISMATCH_* */
+  float geo_lo;          /* 0.999 in Sec. 5.1 */
+  float geo_hi;          /* 1.001 in Sec. 5.1 */
+  float veto_ratio;      /* 1e-4 in Sec. 5.1; 0 disables the token veto */
+  float trunc_c;         /* cap of mode 2 */
+  float norm_override;   /* <= 0: normalise by the number of active tokens (at least 1);
+                            > 0: divide by this value (e.g. a global token count) */
+  int32_t accumulate_dW; /* 0: dW is overwritten; 1: dW += */
+  int32_t dW_dtype;      /* 0: fp32, 1: bf16 */
+} pg_params;
+
+/* Message for the last error returned on this thread ("" if none). */
+const char* pg_last_error(void);
+
+/*
+ * Bytes of device workspace the given call needs for these sizes (S is ignored for
+ * PG_CALL_LOGPROB_FWD).  Returns 0 if the arguments are invalid or unsupported.
+ * The workspace need not be initialised and holds nothing the caller may rely on.
+ */
+size_t pg_workspace_bytes(int64_t T, int64_t d, int64_t V, int32_t S, const pg_params* h_params,
+                          int32_t which_call);
+
+/*
+ * Sec. 4.2, Eq. (2) and Eq. (5).
+ *   rewards[(p*K+k)*Tmax+t]  per-turn reward R of rollout k of prompt p at turn t (0 where the
+ *                            turn was never generated)
+ *   valid  (same indexing)   1 iff the rollout belongs to the turn group G_t of its prompt
+ *   returns_out (nullable)   G = sum_{t'>=t} gamma^(t'-t) R, for every entry
+ *   adv_out                  A = G - mean of the other valid rollouts' G of the same prompt
+ *                            and turn; 0 for invalid entries and for groups with N_t < 2
+ *   group_n_out (nullable)   [P*Tmax] N_t
+ * Accumulation and outputs are fp64.  P, K, Tmax >= 1.
+ */
+int32_t trloo_advantage(const float* rewards, const uint8_t* valid, int32_t P, int32_t K, int32_t Tmax,
+                        float gamma, double* returns_out, double* adv_out, int32_t* group_n_out,
+                        void* stream);
+
+/*
+ * Log-prob of y[t], entropy and logsumexp of softmax(H W^T / tau) for the rows with
+ * row_mask[t] != 0 (row_mask NULL = all rows).  Outputs are float32 [T]; rows that are
+ * masked out are written as 0.  entropy_out and lse_out may be NULL.
+ */
+int32_t pg_logprob_fwd(const void* H, const void* W, const int32_t* y, const uint8_t* row_mask, int64_t T,
+                       int64_t d, int64_t V, const pg_params* h_params, float* logp_out,
+                       float* entropy_out, float* lse_out, void* workspace, size_t workspace_bytes,
+                       void* stream);
+
+/*
+ * Loss forward and backward for one packed microbatch of S segments; segment s covers
+ * rows cu_seqlens[s] .. cu_seqlens[s+1]-1 (cu_seqlens[0] = 0, cu_seqlens[S] = T) and is one
+ * training sample, i.e. one (prompt, rollout, turn).
+ *
+ *   loss_mask[t]      1 on response tokens (context / feedback rows are 0)
+ *   adv               fp64 table of advantages (e.g. adv_out of trloo_advantage)
+ *   seg_sample        [S] index into adv of each segment; NULL = segment s uses adv[s]
+ *   old_logp          [T] log-prob under the policy that the update starts from; NULL =
+ *                     on-policy (ratio 1, gradient of log-prob times advantage)
+ *   rollout_logp      [T] log-prob reported by the rollout engine; required unless
+ *                     mismatch_mode is PG_MISMATCH_NONE (old_logp is then required too)
+ *
+ * With delta_t = old_logp - rollout_logp on loss tokens, a sample is rejected if
+ * exp(min delta) < veto_ratio, and in mode 1 also unless geo_lo <= exp(mean delta) <= geo_hi;
+ * c_t is 1 (modes 0, 1) or min(exp(delta_t), trunc_c) (mode 2).  Active rows are the loss
+ * tokens of samples that were not rejected.  For active rows, with r = exp(logp - old_logp)
+ * and A the segment's advantage,
+ *   l_t   = -min(r A, clip(r, 1-eps_lo, 1+eps_hi) A)
+ *   loss  = (1/norm) sum_t c_t l_t
+ *   dS    = (c_t (dl_t/dlogp_t) / (norm tau)) (onehot(y_t) - softmax_t)
+ *   dH    = dS W   (rows that are not active are written as 0)
+ *   dW    = dS^T H (added to dW if accumulate_dW)
+ *
+ * Outputs: loss_out (one float), dH [T,d] in the dtype of H, dW [V,d] in dW_dtype,
+ * logp_out [T] and entropy_out [T] (nullable; 0 on rows that are not active),
+ * counters_out [8] int64 (nullable; see PG_CNT_*).
+ */
+int32_t pg_loss_fwd_bwd(const void* H, const void* W, const int32_t* y, const uint8_t* loss_mask,
+                        const int32_t* cu_seqlens, int32_t S, const double* adv,
+                        const int32_t* seg_sample, const float* old_logp, const float* rollout_logp,
+                        int64_t T, int64_t d, int64_t V, const pg_params* h_params, float* loss_out,
+                        void* dH, void* dW, float* logp_out, float* entropy_out, int64_t* counters_out,
+                        void* workspace, size_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PG_HEAD_H */

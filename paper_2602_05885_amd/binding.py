@@ -1,0 +1,181 @@
+"""ctypes binding of libpg_head.so: same names as the C ABI, argument marshalling only.
+
+Every computation happens in the HIP kernels behind the C entry points.  torch is used
+for device memory, data pointers and the current stream.  There is no fallback: if the
+library is missing or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import Optional
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libpg_head.so")
+
+PG_OK = 0
+CALL_LOGPROB_FWD = 0
+CALL_LOSS_FWD_BWD = 1
+COUNTER_NAMES = ("active", "clip_hi", "clip_lo", "seg_geo", "seg_veto", "truncated", "loss_tokens", "reserved")
+
+EXPORTS = ("pg_last_error", "pg_workspace_bytes", "trloo_advantage", "pg_logprob_fwd", "pg_loss_fwd_bwd")
+
+
+class PgParams(C.Structure):
+    _fields_ = [("dtype", C.c_int32), ("temperature", C.c_float), ("clip_eps_lo", C.c_float),
+                ("clip_eps_hi", C.c_float), ("mismatch_mode", C.c_int32), ("geo_lo", C.c_float),
+                ("geo_hi", C.c_float), ("veto_ratio", C.c_float), ("trunc_c", C.c_float),
+                ("norm_override", C.c_float), ("accumulate_dW", C.c_int32), ("dW_dtype", C.c_int32)]
+
+
+@dataclass
+class Params:
+    """Host-side mirror of pg_params (defaults: the paper's thresholds, Sec. 5.1)."""
+    dtype: int = 0
+    temperature: float = 1.0
+    clip_eps_lo: float = 0.2
+    clip_eps_hi: float = 0.2
+    mismatch_mode: int = 0
+    geo_lo: float = 0.999
+    geo_hi: float = 1.001
+    veto_ratio: float = 1e-4
+    trunc_c: float = 2.0
+    norm_override: float = 0.0
+    accumulate_dW: int = 0
+    dW_dtype: int = 0
+
+    def c_struct(self) -> PgParams:
+        return PgParams(self.dtype, self.temperature, self.clip_eps_lo, self.clip_eps_hi, self.mismatch_mode,
+                        self.geo_lo, self.geo_hi, self.veto_ratio, self.trunc_c, self.norm_override,
+                        self.accumulate_dW, self.dW_dtype)
+
+
+class PgError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"pg_head error {code}: {msg}")
+        self.code = code
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """Loads the shared library (once).  Raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2602_05885_amd.build`")
+        L = C.CDLL(LIB_PATH)
+        L.pg_last_error.restype = C.c_char_p
+        L.pg_last_error.argtypes = []
+        L.pg_workspace_bytes.restype = C.c_size_t
+        L.pg_workspace_bytes.argtypes = [C.c_int64, C.c_int64, C.c_int64, C.c_int32, C.POINTER(PgParams), C.c_int32]
+        L.trloo_advantage.restype = C.c_int32
+        L.trloo_advantage.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_float,
+                                      C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.pg_logprob_fwd.restype = C.c_int32
+        L.pg_logprob_fwd.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_int64,
+                                     C.POINTER(PgParams), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                     C.c_size_t, C.c_void_p]
+        L.pg_loss_fwd_bwd.restype = C.c_int32
+        L.pg_loss_fwd_bwd.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
+                                      C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int64,
+                                      C.c_int64, C.POINTER(PgParams), C.c_void_p, C.c_void_p, C.c_void_p,
+                                      C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        _lib = L
+    return _lib
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    if t is None:
+        return None
+    if not t.is_contiguous():
+        raise ValueError("tensors passed to the C ABI must be contiguous")
+    return C.c_void_p(t.data_ptr())
+
+
+def _stream(stream=None):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return C.c_void_p(stream.cuda_stream)
+
+
+def _check(rc: int):
+    if rc != PG_OK:
+        raise PgError(rc, lib().pg_last_error().decode())
+
+
+def pg_last_error() -> str:
+    return lib().pg_last_error().decode()
+
+
+def pg_workspace_bytes(T: int, d: int, V: int, S: int, params: Params, which_call: int) -> int:
+    p = params.c_struct()
+    return int(lib().pg_workspace_bytes(T, d, V, S, C.byref(p), which_call))
+
+
+def alloc_workspace(T: int, d: int, V: int, S: int, params: Params, which_call: int, device="cuda") -> torch.Tensor:
+    n = pg_workspace_bytes(T, d, V, S, params, which_call)
+    if n == 0:
+        raise PgError(-1, pg_last_error())
+    return torch.empty(n, dtype=torch.uint8, device=device)
+
+
+def trloo_advantage(rewards: torch.Tensor, valid: torch.Tensor, gamma: float = 1.0, want_returns=True,
+                    want_group_n=True, stream=None):
+    """rewards float32 [P,K,Tmax], valid uint8 [P,K,Tmax] (device).  Returns (adv f64, returns f64|None, N i32|None)."""
+    P, K, Tm = rewards.shape
+    assert rewards.dtype == torch.float32 and valid.dtype == torch.uint8 and valid.shape == rewards.shape
+    adv = torch.empty((P, K, Tm), dtype=torch.float64, device=rewards.device)
+    ret = torch.empty_like(adv) if want_returns else None
+    gn = torch.empty((P, Tm), dtype=torch.int32, device=rewards.device) if want_group_n else None
+    _check(lib().trloo_advantage(_ptr(rewards), _ptr(valid), P, K, Tm, gamma, _ptr(ret), _ptr(adv), _ptr(gn),
+                                 _stream(stream)))
+    return adv, ret, gn
+
+
+def pg_logprob_fwd(H, W, y, row_mask, params: Params, workspace: torch.Tensor, want_entropy=True, want_lse=True,
+                   out=None, stream=None):
+    """Returns (logp, entropy|None, lse|None), float32 [T] on the device of H."""
+    T, d = H.shape
+    V = W.shape[0]
+    if out is None:
+        logp = torch.empty(T, dtype=torch.float32, device=H.device)
+        ent = torch.empty_like(logp) if want_entropy else None
+        lse = torch.empty_like(logp) if want_lse else None
+    else:
+        logp, ent, lse = out
+    p = params.c_struct()
+    _check(lib().pg_logprob_fwd(_ptr(H), _ptr(W), _ptr(y), _ptr(row_mask), T, d, V, C.byref(p), _ptr(logp),
+                                _ptr(ent), _ptr(lse), _ptr(workspace), workspace.numel(), _stream(stream)))
+    return logp, ent, lse
+
+
+def pg_loss_fwd_bwd(H, W, y, loss_mask, cu_seqlens, adv, seg_sample, old_logp, rollout_logp, params: Params,
+                    workspace: torch.Tensor, dW: Optional[torch.Tensor] = None, out=None, stream=None):
+    """Returns dict(loss [1] f32, dH, dW, logp, entropy, counters [8] i64), all on the device of H."""
+    T, d = H.shape
+    V = W.shape[0]
+    S = cu_seqlens.numel() - 1
+    dev = W.device
+    if out is None:
+        loss = torch.empty(1, dtype=torch.float32, device=dev)
+        dH = torch.empty_like(H)
+        logp = torch.empty(T, dtype=torch.float32, device=dev)
+        ent = torch.empty(T, dtype=torch.float32, device=dev)
+        counters = torch.empty(8, dtype=torch.int64, device=dev)
+    else:
+        loss, dH, logp, ent, counters = out
+    if dW is None:
+        if params.accumulate_dW:
+            raise ValueError("accumulate_dW needs an existing dW")
+        dW = torch.empty((V, d), dtype=torch.bfloat16 if params.dW_dtype else torch.float32, device=dev)
+    p = params.c_struct()
+    _check(lib().pg_loss_fwd_bwd(_ptr(H), _ptr(W), _ptr(y), _ptr(loss_mask), _ptr(cu_seqlens), S, _ptr(adv),
+                                 _ptr(seg_sample), _ptr(old_logp), _ptr(rollout_logp), T, d, V, C.byref(p),
+                                 _ptr(loss), _ptr(dH), _ptr(dW), _ptr(logp), _ptr(ent), _ptr(counters),
+                                 _ptr(workspace), workspace.numel(), _stream(stream)))
+    return dict(loss=loss, dH=dH, dW=dW, logp=logp, entropy=ent, counters=counters)

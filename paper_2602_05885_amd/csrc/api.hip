@@ -1,0 +1,340 @@
+// Host side of the C ABI: argument validation, workspace planning, kernel sequencing.
+// Nothing here synchronises with the device or allocates device memory.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+
+#include "../../include/pg_head.h"
+#include "gemm_core.h"
+#include "kernels.h"
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+int32_t fail(int32_t code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+constexpr size_t ALIGN = 256;
+constexpr uint64_t FOUR_GIB = 1ull << 32;
+constexpr uint64_t DS_BUDGET = 2ull << 30;   // bytes per orientation of the dS chunk scratch
+constexpr double LOG2E = 1.4426950408889634;
+
+// Tuning knob: PG_HEAD_DS_BUDGET_BYTES overrides the size of the dS chunk scratch (and with
+// it the number of vocab chunks of the backward pass).
+uint64_t ds_budget() {
+  if (const char* e = std::getenv("PG_HEAD_DS_BUDGET_BYTES")) {
+    const unsigned long long v = std::strtoull(e, nullptr, 10);
+    if (v > 0) return v;
+  }
+  return DS_BUDGET;
+}
+
+inline size_t align_up(size_t x) { return (x + ALIGN - 1) / ALIGN * ALIGN; }
+
+struct Plan {
+  int64_t T = 0, d = 0, V = 0;
+  int is_f32 = 0;
+  int t_cap = 0;       // T rounded up to 256
+  int kd = 0;          // contraction length of the logits (d, or 3d for the split fp32 path)
+  int tiles_v = 0;     // 256-row vocab tiles
+  int tiles_t = 0;
+  int chunk_tiles = 0; // vocab tiles per backward chunk
+  int nchunks = 0;
+  int vc = 0;          // chunk_tiles * 256
+  size_t ctl, counters, flag, c_tok, a_tok, rows, pos, yc, zy, lse2, coefc, lossterm;
+  size_t part_m, part_s, part_u, Hc, HcT, Wc, dS, dST, WT, dHacc;
+  size_t total = 0;
+};
+
+int32_t check_params(const pg_params* p) {
+  if (!p) return fail(PG_ERR_INVALID_ARG, "params is NULL");
+  if (p->dtype != PG_DTYPE_BF16 && p->dtype != PG_DTYPE_F32) return fail(PG_ERR_INVALID_ARG, "unknown dtype %d", p->dtype);
+  if (!(p->temperature > 0.f) || !std::isfinite(p->temperature))
+    return fail(PG_ERR_INVALID_ARG, "temperature must be finite and > 0");
+  if (p->mismatch_mode < 0 || p->mismatch_mode > 2) return fail(PG_ERR_INVALID_ARG, "unknown mismatch_mode %d", p->mismatch_mode);
+  if (!(p->clip_eps_lo >= 0.f) || !(p->clip_eps_hi >= 0.f)) return fail(PG_ERR_INVALID_ARG, "clip eps must be >= 0");
+  if (p->mismatch_mode == PG_MISMATCH_GEOMETRIC && !(p->geo_lo <= p->geo_hi))
+    return fail(PG_ERR_INVALID_ARG, "geo_lo must be <= geo_hi");
+  if (p->mismatch_mode == PG_MISMATCH_TRUNCATE && !(p->trunc_c > 0.f))
+    return fail(PG_ERR_INVALID_ARG, "trunc_c must be > 0");
+  if (!(p->veto_ratio >= 0.f)) return fail(PG_ERR_INVALID_ARG, "veto_ratio must be >= 0");
+  if (p->dW_dtype != 0 && p->dW_dtype != 1) return fail(PG_ERR_INVALID_ARG, "unknown dW_dtype %d", p->dW_dtype);
+  return PG_OK;
+}
+
+int32_t make_plan(int64_t T, int64_t d, int64_t V, int32_t S, const pg_params* p, int which, Plan& pl) {
+  int32_t rc = check_params(p);
+  if (rc) return rc;
+  if (which != PG_CALL_LOGPROB_FWD && which != PG_CALL_LOSS_FWD_BWD) return fail(PG_ERR_INVALID_ARG, "unknown call id %d", which);
+  if (T < 0 || d < 1 || V < 1 || S < 0) return fail(PG_ERR_INVALID_ARG, "negative or zero extent (T=%lld d=%lld V=%lld S=%d)", (long long)T, (long long)d, (long long)V, S);
+  if (d % 64 != 0) return fail(PG_ERR_UNSUPPORTED_SHAPE, "d=%lld is not a multiple of 64", (long long)d);
+  if (T > (1ll << 30) || V > (1ll << 30)) return fail(PG_ERR_UNSUPPORTED_SHAPE, "T or V too large");
+  pl.T = T; pl.d = d; pl.V = V;
+  pl.is_f32 = p->dtype == PG_DTYPE_F32;
+  const int64_t t_cap = (T + 255) / 256 * 256;
+  const int64_t kd = pl.is_f32 ? 3 * d : d;
+  const int64_t tiles_v = (V + 255) / 256;
+  if ((uint64_t)V * kd * 2 >= FOUR_GIB) return fail(PG_ERR_UNSUPPORTED_SHAPE, "head weight operand reaches 4 GiB");
+  if ((uint64_t)t_cap * kd * 2 >= FOUR_GIB) return fail(PG_ERR_UNSUPPORTED_SHAPE, "hidden-state operand reaches 4 GiB");
+  pl.t_cap = (int)t_cap; pl.kd = (int)kd; pl.tiles_v = (int)tiles_v; pl.tiles_t = (int)(t_cap / 256);
+
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
+  pl.ctl = take(sizeof(pg::Ctl));
+  pl.counters = take(8 * sizeof(unsigned long long));
+  pl.flag = take((size_t)T);
+  pl.c_tok = take((size_t)T * 4);
+  pl.a_tok = take((size_t)T * 4);
+  pl.rows = take((size_t)t_cap * 4);
+  pl.pos = take((size_t)T * 4);
+  pl.yc = take((size_t)t_cap * 4);
+  pl.zy = take((size_t)t_cap * 4);
+  pl.lse2 = take((size_t)t_cap * 4);
+  pl.coefc = take((size_t)t_cap * 4);
+  pl.lossterm = take((size_t)t_cap * 4);
+  pl.part_m = take((size_t)tiles_v * t_cap * 4);
+  pl.part_s = take((size_t)tiles_v * t_cap * 4);
+  pl.part_u = take((size_t)tiles_v * t_cap * 4);
+  pl.Hc = take((size_t)t_cap * kd * 2);
+  pl.Wc = pl.is_f32 ? take((size_t)V * kd * 2) : 0;
+  if (which == PG_CALL_LOSS_FWD_BWD) {
+    int64_t max_tiles = t_cap > 0 ? (int64_t)(ds_budget() / ((uint64_t)t_cap * 2 * 256)) : tiles_v;
+    if (max_tiles < 1) max_tiles = 1;
+    if (max_tiles > tiles_v) max_tiles = tiles_v;
+    const int64_t nchunks = (tiles_v + max_tiles - 1) / max_tiles;
+    const int64_t chunk_tiles = (tiles_v + nchunks - 1) / nchunks;
+    const int64_t vc = chunk_tiles * 256;
+    if ((uint64_t)t_cap * vc * 2 >= FOUR_GIB || (uint64_t)d * vc * 2 >= FOUR_GIB || (uint64_t)d * t_cap * 2 >= FOUR_GIB)
+      return fail(PG_ERR_UNSUPPORTED_SHAPE, "a backward scratch matrix reaches 4 GiB");
+    pl.nchunks = (int)nchunks; pl.chunk_tiles = (int)chunk_tiles; pl.vc = (int)vc;
+    pl.HcT = take((size_t)d * t_cap * 2);
+    pl.dS = take((size_t)t_cap * vc * 2);
+    pl.dST = take((size_t)vc * t_cap * 2);
+    pl.WT = take((size_t)d * vc * 2);
+    pl.dHacc = take((size_t)t_cap * d * 4);
+  }
+  pl.total = off > 0 ? off : ALIGN;
+  return PG_OK;
+}
+
+bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+
+int32_t ensure_init() {
+  static bool done[64] = {};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return fail(PG_ERR_HIP, "hipGetDevice failed");
+  if (dev < 0 || dev >= 64) return fail(PG_ERR_HIP, "device index %d out of range", dev);
+  if (!done[dev]) {
+    hipError_t e = pg::init_gemm_kernels();
+    if (e != hipSuccess) return fail(PG_ERR_HIP, "kernel attribute setup failed: %s", hipGetErrorString(e));
+    done[dev] = true;
+  }
+  return PG_OK;
+}
+
+int32_t check_launches(const char* what) {
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(PG_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+  return PG_OK;
+}
+
+template <typename T>
+T* at(void* ws, size_t off) { return reinterpret_cast<T*>(static_cast<char*>(ws) + off); }
+
+// Steps shared by both calls: pre-pass, operand staging, forward contraction, combine.
+void run_forward(const Plan& pl, const pg_params& p, void* ws, const void* H, const void* W, const int32_t* y,
+                 const pg::PrepArgs& prep, pg::CombineArgs comb, bool need_HT, hipStream_t st) {
+  pg::launch_prepass(prep, st);
+  const void* Wop = W;
+  if (pl.is_f32) {
+    pg::launch_split_w(static_cast<const float*>(W), at<__bf16>(ws, pl.Wc), pl.V, (int)pl.d, st);
+    Wop = at<__bf16>(ws, pl.Wc);
+  }
+  pg::GatherArgs g{};
+  g.H = H; g.y = y; g.d = (int)pl.d; g.t_cap = pl.t_cap; g.is_f32 = pl.is_f32;
+  g.rows = at<int>(ws, pl.rows); g.Hc = at<__bf16>(ws, pl.Hc);
+  g.HcT = need_HT ? at<__bf16>(ws, pl.HcT) : nullptr;
+  g.yc = at<int>(ws, pl.yc); g.ctl = at<pg::Ctl>(ws, pl.ctl);
+  pg::launch_gather(g, st);
+
+  pg::FwdArgs f{};
+  f.W = Wop; f.Hc = at<__bf16>(ws, pl.Hc);
+  f.w_bytes = (uint32_t)((uint64_t)pl.V * pl.kd * 2); f.h_bytes = (uint32_t)((uint64_t)pl.t_cap * pl.kd * 2);
+  f.ldw = pl.kd; f.ldh = pl.kd; f.K = pl.kd; f.V = (int)pl.V;
+  f.tiles_v = pl.tiles_v; f.tiles_t = pl.tiles_t; f.t_cap = pl.t_cap;
+  f.scale = (float)(LOG2E / (double)p.temperature);
+  f.yc = at<int>(ws, pl.yc); f.zy = at<float>(ws, pl.zy);
+  f.part_m = at<float>(ws, pl.part_m); f.part_s = at<float>(ws, pl.part_s); f.part_u = at<float>(ws, pl.part_u);
+  f.ctl = at<pg::Ctl>(ws, pl.ctl);
+  pg::launch_lmhead_fwd(f, st);
+
+  comb.tiles_v = pl.tiles_v; comb.t_cap = pl.t_cap;
+  comb.part_m = f.part_m; comb.part_s = f.part_s; comb.part_u = f.part_u;
+  comb.zy = f.zy; comb.rows = at<int>(ws, pl.rows); comb.lse2 = at<float>(ws, pl.lse2);
+  comb.ctl = f.ctl;
+  pg::launch_combine(comb, st);
+}
+
+pg::PrepArgs base_prep(const Plan& pl, void* ws) {
+  pg::PrepArgs a{};
+  a.T = (int)pl.T; a.t_cap = pl.t_cap;
+  a.flag = at<uint8_t>(ws, pl.flag); a.c_tok = at<float>(ws, pl.c_tok); a.a_tok = at<float>(ws, pl.a_tok);
+  a.rows = at<int>(ws, pl.rows); a.pos = at<int>(ws, pl.pos); a.zy = at<float>(ws, pl.zy);
+  a.counters = at<unsigned long long>(ws, pl.counters); a.ctl = at<pg::Ctl>(ws, pl.ctl);
+  return a;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* pg_last_error(void) { return g_err; }
+
+size_t pg_workspace_bytes(int64_t T, int64_t d, int64_t V, int32_t S, const pg_params* h_params, int32_t which_call) {
+  Plan pl;
+  if (make_plan(T, d, V, S, h_params, which_call, pl) != PG_OK) return 0;
+  return pl.total;
+}
+
+int32_t trloo_advantage(const float* rewards, const uint8_t* valid, int32_t P, int32_t K, int32_t Tmax, float gamma,
+                        double* returns_out, double* adv_out, int32_t* group_n_out, void* stream) {
+  if (!rewards || !valid || !adv_out) return fail(PG_ERR_INVALID_ARG, "rewards, valid and adv_out must not be NULL");
+  if (P < 1 || K < 1 || Tmax < 1) return fail(PG_ERR_INVALID_ARG, "P, K, Tmax must be >= 1");
+  if ((int64_t)P * K * Tmax > (1ll << 30)) return fail(PG_ERR_UNSUPPORTED_SHAPE, "P*K*Tmax too large");
+  if (!std::isfinite(gamma)) return fail(PG_ERR_INVALID_ARG, "gamma must be finite");
+  pg::TrlooArgs a{rewards, valid, P, K, Tmax, gamma, returns_out, adv_out, group_n_out};
+  pg::launch_trloo(a, static_cast<hipStream_t>(stream));
+  return check_launches("trloo_advantage");
+}
+
+int32_t pg_logprob_fwd(const void* H, const void* W, const int32_t* y, const uint8_t* row_mask, int64_t T, int64_t d,
+                       int64_t V, const pg_params* h_params, float* logp_out, float* entropy_out, float* lse_out,
+                       void* workspace, size_t workspace_bytes, void* stream) {
+  Plan pl;
+  int32_t rc = make_plan(T, d, V, 0, h_params, PG_CALL_LOGPROB_FWD, pl);
+  if (rc) return rc;
+  if (T == 0) return PG_OK;
+  if (!H || !W || !y || !logp_out || !workspace) return fail(PG_ERR_INVALID_ARG, "H, W, y, logp_out and workspace must not be NULL");
+  if (misaligned(H) || misaligned(W) || misaligned(workspace)) return fail(PG_ERR_INVALID_ARG, "H, W and workspace must be 16-byte aligned");
+  if (workspace_bytes < pl.total) return fail(PG_ERR_WORKSPACE_TOO_SMALL, "workspace has %zu bytes, %zu needed", workspace_bytes, pl.total);
+  if ((rc = ensure_init())) return rc;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+
+  pg::PrepArgs prep = base_prep(pl, workspace);
+  prep.mask = row_mask;
+  prep.out0 = logp_out; prep.out1 = entropy_out; prep.out2 = lse_out;
+  pg::CombineArgs comb{};
+  comb.logp_out = logp_out; comb.ent_out = entropy_out; comb.lse_out = lse_out;
+  comb.with_loss = 0;
+  run_forward(pl, *h_params, workspace, H, W, y, prep, comb, false, st);
+  return check_launches("pg_logprob_fwd");
+}
+
+int32_t pg_loss_fwd_bwd(const void* H, const void* W, const int32_t* y, const uint8_t* loss_mask,
+                        const int32_t* cu_seqlens, int32_t S, const double* adv, const int32_t* seg_sample,
+                        const float* old_logp, const float* rollout_logp, int64_t T, int64_t d, int64_t V,
+                        const pg_params* h_params, float* loss_out, void* dH, void* dW, float* logp_out,
+                        float* entropy_out, int64_t* counters_out, void* workspace, size_t workspace_bytes,
+                        void* stream) {
+  Plan pl;
+  int32_t rc = make_plan(T, d, V, S, h_params, PG_CALL_LOSS_FWD_BWD, pl);
+  if (rc) return rc;
+  const pg_params& p = *h_params;
+  if (!W || !loss_out || !dW) return fail(PG_ERR_INVALID_ARG, "W, loss_out and dW must not be NULL");
+  if (misaligned(W) || misaligned(dW)) return fail(PG_ERR_INVALID_ARG, "W and dW must be 16-byte aligned");
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const size_t dw_elem = p.dW_dtype ? 2 : 4;
+  if (T == 0) {   // empty microbatch: zero loss, zero gradient
+    pg::launch_fill_f32(loss_out, 1, 0.f, st);
+    if (counters_out) pg::launch_fill_zero_bytes(counters_out, 8 * sizeof(int64_t), st);
+    if (!p.accumulate_dW) pg::launch_fill_zero_bytes(dW, (size_t)V * d * dw_elem, st);
+    return check_launches("pg_loss_fwd_bwd (empty)");
+  }
+  if (!H || !y || !loss_mask || !cu_seqlens || !adv || !dH || !workspace)
+    return fail(PG_ERR_INVALID_ARG, "H, y, loss_mask, cu_seqlens, adv, dH and workspace must not be NULL");
+  if (S < 1) return fail(PG_ERR_INVALID_ARG, "S must be >= 1 when T > 0");
+  if (p.mismatch_mode != PG_MISMATCH_NONE && (!old_logp || !rollout_logp))
+    return fail(PG_ERR_INVALID_ARG, "mismatch correction needs old_logp and rollout_logp");
+  if (misaligned(H) || misaligned(dH) || misaligned(workspace)) return fail(PG_ERR_INVALID_ARG, "H, dH and workspace must be 16-byte aligned");
+  if (workspace_bytes < pl.total) return fail(PG_ERR_WORKSPACE_TOO_SMALL, "workspace has %zu bytes, %zu needed", workspace_bytes, pl.total);
+  if ((rc = ensure_init())) return rc;
+  void* ws = workspace;
+
+  pg::PrepArgs prep = base_prep(pl, ws);
+  prep.mask = loss_mask; prep.cu = cu_seqlens; prep.S = S; prep.adv = adv; prep.seg_sample = seg_sample;
+  prep.old_logp = old_logp; prep.rollout_logp = rollout_logp;
+  prep.mismatch_mode = p.mismatch_mode; prep.geo_lo = p.geo_lo; prep.geo_hi = p.geo_hi;
+  prep.veto_ratio = p.veto_ratio; prep.trunc_c = p.trunc_c; prep.norm_override = p.norm_override;
+  prep.out0 = logp_out; prep.out1 = entropy_out; prep.out2 = nullptr;
+
+  pg::CombineArgs comb{};
+  comb.logp_out = logp_out; comb.ent_out = entropy_out; comb.lse_out = nullptr;
+  comb.with_loss = 1; comb.old_logp = old_logp;
+  comb.c_tok = at<float>(ws, pl.c_tok); comb.a_tok = at<float>(ws, pl.a_tok);
+  comb.eps_lo = p.clip_eps_lo; comb.eps_hi = p.clip_eps_hi; comb.inv_tau = 1.f / p.temperature;
+  comb.coefc = at<float>(ws, pl.coefc); comb.lossterm = at<float>(ws, pl.lossterm);
+  comb.counters = at<unsigned long long>(ws, pl.counters);
+  run_forward(pl, p, ws, H, W, y, prep, comb, true, st);
+
+  pg::FinishArgs fin{at<float>(ws, pl.lossterm), at<unsigned long long>(ws, pl.counters), loss_out,
+                     reinterpret_cast<long long*>(counters_out), at<pg::Ctl>(ws, pl.ctl)};
+  pg::launch_finish(fin, st);
+
+  // ---- backward, one vocab chunk at a time ----
+  const void* Wop = pl.is_f32 ? static_cast<const void*>(at<__bf16>(ws, pl.Wc)) : W;
+  const pg::Ctl* ctl = at<pg::Ctl>(ws, pl.ctl);
+  const int d_i = (int)pl.d;
+  for (int c = 0; c < pl.nchunks; ++c) {
+    const int v0 = c * pl.vc;
+    if (v0 >= pl.V) break;
+    const int rows_valid = (int)((pl.V - v0) < pl.vc ? (pl.V - v0) : pl.vc);
+    const int tiles_c = (rows_valid + 255) / 256;
+    const int kc = tiles_c * 256;
+
+    pg::launch_transpose_w(W, pl.is_f32, pl.V, d_i, v0, kc, pl.vc, at<__bf16>(ws, pl.WT), st);
+
+    pg::DlogitsArgs g{};
+    g.W = Wop; g.Hc = at<__bf16>(ws, pl.Hc);
+    g.w_bytes = (uint32_t)((uint64_t)pl.V * pl.kd * 2); g.h_bytes = (uint32_t)((uint64_t)pl.t_cap * pl.kd * 2);
+    g.ldw = pl.kd; g.ldh = pl.kd; g.K = pl.kd; g.V = (int)pl.V; g.v0 = v0; g.vc = pl.vc;
+    g.tiles_v = tiles_c; g.tiles_t = pl.tiles_t; g.t_cap = pl.t_cap;
+    g.scale = (float)(LOG2E / (double)p.temperature);
+    g.yc = at<int>(ws, pl.yc); g.lse2 = at<float>(ws, pl.lse2); g.coefc = at<float>(ws, pl.coefc);
+    g.dS = at<__bf16>(ws, pl.dS); g.dST = at<__bf16>(ws, pl.dST); g.ctl = ctl;
+    pg::launch_lmhead_dlogits(g, st);
+
+    pg::StoreArgs w{};   // dW[v0 + m, :] = sum_t dS^T[m, t] H^T[:, t]
+    w.A = at<__bf16>(ws, pl.dST); w.B = at<__bf16>(ws, pl.HcT);
+    w.a_bytes = (uint32_t)((uint64_t)pl.vc * pl.t_cap * 2); w.b_bytes = (uint32_t)((uint64_t)pl.d * pl.t_cap * 2);
+    w.lda = pl.t_cap; w.ldb = pl.t_cap; w.M = rows_valid; w.N = d_i; w.K = pl.t_cap;
+    w.tiles_m = tiles_c; w.tiles_n = (d_i + 255) / 256;
+    w.C = static_cast<char*>(dW) + (size_t)v0 * pl.d * dw_elem; w.ldc = d_i;
+    w.accumulate = p.accumulate_dW; w.out_bf16 = p.dW_dtype; w.k_from_ctl = 1; w.m_from_ctl = 0; w.ctl = ctl;
+    pg::launch_gemm_store(w, st);
+
+    pg::StoreArgs h{};   // dHacc[t, :] (+)= sum_v dS[t, v] W^T[:, v]
+    h.A = at<__bf16>(ws, pl.dS); h.B = at<__bf16>(ws, pl.WT);
+    h.a_bytes = (uint32_t)((uint64_t)pl.t_cap * pl.vc * 2); h.b_bytes = (uint32_t)((uint64_t)pl.d * pl.vc * 2);
+    h.lda = pl.vc; h.ldb = pl.vc; h.M = pl.t_cap; h.N = d_i; h.K = kc;
+    h.tiles_m = pl.tiles_t; h.tiles_n = (d_i + 255) / 256;
+    h.C = at<float>(ws, pl.dHacc); h.ldc = d_i;
+    h.accumulate = c > 0; h.out_bf16 = 0; h.k_from_ctl = 0; h.m_from_ctl = 1; h.ctl = ctl;
+    pg::launch_gemm_store(h, st);
+  }
+
+  pg::ScatterArgs sc{at<float>(ws, pl.dHacc), at<int>(ws, pl.pos), dH, (int)pl.T, d_i, pl.is_f32};
+  pg::launch_scatter_dh(sc, st);
+  return check_launches("pg_loss_fwd_bwd");
+}
+
+}  // extern "C"

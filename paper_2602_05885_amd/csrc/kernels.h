@@ -1,0 +1,168 @@
+// Argument blocks and launchers of the device kernels (internal to the library).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace pg {
+
+struct Ctl;
+
+// ---- MFMA kernels ---------------------------------------------------------------------
+struct FwdArgs {
+  const void* W;        // [V, ldw] bf16
+  const void* Hc;       // [t_cap, ldh] bf16, compacted rows, zero padded
+  uint32_t w_bytes, h_bytes;
+  int ldw, ldh;         // elements
+  int K;                // contraction length (multiple of 64)
+  int V;
+  int tiles_v, tiles_t; // tile counts (tiles_t from t_cap; tiles beyond n_pad exit)
+  int t_cap;
+  float scale;          // log2(e) / tau
+  const int* yc;        // [t_cap] compacted token ids (-1 on padding)
+  float* zy;            // [t_cap] scaled logit of the sampled token
+  float* part_m;        // [tiles_v, t_cap] each
+  float* part_s;
+  float* part_u;
+  const Ctl* ctl;
+};
+
+struct DlogitsArgs {
+  const void* W;
+  const void* Hc;
+  uint32_t w_bytes, h_bytes;
+  int ldw, ldh;
+  int K;
+  int V;
+  int v0;               // first vocab row of this chunk
+  int vc;               // leading dimension of dS (chunk capacity, multiple of 256)
+  int tiles_v, tiles_t; // tiles of this chunk
+  int t_cap;
+  float scale;
+  const int* yc;
+  const float* lse2;    // [t_cap] log2-domain logsumexp
+  const float* coefc;   // [t_cap] coef / tau (0 on padding)
+  __bf16* dS;           // [t_cap, vc]
+  __bf16* dST;          // [vc, t_cap]
+  const Ctl* ctl;
+};
+
+struct StoreArgs {
+  const void* A;        // [M, lda] bf16
+  const void* B;        // [N, ldb] bf16
+  uint32_t a_bytes, b_bytes;
+  int lda, ldb;
+  int M, N, K;
+  int tiles_m, tiles_n;
+  void* C;              // [M, ldc] fp32 or bf16
+  int ldc;
+  int accumulate;
+  int out_bf16;
+  int k_from_ctl;       // contraction length = padded active-token count
+  int m_from_ctl;       // row extent        = padded active-token count
+  const Ctl* ctl;
+};
+
+hipError_t init_gemm_kernels();
+void launch_lmhead_fwd(const FwdArgs& a, hipStream_t s);
+void launch_lmhead_dlogits(const DlogitsArgs& a, hipStream_t s);
+void launch_gemm_store(const StoreArgs& a, hipStream_t s);
+
+// ---- row / vector kernels ----------------------------------------------------------------
+struct TrlooArgs {
+  const float* rewards;
+  const uint8_t* valid;
+  int P, K, Tmax;
+  float gamma;
+  double* returns_out;
+  double* adv_out;
+  int* group_n_out;
+};
+void launch_trloo(const TrlooArgs& a, hipStream_t s);
+
+struct PrepArgs {
+  // inputs
+  const uint8_t* mask;       // [T] loss / row mask (nullable = all ones)
+  const int* cu;             // [S+1] (nullable: no segments, every row its own weight 1)
+  int S;
+  const double* adv;
+  const int* seg_sample;
+  const float* old_logp;
+  const float* rollout_logp;
+  int T, t_cap;
+  int mismatch_mode;
+  float geo_lo, geo_hi, veto_ratio, trunc_c, norm_override;
+  // workspace
+  uint8_t* flag;             // [T]
+  float* c_tok;              // [T]
+  float* a_tok;              // [T]
+  int* rows;                 // [t_cap]
+  int* pos;                  // [T]
+  float* zy;                 // [t_cap]
+  unsigned long long* counters; // [8]
+  Ctl* ctl;
+  // per-row outputs to clear
+  float* out0; float* out1; float* out2;
+};
+void launch_prepass(const PrepArgs& a, hipStream_t s);
+
+struct GatherArgs {
+  const void* H;        // [T, d] bf16 or fp32
+  const int* y;
+  int d, t_cap;
+  int is_f32;
+  const int* rows;
+  __bf16* Hc;           // [t_cap, ldh]   bf16: ldh = d;  fp32: ldh = 3d = [hi | hi | lo]
+  __bf16* HcT;          // [d, t_cap] (nullable)
+  int* yc;
+  const Ctl* ctl;
+};
+void launch_gather(const GatherArgs& a, hipStream_t s);
+
+// fp32 head weight -> [V, 3d] bf16 = [hi | lo | hi]
+void launch_split_w(const float* W, __bf16* Wc, int64_t V, int d, hipStream_t s);
+
+struct CombineArgs {
+  int tiles_v, t_cap;
+  const float* part_m; const float* part_s; const float* part_u;
+  const float* zy;
+  const int* rows;
+  float* lse2;
+  float* logp_out; float* ent_out; float* lse_out;      // original-row indexed, nullable
+  // loss epilogue (with_loss != 0)
+  int with_loss;
+  const float* old_logp;     // original-row indexed, nullable
+  const float* c_tok; const float* a_tok;
+  float eps_lo, eps_hi, inv_tau;
+  float* coefc;              // [t_cap]
+  float* lossterm;           // [t_cap]
+  unsigned long long* counters;
+  const Ctl* ctl;
+};
+void launch_combine(const CombineArgs& a, hipStream_t s);
+
+struct FinishArgs {
+  const float* lossterm;
+  const unsigned long long* counters;
+  float* loss_out;
+  long long* counters_out;
+  const Ctl* ctl;
+};
+void launch_finish(const FinishArgs& a, hipStream_t s);
+
+// W[v0 .. v0+cols) x d  ->  WT [d, ldt] bf16 (zeros for v >= V)
+void launch_transpose_w(const void* W, int is_f32, int64_t V, int d, int v0, int cols, int ldt, __bf16* WT,
+                        hipStream_t s);
+
+struct ScatterArgs {
+  const float* acc;     // [t_cap, d]
+  const int* pos;       // [T]
+  void* dH;             // [T, d]
+  int T, d;
+  int out_f32;
+};
+void launch_scatter_dh(const ScatterArgs& a, hipStream_t s);
+
+void launch_fill_f32(float* p, size_t n, float v, hipStream_t s);
+void launch_fill_zero_bytes(void* p, size_t nbytes, hipStream_t s);   // nbytes multiple of 4
+
+}  // namespace pg

@@ -1,0 +1,284 @@
+// The three MFMA kernels of the policy-gradient head (see gemm_core.h for the tile engine).
+#include "kernels.h"
+#include "gemm_core.h"
+
+namespace pg {
+
+// 8 wavefronts as 4 (m) x 2 (n): two wavefronts per SIMD hide each other's LDS and barrier
+// latency; global->LDS loads bypass the register file.
+using GC = Cfg<4, 2, true>;
+constexpr int NTHREADS = GC::NT;
+constexpr int FM = GC::FM, FN = GC::FN;
+
+extern __shared__ __attribute__((aligned(16))) char g_smem[];
+
+// Softmax partial state in the log2 domain: t = z * log2(e) / tau,
+// m = max t, s = sum 2^(t-m), u = sum 2^(t-m) (t-m).
+__device__ __forceinline__ void merge_state(float& m, float& s, float& u, float m2, float s2, float u2) {
+  const float mm = fmaxf(m, m2);
+  const float a1 = __builtin_amdgcn_exp2f(m - mm), a2 = __builtin_amdgcn_exp2f(m2 - mm);
+  u = a1 * (u + (m - mm) * s) + a2 * (u2 + (m2 - mm) * s2);
+  s = a1 * s + a2 * s2;
+  m = mm;
+}
+
+constexpr float NEG_BIG = -1.0e30f;   // finite stand-in for -inf: keeps 0 * (t - m) finite
+
+// ------------------------------------------------------------------------------------
+// Forward: one workgroup = 256 vocab rows x 256 compacted tokens.  The logits live only in
+// the accumulators; what leaves the kernel is one (m, s, u) triple per token and vocab
+// tile, plus the scaled logit of the sampled token.
+// ------------------------------------------------------------------------------------
+__global__ __launch_bounds__(NTHREADS) void lmhead_fwd_kernel(FwdArgs a) {
+  const Ctl ctl = *a.ctl;
+  int tm, tn;
+  if (!map_tile(blockIdx.x, a.tiles_v, a.tiles_t, tm, tn)) return;
+  if (tn * BN >= ctl.n_pad) return;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / GC::WN, wn = wave % GC::WN;
+
+  TileLoader<GC> LA, LB;
+  init_loader<GC>(LA, a.W, a.w_bytes, tm * BM, a.ldw, tid);
+  init_loader<GC>(LB, a.Hc, a.h_bytes, tn * BN, a.ldh, tid);
+  f32x16 acc[FM][FN];
+  zero_acc<FM, FN>(acc);
+  mainloop<GC>(LA, LB, a.K / BK, g_smem, acc);
+
+  const int v_base = tm * BM + wm * GC::WROWS;              // first vocab row of this wave's block
+  const bool ragged = (tm * BM + BM > a.V);
+  float* red = reinterpret_cast<float*>(g_smem);      // [WM][256 tokens][3]
+
+#pragma unroll
+  for (int j = 0; j < FN; ++j) {
+    const int tok_l = wn * GC::WCOLS + j * 32 + (lane & 31);
+    const int tok = tn * BN + tok_l;
+    float mx = NEG_BIG;
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        float t = acc[i][j][r] * a.scale;
+        if (ragged && (v_base + i * 32 + acc_row(r, lane) >= a.V)) t = NEG_BIG;
+        acc[i][j][r] = t;
+        mx = fmaxf(mx, t);
+      }
+    float s = 0.f, u = 0.f;
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const float dlt = acc[i][j][r] - mx;
+        const float e = __builtin_amdgcn_exp2f(dlt);
+        s += e;
+        u = fmaf(e, dlt, u);
+      }
+    // sampled token's logit: at most one lane of the whole grid owns (tok, y[tok])
+    const int ytok = a.yc[tok];
+    const int yrel = ytok - v_base;
+    const bool mine = (yrel >= 0) && (yrel < GC::WROWS) && (ytok < a.V) && (((yrel >> 2) & 1) == (lane >> 5));
+    if (__any(mine)) {
+      float zy = 0.f;
+#pragma unroll
+      for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+          if (yrel == i * 32 + acc_row(r, lane)) zy = acc[i][j][r];
+      if (mine) a.zy[tok] = zy;
+    }
+    // the other half-wave holds the other vocab rows of the same token
+    const float m2 = __shfl_xor(mx, 32), s2 = __shfl_xor(s, 32), u2 = __shfl_xor(u, 32);
+    merge_state(mx, s, u, m2, s2, u2);
+    if (lane < 32) {
+      float* p = red + (wm * 256 + tok_l) * 3;
+      p[0] = mx; p[1] = s; p[2] = u;
+    }
+  }
+  __syncthreads();
+  if (tid < BN) {
+    const float* p0 = red + tid * 3;
+    float m = p0[0], s = p0[1], u = p0[2];
+#pragma unroll
+    for (int w = 1; w < GC::WM; ++w) {
+      const float* p1 = red + (w * 256 + tid) * 3;
+      merge_state(m, s, u, p1[0], p1[1], p1[2]);
+    }
+    const size_t o = (size_t)tm * a.t_cap + (size_t)tn * BN + tid;
+    a.part_m[o] = m; a.part_s[o] = s; a.part_u[o] = u;
+  }
+}
+
+// ------------------------------------------------------------------------------------
+// Backward recompute: the same contraction, finished with
+//   dS[t,v] = c_t * (onehot(y_t)[v] - 2^(t2 - lse2_t)),  c_t = coef_t / tau,
+// rounded to bf16 and written for one vocab chunk in both orientations
+// (dS [t_cap, vc] for dH, dS^T [vc, t_cap] for dW).
+// ------------------------------------------------------------------------------------
+
+__global__ __launch_bounds__(NTHREADS) void lmhead_dlogits_kernel(DlogitsArgs a) {
+  const Ctl ctl = *a.ctl;
+  int tm, tn;
+  if (!map_tile(blockIdx.x, a.tiles_v, a.tiles_t, tm, tn)) return;
+  if (tn * BN >= ctl.n_pad) return;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / GC::WN, wn = wave % GC::WN;
+
+  TileLoader<GC> LA, LB;
+  init_loader<GC>(LA, a.W, a.w_bytes, a.v0 + tm * BM, a.ldw, tid);
+  init_loader<GC>(LB, a.Hc, a.h_bytes, tn * BN, a.ldh, tid);
+  f32x16 acc[FM][FN];
+  zero_acc<FM, FN>(acc);
+  mainloop<GC>(LA, LB, a.K / BK, g_smem, acc);
+
+  const int v_base = a.v0 + tm * BM + wm * GC::WROWS;       // global vocab index
+  const bool ragged = (a.v0 + tm * BM + BM > a.V);
+
+#pragma unroll
+  for (int j = 0; j < FN; ++j) {
+    const int tok = tn * BN + wn * GC::WCOLS + j * 32 + (lane & 31);
+    const float c = a.coefc[tok];
+    const float l2 = a.lse2[tok];
+    const int yrel = a.yc[tok] - v_base;
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int vr = i * 32 + acc_row(r, lane);
+        const float p = __builtin_amdgcn_exp2f(fmaf(acc[i][j][r], a.scale, -l2));
+        float g = c * ((vr == yrel ? 1.f : 0.f) - p);
+        if (ragged && (v_base + vr >= a.V)) g = 0.f;
+        acc[i][j][r] = g;
+      }
+  }
+
+  // ---- orientation 1: dS[tok][v], staged as rows of 256 v ----
+  char* st = g_smem;
+#pragma unroll
+  for (int j = 0; j < FN; ++j) {
+    const int tok_l = wn * GC::WCOLS + j * 32 + (lane & 31);
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        bf16x4 pk;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) pk[e] = (__bf16)acc[i][j][q * 4 + e];
+        const int v_l = wm * GC::WROWS + i * 32 + q * 8 + ((lane >> 5) << 2);
+        *reinterpret_cast<bf16x4*>(st + tok_l * EPI_STRIDE + v_l * 2) = pk;
+      }
+  }
+  __syncthreads();
+  {
+    const int chunk = tid & 31, r0 = tid >> 5;
+    __bf16* dst = a.dS + ((size_t)tn * BN) * a.vc + (size_t)tm * BM + chunk * 8;
+#pragma unroll 4
+    for (int ps = 0; ps < 256 / (NTHREADS / 32); ++ps) {
+      const int row = r0 + ps * (NTHREADS / 32);
+      const i32x4 v = *reinterpret_cast<const i32x4*>(st + row * EPI_STRIDE + chunk * 16);
+      *reinterpret_cast<i32x4*>(dst + (size_t)row * a.vc) = v;
+    }
+  }
+  __syncthreads();
+  // ---- orientation 2: dS^T[v][tok], staged as rows of 256 tokens ----
+#pragma unroll
+  for (int j = 0; j < FN; ++j) {
+    const int tok_l = wn * GC::WCOLS + j * 32 + (lane & 31);
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int v_l = wm * GC::WROWS + i * 32 + acc_row(r, lane);
+        *reinterpret_cast<__bf16*>(st + v_l * EPI_STRIDE + tok_l * 2) = (__bf16)acc[i][j][r];
+      }
+  }
+  __syncthreads();
+  {
+    const int chunk = tid & 31, r0 = tid >> 5;
+    __bf16* dst = a.dST + ((size_t)tm * BM) * a.t_cap + (size_t)tn * BN + chunk * 8;
+#pragma unroll 4
+    for (int ps = 0; ps < 256 / (NTHREADS / 32); ++ps) {
+      const int row = r0 + ps * (NTHREADS / 32);
+      const i32x4 v = *reinterpret_cast<const i32x4*>(st + row * EPI_STRIDE + chunk * 16);
+      *reinterpret_cast<i32x4*>(dst + (size_t)row * a.t_cap) = v;
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------
+// Plain contraction with a store epilogue: C[m,n] (+)= sum_k A[m,k] B[n,k].
+// Used for dW (A = dS^T chunk, B = H^T, k = compacted tokens) and for dH
+// (A = dS chunk, B = W^T chunk, k = vocab chunk).  The extent marked by k_from_ctl /
+// m_from_ctl is the device-side padded token count.
+// ------------------------------------------------------------------------------------
+template <typename OutT>
+__device__ __forceinline__ void store_tile(const StoreArgs& a, int tm, int tn, int m_lim, f32x16 (&acc)[FM][FN]) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / GC::WN, wn = wave % GC::WN;
+  OutT* C = reinterpret_cast<OutT*>(a.C);
+#pragma unroll
+  for (int j = 0; j < FN; ++j) {
+    const int n = tn * BN + wn * GC::WCOLS + j * 32 + (lane & 31);
+    if (n >= a.N) continue;
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int m = tm * BM + wm * GC::WROWS + i * 32 + acc_row(r, lane);
+        if (m >= m_lim) continue;
+        OutT* p = C + (size_t)m * a.ldc + n;
+        float v = acc[i][j][r];
+        if (a.accumulate) v += (float)*p;
+        *p = (OutT)v;
+      }
+  }
+}
+
+__global__ __launch_bounds__(NTHREADS) void gemm_store_kernel(StoreArgs a) {
+  const Ctl ctl = *a.ctl;
+  int tm, tn;
+  if (!map_tile(blockIdx.x, a.tiles_m, a.tiles_n, tm, tn)) return;
+  const int m_lim = a.m_from_ctl ? min(a.M, ctl.n_pad) : a.M;
+  if (tm * BM >= m_lim) return;
+  const int K = a.k_from_ctl ? ctl.n_pad : a.K;
+
+  const int tid = threadIdx.x;
+  TileLoader<GC> LA, LB;
+  init_loader<GC>(LA, a.A, a.a_bytes, tm * BM, a.lda, tid);
+  init_loader<GC>(LB, a.B, a.b_bytes, tn * BN, a.ldb, tid);
+  f32x16 acc[FM][FN];
+  zero_acc<FM, FN>(acc);
+  mainloop<GC>(LA, LB, K / BK, g_smem, acc);
+  if (a.out_bf16)
+    store_tile<__bf16>(a, tm, tn, m_lim, acc);
+  else
+    store_tile<float>(a, tm, tn, m_lim, acc);
+}
+
+// ---- host-side launchers -------------------------------------------------------------
+static hipError_t ensure_lds(const void* fn) {
+  return hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, GEMM_LDS_BYTES);
+}
+
+hipError_t init_gemm_kernels() {
+  hipError_t e;
+  if ((e = ensure_lds(reinterpret_cast<const void*>(lmhead_fwd_kernel))) != hipSuccess) return e;
+  if ((e = ensure_lds(reinterpret_cast<const void*>(lmhead_dlogits_kernel))) != hipSuccess) return e;
+  if ((e = ensure_lds(reinterpret_cast<const void*>(gemm_store_kernel))) != hipSuccess) return e;
+  return hipSuccess;
+}
+
+void launch_lmhead_fwd(const FwdArgs& a, hipStream_t s) {
+  const int grid = grid_for_tiles(a.tiles_v, a.tiles_t);
+  hipLaunchKernelGGL(lmhead_fwd_kernel, dim3(grid), dim3(NTHREADS), GEMM_LDS_BYTES, s, a);
+}
+void launch_lmhead_dlogits(const DlogitsArgs& a, hipStream_t s) {
+  const int grid = grid_for_tiles(a.tiles_v, a.tiles_t);
+  hipLaunchKernelGGL(lmhead_dlogits_kernel, dim3(grid), dim3(NTHREADS), GEMM_LDS_BYTES, s, a);
+}
+void launch_gemm_store(const StoreArgs& a, hipStream_t s) {
+  const int grid = grid_for_tiles(a.tiles_m, a.tiles_n);
+  hipLaunchKernelGGL(gemm_store_kernel, dim3(grid), dim3(NTHREADS), GEMM_LDS_BYTES, s, a);
+}
+
+}  // namespace pg

@@ -1,0 +1,376 @@
+// Vector / row kernels around the MFMA kernels: TRLOO advantages, mismatch pre-pass, row
+// compaction, operand staging, the per-row softmax combine with the surrogate epilogue,
+// and the final scatter of dH.  None of them is bandwidth- or flop-significant next to the
+// contractions; they are written for determinism (fixed reduction orders, integer atomics
+// only) and to keep the host out of the loop (no synchronisation, counts stay on device).
+#include "kernels.h"
+#include "gemm_core.h"
+
+namespace pg {
+
+// ------------------------------------------------------------------ fills
+__global__ void fill_f32_kernel(float* p, size_t n, float v) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (; i < n; i += stride) p[i] = v;
+}
+void launch_fill_f32(float* p, size_t n, float v, hipStream_t s) {
+  if (!p || n == 0) return;
+  const int grid = (int)((n + 255) / 256 < 4096 ? (n + 255) / 256 : 4096);
+  hipLaunchKernelGGL(fill_f32_kernel, dim3(grid), dim3(256), 0, s, p, n, v);
+}
+void launch_fill_zero_bytes(void* p, size_t nbytes, hipStream_t s) {
+  launch_fill_f32(reinterpret_cast<float*>(p), nbytes / 4, 0.f, s);
+}
+
+// ------------------------------------------------------------------ TRLOO (Sec. 4.2, Eq. 2 and 5)
+// One thread per (prompt, turn) group; fp64 throughout.  Returns are evaluated by Horner's
+// rule from the last turn backwards; the leave-one-out mean is (sum - own) / (N - 1).
+__device__ __forceinline__ double turn_return(const float* r, int t, int Tmax, double gamma) {
+  double g = 0.0;
+  for (int tp = Tmax - 1; tp >= t; --tp) g = (double)r[tp] + gamma * g;
+  return g;
+}
+
+__global__ void trloo_kernel(TrlooArgs a) {
+  const int g = blockIdx.x * blockDim.x + threadIdx.x;
+  if (g >= a.P * a.Tmax) return;
+  const int p = g / a.Tmax, t = g % a.Tmax;
+  const double gamma = (double)a.gamma;
+  double sum = 0.0;
+  int n = 0;
+  for (int k = 0; k < a.K; ++k) {
+    const size_t base = ((size_t)p * a.K + k) * a.Tmax;
+    const double G = turn_return(a.rewards + base, t, a.Tmax, gamma);
+    if (a.returns_out) a.returns_out[base + t] = G;
+    if (a.valid[base + t]) { sum += G; ++n; }
+  }
+  if (a.group_n_out) a.group_n_out[g] = n;
+  for (int k = 0; k < a.K; ++k) {
+    const size_t base = ((size_t)p * a.K + k) * a.Tmax;
+    double A = 0.0;
+    if (n >= 2 && a.valid[base + t]) {
+      const double G = turn_return(a.rewards + base, t, a.Tmax, gamma);
+      A = G - (sum - G) / (double)(n - 1);
+    }
+    a.adv_out[base + t] = A;
+  }
+}
+void launch_trloo(const TrlooArgs& a, hipStream_t s) {
+  const int n = a.P * a.Tmax;
+  hipLaunchKernelGGL(trloo_kernel, dim3((n + 63) / 64), dim3(64), 0, s, a);
+}
+
+// ------------------------------------------------------------------ pre-pass
+__global__ void prep_init_kernel(PrepArgs a) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < 8) a.counters[i] = 0ull;
+  if (i < a.t_cap) a.zy[i] = 0.f;
+  if (i < a.T) {
+    if (a.out0) a.out0[i] = 0.f;
+    if (a.out1) a.out1[i] = 0.f;
+    if (a.out2) a.out2[i] = 0.f;
+    if (a.cu) {
+      a.flag[i] = 0;
+    } else {
+      a.flag[i] = a.mask ? (a.mask[i] != 0) : 1;
+      a.c_tok[i] = 1.f;
+      a.a_tok[i] = 0.f;
+    }
+  }
+}
+
+// One workgroup per segment (= one training sample): Sec. 5.1's geometric-mean ratio and
+// token veto over the sample's loss tokens, decided in fp64, then per-row weights.
+__global__ __launch_bounds__(256) void prep_segment_kernel(PrepArgs a) {
+  __shared__ double sh_sum[256];
+  __shared__ double sh_min[256];
+  __shared__ int sh_n[256];
+  __shared__ int sh_keep;
+  const int s = blockIdx.x, tid = threadIdx.x;
+  int lo = a.cu[s], hi = a.cu[s + 1];
+  lo = max(lo, 0);
+  hi = min(hi, a.T);
+  const bool mm = a.mismatch_mode != 0;
+  double sum = 0.0, mn = 1.0e300;
+  int n = 0;
+  for (int t = lo + tid; t < hi; t += 256) {
+    if (a.mask[t]) {
+      ++n;
+      if (mm) {
+        const double dl = (double)a.old_logp[t] - (double)a.rollout_logp[t];
+        sum += dl;
+        mn = fmin(mn, dl);
+      }
+    }
+  }
+  sh_sum[tid] = sum; sh_min[tid] = mn; sh_n[tid] = n;
+  __syncthreads();
+  for (int w = 128; w > 0; w >>= 1) {
+    if (tid < w) {
+      sh_sum[tid] += sh_sum[tid + w];
+      sh_min[tid] = fmin(sh_min[tid], sh_min[tid + w]);
+      sh_n[tid] += sh_n[tid + w];
+    }
+    __syncthreads();
+  }
+  if (tid == 0) {
+    int keep = 1;
+    const int nn = sh_n[0];
+    if (nn > 0) {
+      atomicAdd(&a.counters[6], (unsigned long long)nn);
+      if (mm) {
+        const bool vetoed = (a.veto_ratio > 0.f) && (exp(sh_min[0]) < (double)a.veto_ratio);
+        if (vetoed) { atomicAdd(&a.counters[4], 1ull); keep = 0; }
+        if (a.mismatch_mode == 1) {
+          const double w = exp(sh_sum[0] / (double)nn);
+          const bool inside = ((double)a.geo_lo <= w) && (w <= (double)a.geo_hi);
+          if (!inside) { atomicAdd(&a.counters[3], 1ull); keep = 0; }
+        }
+      }
+    }
+    sh_keep = keep;
+  }
+  __syncthreads();
+  const int keep = sh_keep;
+  const float A = (float)a.adv[a.seg_sample ? a.seg_sample[s] : s];
+  unsigned long long ntr = 0;
+  for (int t = lo + tid; t < hi; t += 256) {
+    const bool act = a.mask[t] && keep;
+    float c = 0.f;
+    if (act) {
+      c = 1.f;
+      if (a.mismatch_mode == 2) {
+        const double ratio = exp((double)a.old_logp[t] - (double)a.rollout_logp[t]);
+        if (ratio > (double)a.trunc_c) { ++ntr; c = a.trunc_c; } else { c = (float)ratio; }
+      }
+    }
+    a.flag[t] = act;
+    a.c_tok[t] = c;
+    a.a_tok[t] = A;
+  }
+  if (ntr) atomicAdd(&a.counters[5], ntr);
+}
+
+// Single workgroup: exclusive scan of the active flags -> compacted row list, inverse map,
+// counts and the loss normaliser.
+__global__ __launch_bounds__(1024) void prep_compact_kernel(PrepArgs a) {
+  __shared__ int sh[1024];
+  const int tid = threadIdx.x;
+  const int chunk = (a.T + 1023) / 1024;
+  const int lo = min(a.T, tid * chunk), hi = min(a.T, lo + chunk);
+  int cnt = 0;
+  for (int t = lo; t < hi; ++t) cnt += a.flag[t] ? 1 : 0;
+  sh[tid] = cnt;
+  __syncthreads();
+  for (int off = 1; off < 1024; off <<= 1) {
+    const int v = (tid >= off) ? sh[tid - off] : 0;
+    __syncthreads();
+    sh[tid] += v;
+    __syncthreads();
+  }
+  int idx = sh[tid] - cnt;
+  for (int t = lo; t < hi; ++t) {
+    if (a.flag[t]) { a.rows[idx] = t; a.pos[t] = idx; ++idx; } else { a.pos[t] = -1; }
+  }
+  if (tid == 1023) {
+    const int total = sh[1023];
+    a.ctl->n_active = total;
+    a.ctl->n_pad = (total + 255) / 256 * 256;
+    a.ctl->norm = a.norm_override > 0.f ? a.norm_override : (float)max(total, 1);
+    a.ctl->pad_ = 0;
+    a.counters[0] = (unsigned long long)total;
+  }
+}
+
+void launch_prepass(const PrepArgs& a, hipStream_t s) {
+  const int n = a.t_cap > 8 ? a.t_cap : 8;
+  hipLaunchKernelGGL(prep_init_kernel, dim3((n + 255) / 256), dim3(256), 0, s, a);
+  if (a.cu && a.S > 0) hipLaunchKernelGGL(prep_segment_kernel, dim3(a.S), dim3(256), 0, s, a);
+  hipLaunchKernelGGL(prep_compact_kernel, dim3(1), dim3(1024), 0, s, a);
+}
+
+// ------------------------------------------------------------------ operand staging
+__device__ __forceinline__ void split_bf16(float x, __bf16& hi, __bf16& lo) {
+  hi = (__bf16)x;
+  lo = (__bf16)(x - (float)hi);
+}
+
+// 64 compacted rows x 64 columns per workgroup: copies (or splits) H rows into the compacted,
+// zero-padded operand and writes its transpose for the dW contraction.
+__global__ __launch_bounds__(256) void gather_kernel(GatherArgs a) {
+  __shared__ __bf16 tile[64][66];
+  const Ctl ctl = *a.ctl;
+  const int i0 = blockIdx.x * 64, j0 = blockIdx.y * 64;
+  if (i0 >= ctl.n_pad) return;
+  const int tid = threadIdx.x;
+  if (blockIdx.y == 0 && tid < 64) {
+    const int i = i0 + tid;
+    a.yc[i] = (i < ctl.n_active) ? a.y[a.rows[i]] : -1;
+  }
+  const int ldh = a.is_f32 ? 3 * a.d : a.d;
+  const int r = tid >> 2, c0 = (tid & 3) * 16;
+  const int i = i0 + r;
+  const bool live = i < ctl.n_active;
+  const size_t src = live ? (size_t)a.rows[i] * a.d + j0 + c0 : 0;
+#pragma unroll
+  for (int e = 0; e < 16; ++e) {
+    __bf16 hi = (__bf16)0.f, lo = (__bf16)0.f;
+    if (live) {
+      if (a.is_f32) split_bf16(reinterpret_cast<const float*>(a.H)[src + e], hi, lo);
+      else hi = reinterpret_cast<const __bf16*>(a.H)[src + e];
+    }
+    const size_t o = (size_t)i * ldh + j0 + c0 + e;
+    a.Hc[o] = hi;
+    if (a.is_f32) { a.Hc[o + a.d] = hi; a.Hc[o + 2 * a.d] = lo; }
+    tile[r][c0 + e] = hi;
+  }
+  if (!a.HcT) return;
+  __syncthreads();
+  const int j = tid >> 2;
+#pragma unroll
+  for (int e = 0; e < 16; ++e) a.HcT[(size_t)(j0 + j) * a.t_cap + i0 + c0 + e] = tile[c0 + e][j];
+}
+void launch_gather(const GatherArgs& a, hipStream_t s) {
+  hipLaunchKernelGGL(gather_kernel, dim3(a.t_cap / 64, a.d / 64), dim3(256), 0, s, a);
+}
+
+__global__ void split_w_kernel(const float* W, __bf16* Wc, size_t n, int d) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (; i < n; i += stride) {
+    const size_t v = i / d, k = i % d;
+    __bf16 hi, lo;
+    split_bf16(W[i], hi, lo);
+    __bf16* o = Wc + v * 3 * (size_t)d + k;
+    o[0] = hi; o[d] = lo; o[2 * (size_t)d] = hi;
+  }
+}
+void launch_split_w(const float* W, __bf16* Wc, int64_t V, int d, hipStream_t s) {
+  const size_t n = (size_t)V * d;
+  const int grid = (int)((n + 255) / 256 < 65536 ? (n + 255) / 256 : 65536);
+  hipLaunchKernelGGL(split_w_kernel, dim3(grid), dim3(256), 0, s, W, Wc, n, d);
+}
+
+// W rows [v0, v0+cols) -> WT[j][v - v0] (bf16; fp32 weights are rounded), zeros for v >= V.
+__global__ __launch_bounds__(256) void transpose_w_kernel(const void* W, int is_f32, long long V, int d, int v0,
+                                                          int ldt, __bf16* WT) {
+  __shared__ __bf16 tile[64][66];
+  const int vt = blockIdx.x * 64, j0 = blockIdx.y * 64;
+  const int tid = threadIdx.x;
+  const int r = tid >> 2, c0 = (tid & 3) * 16;
+  const long long v = (long long)v0 + vt + r;
+#pragma unroll
+  for (int e = 0; e < 16; ++e) {
+    __bf16 x = (__bf16)0.f;
+    if (v < V) {
+      const size_t o = (size_t)v * d + j0 + c0 + e;
+      x = is_f32 ? (__bf16)reinterpret_cast<const float*>(W)[o] : reinterpret_cast<const __bf16*>(W)[o];
+    }
+    tile[r][c0 + e] = x;
+  }
+  __syncthreads();
+  const int j = tid >> 2;
+#pragma unroll
+  for (int e = 0; e < 16; ++e) WT[(size_t)(j0 + j) * ldt + vt + c0 + e] = tile[c0 + e][j];
+}
+void launch_transpose_w(const void* W, int is_f32, int64_t V, int d, int v0, int cols, int ldt, __bf16* WT,
+                        hipStream_t s) {
+  hipLaunchKernelGGL(transpose_w_kernel, dim3(cols / 64, d / 64), dim3(256), 0, s, W, is_f32, (long long)V, d, v0,
+                     ldt, WT);
+}
+
+// ------------------------------------------------------------------ combine + surrogate
+// One thread per compacted row: merges the per-vocab-tile softmax partials (two sweeps: the
+// global max first, then the rescaled sums), emits log-prob / entropy / logsumexp, and for
+// the loss call evaluates the clipped surrogate and the coefficient that scales
+// (onehot - softmax) in the backward.
+__global__ __launch_bounds__(256) void combine_kernel(CombineArgs a) {
+  const Ctl ctl = *a.ctl;
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= ctl.n_pad) return;
+  float M = a.part_m[i];
+  for (int k = 1; k < a.tiles_v; ++k) M = fmaxf(M, a.part_m[(size_t)k * a.t_cap + i]);
+  float s = 0.f, u = 0.f;
+  for (int k = 0; k < a.tiles_v; ++k) {
+    const size_t o = (size_t)k * a.t_cap + i;
+    const float dm = a.part_m[o] - M;
+    const float w = __builtin_amdgcn_exp2f(dm);
+    const float sk = a.part_s[o];
+    s = fmaf(w, sk, s);
+    u = fmaf(w, fmaf(dm, sk, a.part_u[o]), u);
+  }
+  const float log2s = __builtin_amdgcn_logf(s);     // v_log_f32: log2
+  const float lse2 = M + log2s;
+  a.lse2[i] = lse2;
+  const float LN2 = 0.693147180559945309f;
+  if (i >= ctl.n_active) {
+    if (a.with_loss) { a.coefc[i] = 0.f; a.lossterm[i] = 0.f; }
+    return;
+  }
+  const int row = a.rows[i];
+  const float logp = (a.zy[i] - lse2) * LN2;
+  if (a.logp_out) a.logp_out[row] = logp;
+  if (a.ent_out) a.ent_out[row] = (log2s - u / s) * LN2;
+  if (a.lse_out) a.lse_out[row] = lse2 * LN2;
+  if (!a.with_loss) return;
+  const float A = a.a_tok[row], c = a.c_tok[row];
+  const float r = a.old_logp ? expf(logp - a.old_logp[row]) : 1.f;
+  const float lo = 1.f - a.eps_lo, hi = 1.f + a.eps_hi;
+  const float rc = fminf(fmaxf(r, lo), hi);
+  const float l = -fminf(r * A, rc * A);
+  const bool flows = (A >= 0.f && r <= hi) || (A < 0.f && r >= lo);
+  const float g = flows ? -A * r : 0.f;
+  if (A >= 0.f && r > hi) atomicAdd(&a.counters[1], 1ull);
+  if (A < 0.f && r < lo) atomicAdd(&a.counters[2], 1ull);
+  a.coefc[i] = c * g / ctl.norm * a.inv_tau;
+  a.lossterm[i] = c * l;
+}
+void launch_combine(const CombineArgs& a, hipStream_t s) {
+  hipLaunchKernelGGL(combine_kernel, dim3(a.t_cap / 256), dim3(256), 0, s, a);
+}
+
+// Single workgroup, fixed order, fp64: loss = (sum_t c_t l_t) / norm; publishes the counters.
+__global__ __launch_bounds__(1024) void finish_kernel(FinishArgs a) {
+  __shared__ double sh[1024];
+  const Ctl ctl = *a.ctl;
+  const int tid = threadIdx.x;
+  double acc = 0.0;
+  for (int i = tid; i < ctl.n_active; i += 1024) acc += (double)a.lossterm[i];
+  sh[tid] = acc;
+  __syncthreads();
+  for (int w = 512; w > 0; w >>= 1) {
+    if (tid < w) sh[tid] += sh[tid + w];
+    __syncthreads();
+  }
+  if (tid == 0 && a.loss_out) *a.loss_out = (float)(sh[0] / (double)ctl.norm);
+  if (tid < 8 && a.counters_out) a.counters_out[tid] = (long long)a.counters[tid];
+}
+void launch_finish(const FinishArgs& a, hipStream_t s) {
+  hipLaunchKernelGGL(finish_kernel, dim3(1), dim3(1024), 0, s, a);
+}
+
+// ------------------------------------------------------------------ dH scatter
+// dH[t,:] = accumulated row of its compacted position, or zeros for rows that are not active.
+__global__ __launch_bounds__(256) void scatter_dh_kernel(ScatterArgs a) {
+  const int t = blockIdx.x;
+  const int p = a.pos[t];
+  const float* src = a.acc + (size_t)(p < 0 ? 0 : p) * a.d;
+  for (int j = threadIdx.x * 4; j < a.d; j += 256 * 4) {
+    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (p >= 0) v = *reinterpret_cast<const float4*>(src + j);
+    if (a.out_f32) {
+      *reinterpret_cast<float4*>(reinterpret_cast<float*>(a.dH) + (size_t)t * a.d + j) = v;
+    } else {
+      bf16x4 o;
+      o[0] = (__bf16)v.x; o[1] = (__bf16)v.y; o[2] = (__bf16)v.z; o[3] = (__bf16)v.w;
+      *reinterpret_cast<bf16x4*>(reinterpret_cast<__bf16*>(a.dH) + (size_t)t * a.d + j) = o;
+    }
+  }
+}
+void launch_scatter_dh(const ScatterArgs& a, hipStream_t s) {
+  if (a.T <= 0) return;
+  hipLaunchKernelGGL(scatter_dh_kernel, dim3(a.T), dim3(256), 0, s, a);
+}
+
+}  // namespace pg

@@ -1,0 +1,78 @@
+"""The C-ABI library loads, exports what the header declares, and validates arguments on the host.
+No kernel is launched here (no GPU needed): every call below fails validation before any HIP call."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2602_05885_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_functions():
+    src = open(os.path.join(ROOT, "include", "pg_head.h")).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(\w+)\s*\([^;{]*\)\s*;", src)))
+
+
+def test_header_symbols_are_exported():
+    names = _declared_functions()
+    assert set(names) == set(B.EXPORTS), names
+    lib = C.CDLL(B.LIB_PATH)
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_params_struct_layout_matches_header():
+    src = open(os.path.join(ROOT, "include", "pg_head.h")).read()
+    body = re.search(r"typedef struct pg_params \{(.*?)\} pg_params;", src, flags=re.S).group(1)
+    body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
+    fields = re.findall(r"(int32_t|float)\s+(\w+)\s*;", body)
+    ctype = {"int32_t": C.c_int32, "float": C.c_float}
+    assert [(n, ctype[t]) for t, n in fields] == list(B.PgParams._fields_)
+
+
+def test_workspace_query_and_shape_errors():
+    P = B.Params()
+    small = B.pg_workspace_bytes(1024, 64, 1000, 32, P, B.CALL_LOSS_FWD_BWD)
+    fwd = B.pg_workspace_bytes(1024, 64, 1000, 0, P, B.CALL_LOGPROB_FWD)
+    assert 0 < fwd < small
+    big = B.pg_workspace_bytes(43776, 5120, 151936, 60, P, B.CALL_LOSS_FWD_BWD)
+    assert 2 << 30 < big < 16 << 30
+    assert B.pg_workspace_bytes(1024, 100, 1000, 1, P, 1) == 0 and "multiple of 64" in B.pg_last_error()
+    assert B.pg_workspace_bytes(-1, 64, 1000, 1, P, 1) == 0
+    assert B.pg_workspace_bytes(1024, 64, 1000, 1, B.Params(temperature=0.0), 1) == 0
+    assert B.pg_workspace_bytes(1024, 64, 1000, 1, B.Params(mismatch_mode=7), 1) == 0
+    assert B.pg_workspace_bytes(1 << 20, 5120, 151936, 1, P, 0) == 0 and "4 GiB" in B.pg_last_error()
+    assert B.pg_workspace_bytes(1024, 64, 1000, 1, P, 5) == 0
+    assert B.pg_workspace_bytes(0, 64, 1000, 0, P, 1) > 0          # empty microbatch is legal
+
+
+def test_invalid_arguments_return_error_codes():
+    lib = B.lib()
+    p = B.Params().c_struct()
+    one = C.c_void_p(16)      # never dereferenced: validation fails first
+    rc = lib.trloo_advantage(None, one, 1, 1, 1, 1.0, None, one, None, None)
+    assert rc == -1 and "NULL" in B.pg_last_error()
+    rc = lib.trloo_advantage(one, one, 0, 1, 1, 1.0, None, one, None, None)
+    assert rc == -1
+    rc = lib.pg_logprob_fwd(None, one, one, None, 8, 64, 100, C.byref(p), one, None, None, one, 1 << 30, None)
+    assert rc == -1
+    rc = lib.pg_logprob_fwd(one, one, one, None, 8, 64, 100, C.byref(p), one, None, None, one, 16, None)
+    assert rc == -3 and "needed" in B.pg_last_error()
+    rc = lib.pg_logprob_fwd(C.c_void_p(8), one, one, None, 8, 64, 100, C.byref(p), one, None, None, one, 1 << 30, None)
+    assert rc == -1 and "aligned" in B.pg_last_error()
+    rc = lib.pg_logprob_fwd(one, one, one, None, 8, 72, 100, C.byref(p), one, None, None, one, 1 << 30, None)
+    assert rc == -2
+    pm = B.Params(mismatch_mode=1).c_struct()
+    rc = lib.pg_loss_fwd_bwd(one, one, one, one, one, 1, one, None, one, None, 8, 64, 100, C.byref(pm), one, one, one,
+                             None, None, None, one, 1 << 30, None)
+    assert rc == -1 and "rollout_logp" in B.pg_last_error()
+    rc = lib.pg_loss_fwd_bwd(one, one, one, one, one, 0, one, None, None, None, 8, 64, 100, C.byref(p), one, one, one,
+                             None, None, None, one, 1 << 30, None)
+    assert rc == -1
+    rc = lib.pg_loss_fwd_bwd(one, one, one, one, one, 1, one, None, None, None, 8, 64, 100, None, one, one, one,
+                             None, None, None, one, 1 << 30, None)
+    assert rc == -1 and "params" in B.pg_last_error()
