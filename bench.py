@@ -1,0 +1,171 @@
+#!/usr/bin/env python3
+"""Benchmark of the policy-gradient head on one MI355X.
+
+A step is one pass of the whole path over one synthetic packed microbatch that is already
+resident in device memory: trloo_advantage (returns + leave-one-out advantages of the whole
+rollout batch) followed by pg_loss_fwd_bwd (mismatch pre-pass, fused LM-head forward, clipped
+surrogate, backward to dH and dW).  The workload is the Qwen3-14B head shape (hidden 5120,
+vocab 151936) with 32768 loss tokens: entry [2] of the benchmark's configuration list.
+
+Prints ONE JSON line (see README / DESIGN for the fields).  The oracle is imported only for the
+`cpu_baseline` leg, which times it on a bounded row sample of the same shape.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA peak (published)
+
+
+def cpu_baseline(spec, rows: int):
+    """Times the fp64 oracle (as it stands) on `rows` active rows at the full d and V."""
+    import numpy as np
+    import torch
+    from oracle import pg_oracle as O
+    from paper_2602_05885_amd import synth
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    H, W, y = synth.make_head(rows, spec.d, spec.V, spec.dtype, spec.seed + 1000, "cpu", spec.unit_rms)
+    Hn, Wn, yn = H.double().numpy(), W.double().numpy(), y.numpy()
+    del H, W
+    n_seg = 4
+    cu = np.linspace(0, rows, n_seg + 1).astype(np.int32)
+    mask = np.ones(rows, np.uint8)
+    R = np.random.default_rng(0).random((2, 2, 1)).astype(np.float32)
+    t0 = time.perf_counter()
+    _, A, _ = O.trloo_advantage(R, np.ones_like(R, dtype=np.uint8), 1.0)
+    out = O.pg_loss_fwd_bwd(Hn, Wn, yn, mask, cu, A.reshape(-1), None, None, O.Params(temperature=spec.temperature))
+    dt = time.perf_counter() - t0
+    assert np.isfinite(out["loss"])
+    return {"value": rows / dt, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"{rows} active rows at d={spec.d}, V={spec.V}, fp64 numpy, fwd+bwd, {dt:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=2, help="index into the workload list (default: 14B head, 32k loss tokens)")
+    ap.add_argument("--mismatch-mode", type=int, default=2)
+    ap.add_argument("--cpu-rows", type=int, default=2048, help="rows of the oracle's timed sample (0 = skip)")
+    ap.add_argument("--scale-rows", type=float, default=1.0, help="shrink the packed microbatch (debugging)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only; --gpus must be 1 "
+              "(the path shards by token rows; no multi-GPU figure is produced)", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2602_05885_amd import binding as B
+    from paper_2602_05885_amd import synth
+
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    spec = synth.SPECS[args.config]
+    batch = synth.make_batch(spec, args.scale_rows)
+    T, d, V, S = batch.T, spec.d, spec.V, batch.S
+    H, W, y = synth.make_head(T, d, V, spec.dtype, spec.seed, dev, spec.unit_rms)
+    loss_mask = torch.from_numpy(batch.loss_mask).to(dev)
+    cu = torch.from_numpy(batch.cu_seqlens).to(dev)
+    seg_sample = torch.from_numpy(batch.seg_sample).to(dev)
+    rewards = torch.from_numpy(batch.rewards).to(dev)
+    valid = torch.from_numpy(batch.valid).to(dev)
+    n_loss = int(batch.loss_mask.sum())
+
+    dtype_id = 0 if spec.dtype == "bf16" else 1
+    prm = B.Params(dtype=dtype_id, temperature=spec.temperature, mismatch_mode=args.mismatch_mode)
+
+    # old-policy log-probs come from the forward call of the library itself (the RL step's
+    # "recompute" stage); the rollout engine's log-probs are those plus noise and outliers.
+    ws_f = B.alloc_workspace(T, d, V, 0, prm, B.CALL_LOGPROB_FWD, dev)
+    old_logp, _, _ = B.pg_logprob_fwd(H, W, y, loss_mask, prm, ws_f, want_entropy=False, want_lse=False)
+    torch.cuda.synchronize()
+    del ws_f
+    rollout_logp = synth.perturb_logp(old_logp, spec.logp_noise, spec.outlier_frac, spec.seed + 1)
+    if args.mismatch_mode == 0:
+        rollout_logp = None
+
+    ws = B.alloc_workspace(T, d, V, S, prm, B.CALL_LOSS_FWD_BWD, dev)
+    dW = torch.empty((V, d), dtype=torch.float32, device=dev)
+    outbuf = (torch.empty(1, dtype=torch.float32, device=dev), torch.empty_like(H),
+              torch.empty(T, dtype=torch.float32, device=dev), torch.empty(T, dtype=torch.float32, device=dev),
+              torch.empty(8, dtype=torch.int64, device=dev))
+
+    def step():
+        adv, _, _ = B.trloo_advantage(rewards, valid, 1.0, want_returns=False, want_group_n=False)
+        return B.pg_loss_fwd_bwd(H, W, y, loss_mask, cu, adv.reshape(-1), seg_sample, old_logp, rollout_logp, prm, ws,
+                                 dW=dW, out=outbuf)
+
+    for _ in range(args.warmup):
+        out = step()
+    torch.cuda.synchronize()
+    B.pg_profile_enable(True, 64 * max(args.steps, 1))
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        out = step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    prof = B.pg_profile_read()
+    B.pg_profile_enable(False)
+
+    counters = out["counters"].cpu().numpy()
+    n_active = int(counters[0])
+    loss = float(out["loss"][0])
+    assert loss == loss, "loss is NaN"
+    ms_step = dt / args.steps * 1e3
+    tokens_per_s = n_active * args.steps / dt
+
+    # ---- roofline of the dominant kernel class (dW and dH contractions) ----
+    flop_token = 2.0 * d * V                                  # one contraction, per active token
+    per_step_flop = {"fwd": flop_token * n_active, "dlogits": flop_token * n_active, "grad": 2 * flop_token * n_active}
+    kern = {}
+    for k, (ms, n) in prof.items():
+        if n:
+            kern[k] = {"launches_per_step": n / args.steps, "ms_per_step": ms / args.steps,
+                       "avg_launch_ms": ms / n,
+                       "tflops": per_step_flop[k] * args.steps / (ms * 1e-3) / 1e12}
+    dom = max(kern, key=lambda k: kern[k]["ms_per_step"])
+    achieved = kern[dom]["tflops"]
+    roofline = {"bound": "mfma", "kernel": {"fwd": "lmhead_fwd_kernel", "dlogits": "lmhead_dlogits_kernel",
+                                            "grad": "gemm_store_kernel"}[dom],
+                "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
+                "traffic": None,
+                "flops_per_launch": per_step_flop[dom] / kern[dom]["launches_per_step"],
+                "avg_launch_ms": kern[dom]["avg_launch_ms"]}
+    executed = 8.0 * d * V * n_active / (ms_step * 1e-3) / 1e12   # logits twice, dH, dW
+    useful = 6.0 * d * V * n_active / (ms_step * 1e-3) / 1e12
+
+    cpu = cpu_baseline(spec, args.cpu_rows) if args.cpu_rows > 0 else None
+
+    line = {
+        "metric": "loss fwd+bwd tokens/sec at 14B shape (h5120,V151936); % bf16 MFMA peak",
+        "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if dtype_id == 0 else "f32", "data": "synthetic",
+        "config": {"workload": f"configs[{args.config}] {spec.name}: d={d}, V={V}, {batch.P}x{batch.K}x{batch.Tmax} rollout batch, "
+                               f"packed microbatch of {S} segments, {T} rows, {n_loss} loss tokens",
+                   "loss_tokens": n_loss, "active_tokens": n_active, "packed_rows": T, "segments": S,
+                   "mismatch_mode": args.mismatch_mode, "temperature": spec.temperature,
+                   "dW": "fp32 overwrite", "step": "trloo_advantage + pg_loss_fwd_bwd"},
+        "pct_mfma_peak_executed_8dV": 100.0 * executed / PEAK_BF16_TFLOPS,
+        "pct_mfma_peak_useful_6dV": 100.0 * useful / PEAK_BF16_TFLOPS,
+        "loss": loss, "counters": {n: int(c) for n, c in zip(B.COUNTER_NAMES, counters)},
+        "kernels": kern, "roofline": roofline, "cpu_baseline": cpu,
+    }
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

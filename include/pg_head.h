@@ -154,6 +154,21 @@ int32_t pg_loss_fwd_bwd(const void* H, const void* W, const int32_t* y, const ui
                         void* dH, void* dW, float* logp_out, float* entropy_out, int64_t* counters_out,
                         void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * Measurement hooks (host-side state, not thread-safe; the only calls that create HIP events
+ * or wait on the device).  pg_profile_enable(1, n) creates a pool for n kernel launches; from
+ * then on each launch of the MFMA kernels is bracketed by two events on the caller's stream.
+ * pg_profile_read waits for the recorded events, returns the summed durations in milliseconds
+ * and the launch counts per kernel class (host arrays of PG_KERNEL_CLASSES entries), and
+ * empties the pool.  pg_profile_enable(0, 0) releases the events.
+ */
+#define PG_KERNEL_FWD 0      /* logits + online softmax statistics               */
+#define PG_KERNEL_DLOGITS 1  /* logits recompute + dS in both orientations       */
+#define PG_KERNEL_GRAD 2     /* dW = dS^T H and dH = dS W                        */
+#define PG_KERNEL_CLASSES 3
+int32_t pg_profile_enable(int32_t on, int32_t max_launches);
+int32_t pg_profile_read(double* h_ms, int64_t* h_launches);
+
 #ifdef __cplusplus
 }
 #endif

@@ -21,7 +21,9 @@ CALL_LOGPROB_FWD = 0
 CALL_LOSS_FWD_BWD = 1
 COUNTER_NAMES = ("active", "clip_hi", "clip_lo", "seg_geo", "seg_veto", "truncated", "loss_tokens", "reserved")
 
-EXPORTS = ("pg_last_error", "pg_workspace_bytes", "trloo_advantage", "pg_logprob_fwd", "pg_loss_fwd_bwd")
+EXPORTS = ("pg_last_error", "pg_workspace_bytes", "trloo_advantage", "pg_logprob_fwd", "pg_loss_fwd_bwd",
+           "pg_profile_enable", "pg_profile_read")
+KERNEL_CLASSES = ("fwd", "dlogits", "grad")
 
 
 class PgParams(C.Structure):
@@ -85,6 +87,10 @@ def lib() -> C.CDLL:
                                       C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int64,
                                       C.c_int64, C.POINTER(PgParams), C.c_void_p, C.c_void_p, C.c_void_p,
                                       C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.pg_profile_enable.restype = C.c_int32
+        L.pg_profile_enable.argtypes = [C.c_int32, C.c_int32]
+        L.pg_profile_read.restype = C.c_int32
+        L.pg_profile_read.argtypes = [C.POINTER(C.c_double), C.POINTER(C.c_int64)]
         _lib = L
     return _lib
 
@@ -110,6 +116,18 @@ def _check(rc: int):
 
 def pg_last_error() -> str:
     return lib().pg_last_error().decode()
+
+
+def pg_profile_enable(on: bool, max_launches: int = 0) -> None:
+    _check(lib().pg_profile_enable(1 if on else 0, max_launches))
+
+
+def pg_profile_read():
+    """Returns {class: (total_ms, launches)} for the launches recorded since the last read."""
+    ms = (C.c_double * len(KERNEL_CLASSES))()
+    n = (C.c_int64 * len(KERNEL_CLASSES))()
+    _check(lib().pg_profile_read(ms, n))
+    return {k: (float(ms[i]), int(n[i])) for i, k in enumerate(KERNEL_CLASSES)}
 
 
 def pg_workspace_bytes(T: int, d: int, V: int, S: int, params: Params, which_call: int) -> int:

@@ -7,6 +7,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <vector>
 
 #include "../../include/pg_head.h"
 #include "gemm_core.h"
@@ -148,6 +149,31 @@ int32_t check_launches(const char* what) {
   return PG_OK;
 }
 
+// ---- optional per-kernel timing (measurement hook; off by default) ----
+// When enabled, every launch of the three MFMA kernels is bracketed by a pair of events on the
+// caller's stream, taken from a pool created up front.  Not thread-safe.
+struct Profiler {
+  bool on = false;
+  std::vector<hipEvent_t> ev;     // 2 per recorded launch
+  std::vector<int> cls;           // kernel class per recorded launch
+  size_t cap = 0;
+} g_prof;
+
+struct ProfScope {
+  hipStream_t st;
+  bool active;
+  ProfScope(int cls, hipStream_t s) : st(s), active(false) {
+    if (g_prof.on && g_prof.cls.size() < g_prof.cap) {
+      active = true;
+      (void)hipEventRecord(g_prof.ev[2 * g_prof.cls.size()], st);
+      g_prof.cls.push_back(cls);
+    }
+  }
+  ~ProfScope() {
+    if (active) (void)hipEventRecord(g_prof.ev[2 * (g_prof.cls.size() - 1) + 1], st);
+  }
+};
+
 template <typename T>
 T* at(void* ws, size_t off) { return reinterpret_cast<T*>(static_cast<char*>(ws) + off); }
 
@@ -176,7 +202,7 @@ void run_forward(const Plan& pl, const pg_params& p, void* ws, const void* H, co
   f.yc = at<int>(ws, pl.yc); f.zy = at<float>(ws, pl.zy);
   f.part_m = at<float>(ws, pl.part_m); f.part_s = at<float>(ws, pl.part_s); f.part_u = at<float>(ws, pl.part_u);
   f.ctl = at<pg::Ctl>(ws, pl.ctl);
-  pg::launch_lmhead_fwd(f, st);
+  { ProfScope ps(PG_KERNEL_FWD, st); pg::launch_lmhead_fwd(f, st); }
 
   comb.tiles_v = pl.tiles_v; comb.t_cap = pl.t_cap;
   comb.part_m = f.part_m; comb.part_s = f.part_s; comb.part_u = f.part_u;
@@ -199,6 +225,35 @@ pg::PrepArgs base_prep(const Plan& pl, void* ws) {
 extern "C" {
 
 const char* pg_last_error(void) { return g_err; }
+
+int32_t pg_profile_enable(int32_t on, int32_t max_launches) {
+  for (hipEvent_t e : g_prof.ev) (void)hipEventDestroy(e);
+  g_prof.ev.clear(); g_prof.cls.clear(); g_prof.cap = 0; g_prof.on = false;
+  if (!on) return PG_OK;
+  if (max_launches < 1 || max_launches > (1 << 20)) return fail(PG_ERR_INVALID_ARG, "max_launches out of range");
+  g_prof.ev.resize(2 * (size_t)max_launches);
+  for (auto& e : g_prof.ev)
+    if (hipEventCreate(&e) != hipSuccess) return fail(PG_ERR_HIP, "hipEventCreate failed");
+  g_prof.cls.reserve(max_launches);
+  g_prof.cap = (size_t)max_launches;
+  g_prof.on = true;
+  return PG_OK;
+}
+
+int32_t pg_profile_read(double* h_ms, int64_t* h_launches) {
+  if (!h_ms || !h_launches) return fail(PG_ERR_INVALID_ARG, "output arrays must not be NULL");
+  for (int k = 0; k < PG_KERNEL_CLASSES; ++k) { h_ms[k] = 0.0; h_launches[k] = 0; }
+  for (size_t i = 0; i < g_prof.cls.size(); ++i) {
+    if (hipEventSynchronize(g_prof.ev[2 * i + 1]) != hipSuccess) return fail(PG_ERR_HIP, "hipEventSynchronize failed");
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, g_prof.ev[2 * i], g_prof.ev[2 * i + 1]) != hipSuccess)
+      return fail(PG_ERR_HIP, "hipEventElapsedTime failed");
+    h_ms[g_prof.cls[i]] += ms;
+    h_launches[g_prof.cls[i]] += 1;
+  }
+  g_prof.cls.clear();
+  return PG_OK;
+}
 
 size_t pg_workspace_bytes(int64_t T, int64_t d, int64_t V, int32_t S, const pg_params* h_params, int32_t which_call) {
   Plan pl;
@@ -311,7 +366,7 @@ int32_t pg_loss_fwd_bwd(const void* H, const void* W, const int32_t* y, const ui
     g.scale = (float)(LOG2E / (double)p.temperature);
     g.yc = at<int>(ws, pl.yc); g.lse2 = at<float>(ws, pl.lse2); g.coefc = at<float>(ws, pl.coefc);
     g.dS = at<__bf16>(ws, pl.dS); g.dST = at<__bf16>(ws, pl.dST); g.ctl = ctl;
-    pg::launch_lmhead_dlogits(g, st);
+    { ProfScope ps(PG_KERNEL_DLOGITS, st); pg::launch_lmhead_dlogits(g, st); }
 
     pg::StoreArgs w{};   // dW[v0 + m, :] = sum_t dS^T[m, t] H^T[:, t]
     w.A = at<__bf16>(ws, pl.dST); w.B = at<__bf16>(ws, pl.HcT);
@@ -320,7 +375,7 @@ int32_t pg_loss_fwd_bwd(const void* H, const void* W, const int32_t* y, const ui
     w.tiles_m = tiles_c; w.tiles_n = (d_i + 255) / 256;
     w.C = static_cast<char*>(dW) + (size_t)v0 * pl.d * dw_elem; w.ldc = d_i;
     w.accumulate = p.accumulate_dW; w.out_bf16 = p.dW_dtype; w.k_from_ctl = 1; w.m_from_ctl = 0; w.ctl = ctl;
-    pg::launch_gemm_store(w, st);
+    { ProfScope ps(PG_KERNEL_GRAD, st); pg::launch_gemm_store(w, st); }
 
     pg::StoreArgs h{};   // dHacc[t, :] (+)= sum_v dS[t, v] W^T[:, v]
     h.A = at<__bf16>(ws, pl.dS); h.B = at<__bf16>(ws, pl.WT);
@@ -329,7 +384,7 @@ int32_t pg_loss_fwd_bwd(const void* H, const void* W, const int32_t* y, const ui
     h.tiles_m = pl.tiles_t; h.tiles_n = (d_i + 255) / 256;
     h.C = at<float>(ws, pl.dHacc); h.ldc = d_i;
     h.accumulate = c > 0; h.out_bf16 = 0; h.k_from_ctl = 0; h.m_from_ctl = 1; h.ctl = ctl;
-    pg::launch_gemm_store(h, st);
+    { ProfScope ps(PG_KERNEL_GRAD, st); pg::launch_gemm_store(h, st); }
   }
 
   pg::ScatterArgs sc{at<float>(ws, pl.dHacc), at<int>(ws, pl.pos), dH, (int)pl.T, d_i, pl.is_f32};
