@@ -40,6 +40,10 @@ uint64_t ds_budget() {
   return DS_BUDGET;
 }
 
+// Leading dimensions whose byte stride is a multiple of 2 KiB put every row of a tile on the
+// same memory channels; such strides get 128 bytes of padding.
+inline int64_t pad_ld(int64_t n) { return (n * 2) % 2048 == 0 ? n + 64 : n; }
+
 inline size_t align_up(size_t x) { return (x + ALIGN - 1) / ALIGN * ALIGN; }
 
 struct Plan {
@@ -52,6 +56,8 @@ struct Plan {
   int chunk_tiles = 0; // vocab tiles per backward chunk
   int nchunks = 0;
   int vc = 0;          // chunk_tiles * 256
+  int ld_v = 0;        // leading dimension of the [*, vc] scratch matrices
+  int ld_t = 0;        // leading dimension of the [*, t_cap] scratch matrices
   size_t ctl, counters, flag, c_tok, a_tok, rows, pos, yc, zy, lse2, coefc, lossterm;
   size_t part_m, part_s, part_u, Hc, HcT, Wc, dS, dST, WT, dHacc;
   size_t total = 0;
@@ -115,13 +121,16 @@ int32_t make_plan(int64_t T, int64_t d, int64_t V, int32_t S, const pg_params* p
     const int64_t nchunks = (tiles_v + max_tiles - 1) / max_tiles;
     const int64_t chunk_tiles = (tiles_v + nchunks - 1) / nchunks;
     const int64_t vc = chunk_tiles * 256;
-    if ((uint64_t)t_cap * vc * 2 >= FOUR_GIB || (uint64_t)d * vc * 2 >= FOUR_GIB || (uint64_t)d * t_cap * 2 >= FOUR_GIB)
+    const int64_t ld_v = pad_ld(vc), ld_t = pad_ld(t_cap);
+    if ((uint64_t)t_cap * ld_v * 2 >= FOUR_GIB || (uint64_t)d * ld_v * 2 >= FOUR_GIB ||
+        (uint64_t)d * ld_t * 2 >= FOUR_GIB || (uint64_t)vc * ld_t * 2 >= FOUR_GIB)
       return fail(PG_ERR_UNSUPPORTED_SHAPE, "a backward scratch matrix reaches 4 GiB");
     pl.nchunks = (int)nchunks; pl.chunk_tiles = (int)chunk_tiles; pl.vc = (int)vc;
-    pl.HcT = take((size_t)d * t_cap * 2);
-    pl.dS = take((size_t)t_cap * vc * 2);
-    pl.dST = take((size_t)vc * t_cap * 2);
-    pl.WT = take((size_t)d * vc * 2);
+    pl.ld_v = (int)ld_v; pl.ld_t = (int)ld_t;
+    pl.HcT = take((size_t)d * ld_t * 2);
+    pl.dS = take((size_t)t_cap * ld_v * 2);
+    pl.dST = take((size_t)vc * ld_t * 2);
+    pl.WT = take((size_t)d * ld_v * 2);
     pl.dHacc = take((size_t)t_cap * d * 4);
   }
   pl.total = off > 0 ? off : ALIGN;
@@ -190,7 +199,7 @@ void run_forward(const Plan& pl, const pg_params& p, void* ws, const void* H, co
   g.H = H; g.y = y; g.d = (int)pl.d; g.t_cap = pl.t_cap; g.is_f32 = pl.is_f32;
   g.rows = at<int>(ws, pl.rows); g.Hc = at<__bf16>(ws, pl.Hc);
   g.HcT = need_HT ? at<__bf16>(ws, pl.HcT) : nullptr;
-  g.yc = at<int>(ws, pl.yc); g.ctl = at<pg::Ctl>(ws, pl.ctl);
+  g.yc = at<int>(ws, pl.yc); g.ctl = at<pg::Ctl>(ws, pl.ctl); g.ld_t = pl.ld_t;
   pg::launch_gather(g, st);
 
   pg::FwdArgs f{};
@@ -356,12 +365,12 @@ int32_t pg_loss_fwd_bwd(const void* H, const void* W, const int32_t* y, const ui
     const int tiles_c = (rows_valid + 255) / 256;
     const int kc = tiles_c * 256;
 
-    pg::launch_transpose_w(W, pl.is_f32, pl.V, d_i, v0, kc, pl.vc, at<__bf16>(ws, pl.WT), st);
+    pg::launch_transpose_w(W, pl.is_f32, pl.V, d_i, v0, kc, pl.ld_v, at<__bf16>(ws, pl.WT), st);
 
     pg::DlogitsArgs g{};
     g.W = Wop; g.Hc = at<__bf16>(ws, pl.Hc);
     g.w_bytes = (uint32_t)((uint64_t)pl.V * pl.kd * 2); g.h_bytes = (uint32_t)((uint64_t)pl.t_cap * pl.kd * 2);
-    g.ldw = pl.kd; g.ldh = pl.kd; g.K = pl.kd; g.V = (int)pl.V; g.v0 = v0; g.vc = pl.vc;
+    g.ldw = pl.kd; g.ldh = pl.kd; g.K = pl.kd; g.V = (int)pl.V; g.v0 = v0; g.ld_s = pl.ld_v; g.ld_t = pl.ld_t;
     g.tiles_v = tiles_c; g.tiles_t = pl.tiles_t; g.t_cap = pl.t_cap;
     g.scale = (float)(LOG2E / (double)p.temperature);
     g.yc = at<int>(ws, pl.yc); g.lse2 = at<float>(ws, pl.lse2); g.coefc = at<float>(ws, pl.coefc);
@@ -370,8 +379,8 @@ int32_t pg_loss_fwd_bwd(const void* H, const void* W, const int32_t* y, const ui
 
     pg::StoreArgs w{};   // dW[v0 + m, :] = sum_t dS^T[m, t] H^T[:, t]
     w.A = at<__bf16>(ws, pl.dST); w.B = at<__bf16>(ws, pl.HcT);
-    w.a_bytes = (uint32_t)((uint64_t)pl.vc * pl.t_cap * 2); w.b_bytes = (uint32_t)((uint64_t)pl.d * pl.t_cap * 2);
-    w.lda = pl.t_cap; w.ldb = pl.t_cap; w.M = rows_valid; w.N = d_i; w.K = pl.t_cap;
+    w.a_bytes = (uint32_t)((uint64_t)pl.vc * pl.ld_t * 2); w.b_bytes = (uint32_t)((uint64_t)pl.d * pl.ld_t * 2);
+    w.lda = pl.ld_t; w.ldb = pl.ld_t; w.M = rows_valid; w.N = d_i; w.K = pl.t_cap;
     w.tiles_m = tiles_c; w.tiles_n = (d_i + 255) / 256;
     w.C = static_cast<char*>(dW) + (size_t)v0 * pl.d * dw_elem; w.ldc = d_i;
     w.accumulate = p.accumulate_dW; w.out_bf16 = p.dW_dtype; w.k_from_ctl = 1; w.m_from_ctl = 0; w.ctl = ctl;
@@ -379,8 +388,8 @@ int32_t pg_loss_fwd_bwd(const void* H, const void* W, const int32_t* y, const ui
 
     pg::StoreArgs h{};   // dHacc[t, :] (+)= sum_v dS[t, v] W^T[:, v]
     h.A = at<__bf16>(ws, pl.dS); h.B = at<__bf16>(ws, pl.WT);
-    h.a_bytes = (uint32_t)((uint64_t)pl.t_cap * pl.vc * 2); h.b_bytes = (uint32_t)((uint64_t)pl.d * pl.vc * 2);
-    h.lda = pl.vc; h.ldb = pl.vc; h.M = pl.t_cap; h.N = d_i; h.K = kc;
+    h.a_bytes = (uint32_t)((uint64_t)pl.t_cap * pl.ld_v * 2); h.b_bytes = (uint32_t)((uint64_t)pl.d * pl.ld_v * 2);
+    h.lda = pl.ld_v; h.ldb = pl.ld_v; h.M = pl.t_cap; h.N = d_i; h.K = kc;
     h.tiles_m = pl.tiles_t; h.tiles_n = (d_i + 255) / 256;
     h.C = at<float>(ws, pl.dHacc); h.ldc = d_i;
     h.accumulate = c > 0; h.out_bf16 = 0; h.k_from_ctl = 0; h.m_from_ctl = 1; h.ctl = ctl;

@@ -34,15 +34,16 @@ struct DlogitsArgs {
   int K;
   int V;
   int v0;               // first vocab row of this chunk
-  int vc;               // leading dimension of dS (chunk capacity, multiple of 256)
+  int ld_s;             // leading dimension of dS   (>= chunk capacity)
+  int ld_t;             // leading dimension of dS^T (>= t_cap)
   int tiles_v, tiles_t; // tiles of this chunk
   int t_cap;
   float scale;
   const int* yc;
   const float* lse2;    // [t_cap] log2-domain logsumexp
   const float* coefc;   // [t_cap] coef / tau (0 on padding)
-  __bf16* dS;           // [t_cap, vc]
-  __bf16* dST;          // [vc, t_cap]
+  __bf16* dS;           // [t_cap, ld_s]
+  __bf16* dST;          // [vc, ld_t]
   const Ctl* ctl;
 };
 
@@ -112,7 +113,8 @@ struct GatherArgs {
   int is_f32;
   const int* rows;
   __bf16* Hc;           // [t_cap, ldh]   bf16: ldh = d;  fp32: ldh = 3d = [hi | hi | lo]
-  __bf16* HcT;          // [d, t_cap] (nullable)
+  __bf16* HcT;          // [d, ld_t] (nullable)
+  int ld_t;
   int* yc;
   const Ctl* ctl;
 };

@@ -1,14 +1,14 @@
 // The three MFMA kernels of the policy-gradient head (see gemm_core.h for the tile engine).
+//
+// Accumulator layout they all rely on: acc[i][j][r] of lane l is
+//   vocab-like row  m = wm*64  + i*16 + 4*(l>>4) + r      (i < 4, r < 4)
+//   token-like col  n = wn*128 + j*16 + (l & 15)          (j < 8)
+// so one lane holds 16 m-values of each of its 8 columns, and the four 16-lane groups of a
+// wavefront hold the other 48 m-values of the same columns.
 #include "kernels.h"
 #include "gemm_core.h"
 
 namespace pg {
-
-// 8 wavefronts as 4 (m) x 2 (n): two wavefronts per SIMD hide each other's LDS and barrier
-// latency; global->LDS loads bypass the register file.
-using GC = Cfg<4, 2, true>;
-constexpr int NTHREADS = GC::NT;
-constexpr int FM = GC::FM, FN = GC::FN;
 
 extern __shared__ __attribute__((aligned(16))) char g_smem[];
 
@@ -32,42 +32,42 @@ constexpr float NEG_BIG = -1.0e30f;   // finite stand-in for -inf: keeps 0 * (t 
 __global__ __launch_bounds__(NTHREADS) void lmhead_fwd_kernel(FwdArgs a) {
   const Ctl ctl = *a.ctl;
   int tm, tn;
-  if (!map_tile(blockIdx.x, a.tiles_v, a.tiles_t, tm, tn)) return;
-  if (tn * BN >= ctl.n_pad) return;
+  // the live token tiles are known only on the device; the grid covers the host-side maximum
+  if (!map_tile(blockIdx.x, a.tiles_v, min(a.tiles_t, ctl.n_pad / BN), tm, tn)) return;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave / GC::WN, wn = wave % GC::WN;
+  const int wm = wave / WN, wn = wave % WN;
 
-  TileLoader<GC> LA, LB;
-  init_loader<GC>(LA, a.W, a.w_bytes, tm * BM, a.ldw, tid);
-  init_loader<GC>(LB, a.Hc, a.h_bytes, tn * BN, a.ldh, tid);
-  f32x16 acc[FM][FN];
-  zero_acc<FM, FN>(acc);
-  mainloop<GC>(LA, LB, a.K / BK, g_smem, acc);
+  TileLoader LA, LB;
+  LA.init(a.W, a.w_bytes, tm * BM, a.ldw, tid);
+  LB.init(a.Hc, a.h_bytes, tn * BN, a.ldh, tid);
+  f32x4 acc[GM][GN];
+  zero_acc(acc);
+  mainloop(LA, LB, a.K / BK, g_smem, acc);
 
-  const int v_base = tm * BM + wm * GC::WROWS;              // first vocab row of this wave's block
+  const int v_base = tm * BM + wm * WROWS;            // first vocab row of this wavefront's block
   const bool ragged = (tm * BM + BM > a.V);
   float* red = reinterpret_cast<float*>(g_smem);      // [WM][256 tokens][3]
 
 #pragma unroll
-  for (int j = 0; j < FN; ++j) {
-    const int tok_l = wn * GC::WCOLS + j * 32 + (lane & 31);
+  for (int j = 0; j < GN; ++j) {
+    const int tok_l = wn * WCOLS + j * 16 + (lane & 15);
     const int tok = tn * BN + tok_l;
     float mx = NEG_BIG;
 #pragma unroll
-    for (int i = 0; i < FM; ++i)
+    for (int i = 0; i < GM; ++i)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
+      for (int r = 0; r < 4; ++r) {
         float t = acc[i][j][r] * a.scale;
-        if (ragged && (v_base + i * 32 + acc_row(r, lane) >= a.V)) t = NEG_BIG;
+        if (ragged && (v_base + i * 16 + acc_row(r, lane) >= a.V)) t = NEG_BIG;
         acc[i][j][r] = t;
         mx = fmaxf(mx, t);
       }
     float s = 0.f, u = 0.f;
 #pragma unroll
-    for (int i = 0; i < FM; ++i)
+    for (int i = 0; i < GM; ++i)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
+      for (int r = 0; r < 4; ++r) {
         const float dlt = acc[i][j][r] - mx;
         const float e = __builtin_amdgcn_exp2f(dlt);
         s += e;
@@ -76,20 +76,23 @@ __global__ __launch_bounds__(NTHREADS) void lmhead_fwd_kernel(FwdArgs a) {
     // sampled token's logit: at most one lane of the whole grid owns (tok, y[tok])
     const int ytok = a.yc[tok];
     const int yrel = ytok - v_base;
-    const bool mine = (yrel >= 0) && (yrel < GC::WROWS) && (ytok < a.V) && (((yrel >> 2) & 1) == (lane >> 5));
+    const bool mine = (yrel >= 0) && (yrel < WROWS) && (ytok < a.V) && (((yrel >> 2) & 3) == (lane >> 4));
     if (__any(mine)) {
       float zy = 0.f;
 #pragma unroll
-      for (int i = 0; i < FM; ++i)
+      for (int i = 0; i < GM; ++i)
 #pragma unroll
-        for (int r = 0; r < 16; ++r)
-          if (yrel == i * 32 + acc_row(r, lane)) zy = acc[i][j][r];
+        for (int r = 0; r < 4; ++r)
+          if (yrel == i * 16 + acc_row(r, lane)) zy = acc[i][j][r];
       if (mine) a.zy[tok] = zy;
     }
-    // the other half-wave holds the other vocab rows of the same token
-    const float m2 = __shfl_xor(mx, 32), s2 = __shfl_xor(s, 32), u2 = __shfl_xor(u, 32);
-    merge_state(mx, s, u, m2, s2, u2);
-    if (lane < 32) {
+    // the other three 16-lane groups hold the other vocab rows of the same token
+#pragma unroll
+    for (int sh = 16; sh <= 32; sh <<= 1) {
+      const float m2 = __shfl_xor(mx, sh), s2 = __shfl_xor(s, sh), u2 = __shfl_xor(u, sh);
+      merge_state(mx, s, u, m2, s2, u2);
+    }
+    if (lane < 16) {
       float* p = red + (wm * 256 + tok_l) * 3;
       p[0] = mx; p[1] = s; p[2] = u;
     }
@@ -99,7 +102,7 @@ __global__ __launch_bounds__(NTHREADS) void lmhead_fwd_kernel(FwdArgs a) {
     const float* p0 = red + tid * 3;
     float m = p0[0], s = p0[1], u = p0[2];
 #pragma unroll
-    for (int w = 1; w < GC::WM; ++w) {
+    for (int w = 1; w < WM; ++w) {
       const float* p1 = red + (w * 256 + tid) * 3;
       merge_state(m, s, u, p1[0], p1[1], p1[2]);
     }
@@ -112,39 +115,39 @@ __global__ __launch_bounds__(NTHREADS) void lmhead_fwd_kernel(FwdArgs a) {
 // Backward recompute: the same contraction, finished with
 //   dS[t,v] = c_t * (onehot(y_t)[v] - 2^(t2 - lse2_t)),  c_t = coef_t / tau,
 // rounded to bf16 and written for one vocab chunk in both orientations
-// (dS [t_cap, vc] for dH, dS^T [vc, t_cap] for dW).
+// (dS [t_cap, ld_s] for dH, dS^T [vc, ld_t] for dW).  Both go through an LDS transposition
+// stage so that global stores are 16 B per lane and 512 B per row.
 // ------------------------------------------------------------------------------------
-
 __global__ __launch_bounds__(NTHREADS) void lmhead_dlogits_kernel(DlogitsArgs a) {
   const Ctl ctl = *a.ctl;
   int tm, tn;
-  if (!map_tile(blockIdx.x, a.tiles_v, a.tiles_t, tm, tn)) return;
-  if (tn * BN >= ctl.n_pad) return;
+  // the live token tiles are known only on the device; the grid covers the host-side maximum
+  if (!map_tile(blockIdx.x, a.tiles_v, min(a.tiles_t, ctl.n_pad / BN), tm, tn)) return;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave / GC::WN, wn = wave % GC::WN;
+  const int wm = wave / WN, wn = wave % WN;
 
-  TileLoader<GC> LA, LB;
-  init_loader<GC>(LA, a.W, a.w_bytes, a.v0 + tm * BM, a.ldw, tid);
-  init_loader<GC>(LB, a.Hc, a.h_bytes, tn * BN, a.ldh, tid);
-  f32x16 acc[FM][FN];
-  zero_acc<FM, FN>(acc);
-  mainloop<GC>(LA, LB, a.K / BK, g_smem, acc);
+  TileLoader LA, LB;
+  LA.init(a.W, a.w_bytes, a.v0 + tm * BM, a.ldw, tid);
+  LB.init(a.Hc, a.h_bytes, tn * BN, a.ldh, tid);
+  f32x4 acc[GM][GN];
+  zero_acc(acc);
+  mainloop(LA, LB, a.K / BK, g_smem, acc);
 
-  const int v_base = a.v0 + tm * BM + wm * GC::WROWS;       // global vocab index
+  const int v_base = a.v0 + tm * BM + wm * WROWS;     // global vocab index
   const bool ragged = (a.v0 + tm * BM + BM > a.V);
 
 #pragma unroll
-  for (int j = 0; j < FN; ++j) {
-    const int tok = tn * BN + wn * GC::WCOLS + j * 32 + (lane & 31);
+  for (int j = 0; j < GN; ++j) {
+    const int tok = tn * BN + wn * WCOLS + j * 16 + (lane & 15);
     const float c = a.coefc[tok];
     const float l2 = a.lse2[tok];
     const int yrel = a.yc[tok] - v_base;
 #pragma unroll
-    for (int i = 0; i < FM; ++i)
+    for (int i = 0; i < GM; ++i)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int vr = i * 32 + acc_row(r, lane);
+      for (int r = 0; r < 4; ++r) {
+        const int vr = i * 16 + acc_row(r, lane);
         const float p = __builtin_amdgcn_exp2f(fmaf(acc[i][j][r], a.scale, -l2));
         float g = c * ((vr == yrel ? 1.f : 0.f) - p);
         if (ragged && (v_base + vr >= a.V)) g = 0.f;
@@ -155,52 +158,50 @@ __global__ __launch_bounds__(NTHREADS) void lmhead_dlogits_kernel(DlogitsArgs a)
   // ---- orientation 1: dS[tok][v], staged as rows of 256 v ----
   char* st = g_smem;
 #pragma unroll
-  for (int j = 0; j < FN; ++j) {
-    const int tok_l = wn * GC::WCOLS + j * 32 + (lane & 31);
+  for (int j = 0; j < GN; ++j) {
+    const int tok_l = wn * WCOLS + j * 16 + (lane & 15);
 #pragma unroll
-    for (int i = 0; i < FM; ++i)
+    for (int i = 0; i < GM; ++i) {
+      bf16x4 pk;
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        bf16x4 pk;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) pk[e] = (__bf16)acc[i][j][q * 4 + e];
-        const int v_l = wm * GC::WROWS + i * 32 + q * 8 + ((lane >> 5) << 2);
-        *reinterpret_cast<bf16x4*>(st + tok_l * EPI_STRIDE + v_l * 2) = pk;
-      }
+      for (int e = 0; e < 4; ++e) pk[e] = (__bf16)acc[i][j][e];
+      const int v_l = wm * WROWS + i * 16 + ((lane >> 4) << 2);
+      *reinterpret_cast<bf16x4*>(st + tok_l * EPI_STRIDE + v_l * 2) = pk;
+    }
   }
   __syncthreads();
   {
     const int chunk = tid & 31, r0 = tid >> 5;
-    __bf16* dst = a.dS + ((size_t)tn * BN) * a.vc + (size_t)tm * BM + chunk * 8;
+    __bf16* dst = a.dS + ((size_t)tn * BN) * a.ld_s + (size_t)tm * BM + chunk * 8;
 #pragma unroll 4
     for (int ps = 0; ps < 256 / (NTHREADS / 32); ++ps) {
       const int row = r0 + ps * (NTHREADS / 32);
       const i32x4 v = *reinterpret_cast<const i32x4*>(st + row * EPI_STRIDE + chunk * 16);
-      *reinterpret_cast<i32x4*>(dst + (size_t)row * a.vc) = v;
+      *reinterpret_cast<i32x4*>(dst + (size_t)row * a.ld_s) = v;
     }
   }
   __syncthreads();
   // ---- orientation 2: dS^T[v][tok], staged as rows of 256 tokens ----
 #pragma unroll
-  for (int j = 0; j < FN; ++j) {
-    const int tok_l = wn * GC::WCOLS + j * 32 + (lane & 31);
+  for (int j = 0; j < GN; ++j) {
+    const int tok_l = wn * WCOLS + j * 16 + (lane & 15);
 #pragma unroll
-    for (int i = 0; i < FM; ++i)
+    for (int i = 0; i < GM; ++i)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int v_l = wm * GC::WROWS + i * 32 + acc_row(r, lane);
+      for (int r = 0; r < 4; ++r) {
+        const int v_l = wm * WROWS + i * 16 + acc_row(r, lane);
         *reinterpret_cast<__bf16*>(st + v_l * EPI_STRIDE + tok_l * 2) = (__bf16)acc[i][j][r];
       }
   }
   __syncthreads();
   {
     const int chunk = tid & 31, r0 = tid >> 5;
-    __bf16* dst = a.dST + ((size_t)tm * BM) * a.t_cap + (size_t)tn * BN + chunk * 8;
+    __bf16* dst = a.dST + ((size_t)tm * BM) * a.ld_t + (size_t)tn * BN + chunk * 8;
 #pragma unroll 4
     for (int ps = 0; ps < 256 / (NTHREADS / 32); ++ps) {
       const int row = r0 + ps * (NTHREADS / 32);
       const i32x4 v = *reinterpret_cast<const i32x4*>(st + row * EPI_STRIDE + chunk * 16);
-      *reinterpret_cast<i32x4*>(dst + (size_t)row * a.t_cap) = v;
+      *reinterpret_cast<i32x4*>(dst + (size_t)row * a.ld_t) = v;
     }
   }
 }
@@ -212,19 +213,19 @@ __global__ __launch_bounds__(NTHREADS) void lmhead_dlogits_kernel(DlogitsArgs a)
 // m_from_ctl is the device-side padded token count.
 // ------------------------------------------------------------------------------------
 template <typename OutT>
-__device__ __forceinline__ void store_tile(const StoreArgs& a, int tm, int tn, int m_lim, f32x16 (&acc)[FM][FN]) {
+__device__ __forceinline__ void store_tile(const StoreArgs& a, int tm, int tn, int m_lim, f32x4 (&acc)[GM][GN]) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave / GC::WN, wn = wave % GC::WN;
+  const int wm = wave / WN, wn = wave % WN;
   OutT* C = reinterpret_cast<OutT*>(a.C);
 #pragma unroll
-  for (int j = 0; j < FN; ++j) {
-    const int n = tn * BN + wn * GC::WCOLS + j * 32 + (lane & 31);
+  for (int j = 0; j < GN; ++j) {
+    const int n = tn * BN + wn * WCOLS + j * 16 + (lane & 15);
     if (n >= a.N) continue;
 #pragma unroll
-    for (int i = 0; i < FM; ++i)
+    for (int i = 0; i < GM; ++i)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int m = tm * BM + wm * GC::WROWS + i * 32 + acc_row(r, lane);
+      for (int r = 0; r < 4; ++r) {
+        const int m = tm * BM + wm * WROWS + i * 16 + acc_row(r, lane);
         if (m >= m_lim) continue;
         OutT* p = C + (size_t)m * a.ldc + n;
         float v = acc[i][j][r];
@@ -237,18 +238,17 @@ __device__ __forceinline__ void store_tile(const StoreArgs& a, int tm, int tn, i
 __global__ __launch_bounds__(NTHREADS) void gemm_store_kernel(StoreArgs a) {
   const Ctl ctl = *a.ctl;
   int tm, tn;
-  if (!map_tile(blockIdx.x, a.tiles_m, a.tiles_n, tm, tn)) return;
   const int m_lim = a.m_from_ctl ? min(a.M, ctl.n_pad) : a.M;
-  if (tm * BM >= m_lim) return;
+  if (!map_tile(blockIdx.x, min(a.tiles_m, (m_lim + BM - 1) / BM), a.tiles_n, tm, tn)) return;
   const int K = a.k_from_ctl ? ctl.n_pad : a.K;
 
   const int tid = threadIdx.x;
-  TileLoader<GC> LA, LB;
-  init_loader<GC>(LA, a.A, a.a_bytes, tm * BM, a.lda, tid);
-  init_loader<GC>(LB, a.B, a.b_bytes, tn * BN, a.ldb, tid);
-  f32x16 acc[FM][FN];
-  zero_acc<FM, FN>(acc);
-  mainloop<GC>(LA, LB, K / BK, g_smem, acc);
+  TileLoader LA, LB;
+  LA.init(a.A, a.a_bytes, tm * BM, a.lda, tid);
+  LB.init(a.B, a.b_bytes, tn * BN, a.ldb, tid);
+  f32x4 acc[GM][GN];
+  zero_acc(acc);
+  mainloop(LA, LB, K / BK, g_smem, acc);
   if (a.out_bf16)
     store_tile<__bf16>(a, tm, tn, m_lim, acc);
   else

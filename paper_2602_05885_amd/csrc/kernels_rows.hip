@@ -229,7 +229,7 @@ __global__ __launch_bounds__(256) void gather_kernel(GatherArgs a) {
   __syncthreads();
   const int j = tid >> 2;
 #pragma unroll
-  for (int e = 0; e < 16; ++e) a.HcT[(size_t)(j0 + j) * a.t_cap + i0 + c0 + e] = tile[c0 + e][j];
+  for (int e = 0; e < 16; ++e) a.HcT[(size_t)(j0 + j) * a.ld_t + i0 + c0 + e] = tile[c0 + e][j];
 }
 void launch_gather(const GatherArgs& a, hipStream_t s) {
   hipLaunchKernelGGL(gather_kernel, dim3(a.t_cap / 64, a.d / 64), dim3(256), 0, s, a);
