@@ -46,6 +46,11 @@ def build(verbose: bool = True) -> str:
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.run(cmd, check=True)
+    # stand-alone tile-engine benchmark (used for the counter profiles)
+    cmd = [cc, *[f for f in FLAGS if f != "-fPIC"], os.path.join(CSRC, "tile_bench.hip"), "-o", os.path.join(PKG, "tile_bench")]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.run(cmd, check=True, stdout=subprocess.DEVNULL, stderr=subprocess.DEVNULL)
     return LIB
 
 

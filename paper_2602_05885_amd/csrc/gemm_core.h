@@ -16,6 +16,10 @@
 //     clock with it (+6 % end to end, +13 % on a pure MFMA stream).
 //   * operand slabs go global -> LDS directly (buffer_load ... lds, 16 B per lane), two
 //     64-deep stages of 64 KiB, one barrier per stage.
+//   * inside a stage the LDS->register traffic is software-pipelined by hand (A fragments
+//     resident, B fragments streamed two steps ahead) and pinned with sched_barrier: +4 % over
+//     the compiler's own order.  Moving the barrier earlier in the stage, 32-deep stages with
+//     3-5 buffers, and 4-wavefront layouts were all measured slower or equal.
 //   * the M side of the MFMA is the "vocab-like" operand, so a lane's accumulators of one
 //     MFMA tile share one n (token): row statistics over the vocabulary reduce inside a lane
 //     first, then across the four 16-lane groups, then across wavefronts through LDS.
@@ -47,6 +51,7 @@ constexpr int CHUNKS = 32 / NW;                  // direct loads per wavefront p
 constexpr int EPI_STRIDE = 528;                  // epilogue staging: 256 bf16 per row + 16 B pad
 constexpr int GEMM_LDS_BYTES = 256 * EPI_STRIDE; // 132 KiB >= the 128 KiB double-buffered main loop
 static_assert(GEMM_LDS_BYTES >= 2 * STAGE_BYTES, "LDS budget");
+static_assert(GM == 4 && GN == 8, "the main loop's 16-step schedule is written for 4 x 8 MFMA tiles per wavefront");
 
 // ---- control block written by the row-compaction kernel (device memory) ----
 struct Ctl {
@@ -148,18 +153,29 @@ __device__ __forceinline__ void mainloop(const TileLoader& LA, const TileLoader&
       LA.issue((uint32_t)(kt + 1) * (BK * 2), nxt, wave);
       LB.issue((uint32_t)(kt + 1) * (BK * 2), nxt + SLAB_BYTES, wave);
     }
+    {
+      // 16 steps (ks, j) of 4 MFMAs each: the A fragments of a 32-deep half stay resident, the B
+      // fragments stream through a 3-deep register queue fetched two steps ahead, and the A
+      // fragments of the second half arrive during the first.
+      const char* pa = cur + a_off;
+      const char* pb = cur + b_off;
+      bf16x8 a[2][GM], bq[3];
 #pragma unroll
-    for (int ks = 0; ks < 2; ++ks) {
-      bf16x8 a[GM], b[GN];
+      for (int i = 0; i < GM; ++i) a[0][i] = *reinterpret_cast<const bf16x8*>(pa + i * (16 * 128) + koff[0]);
+      bq[0] = *reinterpret_cast<const bf16x8*>(pb + koff[0]);
+      bq[1] = *reinterpret_cast<const bf16x8*>(pb + (16 * 128) + koff[0]);
 #pragma unroll
-      for (int i = 0; i < GM; ++i) a[i] = *reinterpret_cast<const bf16x8*>(cur + a_off + i * (16 * 128) + koff[ks]);
+      for (int s = 0; s < 16; ++s) {
+        const int ks = s >> 3, j = s & 7;
+        if (s + 2 < 16)
+          bq[(s + 2) % 3] = *reinterpret_cast<const bf16x8*>(pb + ((s + 2) & 7) * (16 * 128) + koff[(s + 2) >> 3]);
+        if (s < GM)
+          a[1][s] = *reinterpret_cast<const bf16x8*>(pa + s * (16 * 128) + koff[1]);
 #pragma unroll
-      for (int j = 0; j < GN; ++j) b[j] = *reinterpret_cast<const bf16x8*>(cur + b_off + j * (16 * 128) + koff[ks]);
-#pragma unroll
-      for (int i = 0; i < GM; ++i)
-#pragma unroll
-        for (int j = 0; j < GN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+        for (int i = 0; i < GM; ++i)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[ks][i], bq[s % 3], acc[i][j], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);   // keep this read/MFMA interleave as written
+      }
     }
     // my loads for the next stage have landed and my reads of this one are done
     asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");

@@ -1,0 +1,144 @@
+// Stand-alone benchmark of the tile engine (gemm_core.h): the main loop alone, finished with a
+// checksum instead of an epilogue, at the three contraction shapes of the 14B head
+// (logits: M=V, N=tokens, K=d;  dW chunk: M=vc, N=d, K=tokens;  dH chunk: M=tokens, N=d, K=vc).
+// Usage: tile_bench [iters [shape]]   iters timed launches per shape (default 3); shape 0..2 runs
+// that shape only.  It first verifies a small ragged product against a naive kernel.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdio>
+#include <cstdlib>
+#include <vector>
+
+#include "gemm_core.h"
+using namespace pg;
+
+#define CK(x)                                                                 \
+  do {                                                                        \
+    hipError_t e_ = (x);                                                      \
+    if (e_ != hipSuccess) {                                                   \
+      printf("HIP error %s at line %d\n", hipGetErrorString(e_), __LINE__);   \
+      exit(1);                                                                \
+    }                                                                         \
+  } while (0)
+
+extern __shared__ __attribute__((aligned(16))) char g_smem[];
+
+__global__ __launch_bounds__(NTHREADS) void tile_kernel(const __bf16* A, const __bf16* B, float* out, int M, int N,
+                                                        int K, int tiles_m, int tiles_n, int store_full) {
+  int tm, tn;
+  if (!map_tile(blockIdx.x, tiles_m, tiles_n, tm, tn)) return;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / WN, wn = wave % WN;
+  TileLoader LA, LB;
+  LA.init(A, (uint32_t)((size_t)M * K * 2), tm * BM, K, tid);
+  LB.init(B, (uint32_t)((size_t)N * K * 2), tn * BN, K, tid);
+  f32x4 acc[GM][GN];
+  zero_acc(acc);
+  mainloop(LA, LB, K / BK, g_smem, acc);
+  if (store_full) {
+    for (int j = 0; j < GN; ++j) {
+      const int n = tn * BN + wn * WCOLS + j * 16 + (lane & 15);
+      for (int i = 0; i < GM; ++i)
+        for (int r = 0; r < 4; ++r) {
+          const int m = tm * BM + wm * WROWS + i * 16 + acc_row(r, lane);
+          if (m < M && n < N) out[(size_t)m * N + n] = acc[i][j][r];
+        }
+    }
+  } else {
+    float s = 0.f;
+    for (int i = 0; i < GM; ++i)
+      for (int j = 0; j < GN; ++j)
+        for (int r = 0; r < 4; ++r) s += acc[i][j][r];
+    out[(size_t)blockIdx.x * NTHREADS + tid] = s;
+  }
+}
+
+__global__ void naive_kernel(const __bf16* A, const __bf16* B, float* out, int M, int N, int K) {
+  const int n = blockIdx.x * blockDim.x + threadIdx.x, m = blockIdx.y;
+  if (n >= N || m >= M) return;
+  float s = 0.f;
+  for (int k = 0; k < K; ++k) s += (float)A[(size_t)m * K + k] * (float)B[(size_t)n * K + k];
+  out[(size_t)m * N + n] = s;
+}
+
+__global__ void fill_kernel(__bf16* p, size_t n, unsigned seed, float scale) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (; i < n; i += stride) {
+    unsigned x = (unsigned)(i * 2654435761u) ^ seed;
+    x ^= x >> 16; x *= 0x85ebca6bu; x ^= x >> 13; x *= 0xc2b2ae35u; x ^= x >> 16;
+    p[i] = (__bf16)(((float)(x & 0xffff) / 65536.f - 0.5f) * scale);
+  }
+}
+
+static void launch(const __bf16* A, const __bf16* B, float* out, int M, int N, int K, int full) {
+  const int tiles_m = (M + 255) / 256, tiles_n = (N + 255) / 256;
+  hipLaunchKernelGGL(tile_kernel, dim3(grid_for_tiles(tiles_m, tiles_n)), dim3(NTHREADS), GEMM_LDS_BYTES, 0, A, B, out,
+                     M, N, K, tiles_m, tiles_n, full);
+}
+
+int main(int argc, char** argv) {
+  const int iters = argc > 1 ? atoi(argv[1]) : 3;
+  const int only = argc > 2 ? atoi(argv[2]) : -1;
+  CK(hipFuncSetAttribute(reinterpret_cast<const void*>(tile_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                         GEMM_LDS_BYTES));
+  {  // correctness on a ragged shape
+    const int M = 700, N = 520, K = 320;
+    __bf16 *A, *B;
+    float *out, *ref;
+    CK(hipMalloc(&A, (size_t)M * K * 2)); CK(hipMalloc(&B, (size_t)N * K * 2));
+    CK(hipMalloc(&out, (size_t)M * N * 4)); CK(hipMalloc(&ref, (size_t)M * N * 4));
+    fill_kernel<<<256, 256>>>(A, (size_t)M * K, 1u, 2.f);
+    fill_kernel<<<256, 256>>>(B, (size_t)N * K, 2u, 2.f);
+    naive_kernel<<<dim3((N + 255) / 256, M), 256>>>(A, B, ref, M, N, K);
+    CK(hipMemset(out, 0xff, (size_t)M * N * 4));
+    launch(A, B, out, M, N, K, 1);
+    CK(hipDeviceSynchronize());
+    std::vector<float> h((size_t)M * N), r((size_t)M * N);
+    CK(hipMemcpy(h.data(), out, h.size() * 4, hipMemcpyDeviceToHost));
+    CK(hipMemcpy(r.data(), ref, r.size() * 4, hipMemcpyDeviceToHost));
+    size_t bad = 0;
+    double maxerr = 0;
+    for (size_t i = 0; i < h.size(); ++i) {
+      const double e = fabs((double)h[i] - r[i]);
+      if (!(e < 1e-2)) ++bad;
+      if (e > maxerr) maxerr = e;
+    }
+    printf("[check] M=%d N=%d K=%d maxerr=%.3e bad=%zu %s\n", M, N, K, maxerr, bad, bad ? "FAIL" : "ok");
+    fflush(stdout);
+    CK(hipFree(A)); CK(hipFree(B)); CK(hipFree(out)); CK(hipFree(ref));
+    if (bad) return 1;
+  }
+  struct Shape { const char* name; int M, N, K; } shapes[] = {
+      {"logits  (V x tokens x d)", 151936, 8192, 5120},
+      {"dW chunk (vc x d x tokens)", 21760, 5120, 32768},
+      {"dH chunk (tokens x d x vc)", 32768, 5120, 21760}};
+  for (int si = 0; si < 3; ++si) {
+    if (only >= 0 && si != only) continue;
+    const Shape s = shapes[si];
+    __bf16 *A, *B;
+    float* out;
+    CK(hipMalloc(&A, (size_t)s.M * s.K * 2)); CK(hipMalloc(&B, (size_t)s.N * s.K * 2));
+    const int grid = grid_for_tiles((s.M + 255) / 256, (s.N + 255) / 256);
+    CK(hipMalloc(&out, (size_t)grid * NTHREADS * 4));
+    fill_kernel<<<1024, 256>>>(A, (size_t)s.M * s.K, 1u, 0.1f);
+    fill_kernel<<<1024, 256>>>(B, (size_t)s.N * s.K, 2u, 2.f);
+    for (int w = 0; w < 2; ++w) launch(A, B, out, s.M, s.N, s.K, 0);
+    CK(hipDeviceSynchronize());
+    hipEvent_t e0, e1;
+    CK(hipEventCreate(&e0)); CK(hipEventCreate(&e1));
+    CK(hipEventRecord(e0));
+    for (int w = 0; w < iters; ++w) launch(A, B, out, s.M, s.N, s.K, 0);
+    CK(hipEventRecord(e1)); CK(hipEventSynchronize(e1));
+    float ms;
+    CK(hipEventElapsedTime(&ms, e0, e1));
+    ms /= iters;
+    const double fl = 2.0 * s.M * s.N * s.K;
+    printf("[time ] %-28s M=%d N=%d K=%d  %.3f ms  %.1f TFLOP/s  (%.1f%% of 2500)\n", s.name, s.M, s.N, s.K, ms,
+           fl / ms / 1e9, fl / ms / 1e9 / 25.0);
+    fflush(stdout);
+    CK(hipFree(A)); CK(hipFree(B)); CK(hipFree(out));
+  }
+  return 0;
+}
