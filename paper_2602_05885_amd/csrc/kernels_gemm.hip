@@ -137,22 +137,44 @@ __global__ __launch_bounds__(NTHREADS) void lmhead_dlogits_kernel(DlogitsArgs a)
   const int v_base = a.v0 + tm * BM + wm * WROWS;     // global vocab index
   const bool ragged = (a.v0 + tm * BM + BM > a.V);
 
+  // dS = c (onehot - p) is formed as  -sign(c) 2^(t2 - lse2 + log2|c|)  for every element (one fma
+  // and one exp2 each; c = 0 gives 2^-inf = 0), the one-hot term c is added to the single element
+  // that holds the sampled token (rare, wave-uniform branch), and the sign goes on with the bf16
+  // packing.  pk[i][j][h] holds rows 2h, 2h+1 of this lane's 4-row group as a bf16 pair.
+  uint32_t pk[GM][GN][2];
 #pragma unroll
   for (int j = 0; j < GN; ++j) {
     const int tok = tn * BN + wn * WCOLS + j * 16 + (lane & 15);
     const float c = a.coefc[tok];
-    const float l2 = a.lse2[tok];
+    const float k2 = __builtin_amdgcn_logf(fabsf(c)) - a.lse2[tok];
+    const uint32_t sgn = c > 0.f ? 0x80008000u : 0u;
     const int yrel = a.yc[tok] - v_base;
+    const bool mine = (yrel >= 0) && (yrel < WROWS) && (((yrel >> 2) & 3) == (lane >> 4));
+    const bool any_mine = __any(mine);
 #pragma unroll
-    for (int i = 0; i < GM; ++i)
+    for (int i = 0; i < GM; ++i) {
+      float g[4];
 #pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const int vr = i * 16 + acc_row(r, lane);
-        const float p = __builtin_amdgcn_exp2f(fmaf(acc[i][j][r], a.scale, -l2));
-        float g = c * ((vr == yrel ? 1.f : 0.f) - p);
-        if (ragged && (v_base + vr >= a.V)) g = 0.f;
-        acc[i][j][r] = g;
+      for (int r = 0; r < 4; ++r) g[r] = __builtin_amdgcn_exp2f(fmaf(acc[i][j][r], a.scale, k2));
+      if (any_mine) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+          if (yrel == i * 16 + acc_row(r, lane)) g[r] -= fabsf(c);     // sign is applied below
       }
+      if (ragged) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+          if (v_base + i * 16 + acc_row(r, lane) >= a.V) g[r] = 0.f;
+      }
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+        bf16x2 two;
+        two[0] = (__bf16)g[2 * h];
+        two[1] = (__bf16)g[2 * h + 1];
+        pk[i][j][h] = __builtin_bit_cast(uint32_t, two) ^ sgn;
+      }
+    }
   }
 
   // ---- orientation 1: dS[tok][v], staged as rows of 256 v ----
@@ -162,11 +184,9 @@ __global__ __launch_bounds__(NTHREADS) void lmhead_dlogits_kernel(DlogitsArgs a)
     const int tok_l = wn * WCOLS + j * 16 + (lane & 15);
 #pragma unroll
     for (int i = 0; i < GM; ++i) {
-      bf16x4 pk;
-#pragma unroll
-      for (int e = 0; e < 4; ++e) pk[e] = (__bf16)acc[i][j][e];
       const int v_l = wm * WROWS + i * 16 + ((lane >> 4) << 2);
-      *reinterpret_cast<bf16x4*>(st + tok_l * EPI_STRIDE + v_l * 2) = pk;
+      uint2 two = make_uint2(pk[i][j][0], pk[i][j][1]);
+      *reinterpret_cast<uint2*>(st + tok_l * EPI_STRIDE + v_l * 2) = two;
     }
   }
   __syncthreads();
@@ -177,7 +197,7 @@ __global__ __launch_bounds__(NTHREADS) void lmhead_dlogits_kernel(DlogitsArgs a)
     for (int ps = 0; ps < 256 / (NTHREADS / 32); ++ps) {
       const int row = r0 + ps * (NTHREADS / 32);
       const i32x4 v = *reinterpret_cast<const i32x4*>(st + row * EPI_STRIDE + chunk * 16);
-      *reinterpret_cast<i32x4*>(dst + (size_t)row * a.ld_s) = v;
+      __builtin_nontemporal_store(v, reinterpret_cast<i32x4*>(dst + (size_t)row * a.ld_s));
     }
   }
   __syncthreads();
@@ -190,7 +210,8 @@ __global__ __launch_bounds__(NTHREADS) void lmhead_dlogits_kernel(DlogitsArgs a)
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
         const int v_l = wm * WROWS + i * 16 + acc_row(r, lane);
-        *reinterpret_cast<__bf16*>(st + v_l * EPI_STRIDE + tok_l * 2) = (__bf16)acc[i][j][r];
+        const uint32_t w = pk[i][j][r >> 1];
+        *reinterpret_cast<uint16_t*>(st + v_l * EPI_STRIDE + tok_l * 2) = (uint16_t)((r & 1) ? (w >> 16) : w);
       }
   }
   __syncthreads();
@@ -201,7 +222,7 @@ __global__ __launch_bounds__(NTHREADS) void lmhead_dlogits_kernel(DlogitsArgs a)
     for (int ps = 0; ps < 256 / (NTHREADS / 32); ++ps) {
       const int row = r0 + ps * (NTHREADS / 32);
       const i32x4 v = *reinterpret_cast<const i32x4*>(st + row * EPI_STRIDE + chunk * 16);
-      *reinterpret_cast<i32x4*>(dst + (size_t)row * a.ld_t) = v;
+      __builtin_nontemporal_store(v, reinterpret_cast<i32x4*>(dst + (size_t)row * a.ld_t));
     }
   }
 }
