@@ -118,8 +118,21 @@ int32_t make_plan(int64_t T, int64_t d, int64_t V, int32_t S, const pg_params* p
     int64_t max_tiles = t_cap > 0 ? (int64_t)(ds_budget() / ((uint64_t)t_cap * 2 * 256)) : tiles_v;
     if (max_tiles < 1) max_tiles = 1;
     if (max_tiles > tiles_v) max_tiles = tiles_v;
-    const int64_t nchunks = (tiles_v + max_tiles - 1) / max_tiles;
-    const int64_t chunk_tiles = (tiles_v + nchunks - 1) / nchunks;
+    // Chunk size: within the scratch budget, the size whose dW launches (chunk_tiles x ceil(d/256)
+    // tiles each, over 256 compute units) waste the fewest partly filled rounds; every extra chunk
+    // is charged half a round for its launches and its pass over the dH accumulator.
+    int64_t chunk_tiles = max_tiles;
+    if (tiles_v > max_tiles) {
+      const int64_t td = (d + 255) / 256;
+      double best = 1e30;
+      for (int64_t ct = max_tiles; ct >= 1 && ct * 3 >= max_tiles * 2; --ct) {
+        const int64_t nch = (tiles_v + ct - 1) / ct;
+        const int64_t last = tiles_v - (nch - 1) * ct;
+        const double cost = (double)((nch - 1) * ((ct * td + 255) / 256) + (last * td + 255) / 256) + 0.5 * (double)nch;
+        if (cost < best) { best = cost; chunk_tiles = ct; }
+      }
+    }
+    const int64_t nchunks = (tiles_v + chunk_tiles - 1) / chunk_tiles;
     const int64_t vc = chunk_tiles * 256;
     const int64_t ld_v = pad_ld(vc), ld_t = pad_ld(t_cap);
     if ((uint64_t)t_cap * ld_v * 2 >= FOUR_GIB || (uint64_t)d * ld_v * 2 >= FOUR_GIB ||

@@ -196,10 +196,35 @@ __device__ __forceinline__ void split_bf16(float x, __bf16& hi, __bf16& lo) {
   lo = (__bf16)(x - (float)hi);
 }
 
+// ---- 64 x 64 bf16 tile transposition through LDS with 16-byte global accesses ----
+// Rows are staged with a stride of 68 elements (34 words): 8-byte aligned for the row writes and
+// odd enough in words that the column reads of the transposed phase spread over the banks.
+constexpr int TT_LD = 68;
+
+// thread t: 16-byte chunk t&7 of rows (t>>3) and (t>>3)+32
+__device__ __forceinline__ void tt_put(uint16_t* tile, int row, int chunk, const i32x4& v) {
+  uint2* p = reinterpret_cast<uint2*>(tile + row * TT_LD + chunk * 8);
+  p[0] = make_uint2((uint32_t)v[0], (uint32_t)v[1]);
+  p[1] = make_uint2((uint32_t)v[2], (uint32_t)v[3]);
+}
+// column `col`, rows chunk*8 .. chunk*8+7, packed as one 16-byte row piece of the transpose
+__device__ __forceinline__ i32x4 tt_get(const uint16_t* tile, int col, int chunk) {
+  uint32_t w[4];
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    const uint32_t lo = tile[(chunk * 8 + 2 * e) * TT_LD + col];
+    const uint32_t hi = tile[(chunk * 8 + 2 * e + 1) * TT_LD + col];
+    w[e] = lo | (hi << 16);
+  }
+  i32x4 v;
+  v[0] = (int)w[0]; v[1] = (int)w[1]; v[2] = (int)w[2]; v[3] = (int)w[3];
+  return v;
+}
+
 // 64 compacted rows x 64 columns per workgroup: copies (or splits) H rows into the compacted,
 // zero-padded operand and writes its transpose for the dW contraction.
 __global__ __launch_bounds__(256) void gather_kernel(GatherArgs a) {
-  __shared__ __bf16 tile[64][66];
+  __shared__ __attribute__((aligned(16))) uint16_t tile[64 * TT_LD];
   const Ctl ctl = *a.ctl;
   const int i0 = blockIdx.x * 64, j0 = blockIdx.y * 64;
   if (i0 >= ctl.n_pad) return;
@@ -208,7 +233,30 @@ __global__ __launch_bounds__(256) void gather_kernel(GatherArgs a) {
     const int i = i0 + tid;
     a.yc[i] = (i < ctl.n_active) ? a.y[a.rows[i]] : -1;
   }
-  const int ldh = a.is_f32 ? 3 * a.d : a.d;
+  if (!a.is_f32) {
+    const int chunk = tid & 7;
+#pragma unroll
+    for (int p = 0; p < 2; ++p) {
+      const int r = (tid >> 3) + 32 * p;
+      const int i = i0 + r;
+      i32x4 v = {0, 0, 0, 0};
+      if (i < ctl.n_active)
+        v = *reinterpret_cast<const i32x4*>(reinterpret_cast<const __bf16*>(a.H) + (size_t)a.rows[i] * a.d + j0 + chunk * 8);
+      *reinterpret_cast<i32x4*>(a.Hc + (size_t)i * a.d + j0 + chunk * 8) = v;
+      tt_put(tile, r, chunk, v);
+    }
+    if (!a.HcT) return;
+    __syncthreads();
+#pragma unroll
+    for (int p = 0; p < 2; ++p) {
+      const int jj = (tid >> 3) + 32 * p;
+      *reinterpret_cast<i32x4*>(a.HcT + (size_t)(j0 + jj) * a.ld_t + i0 + chunk * 8) = tt_get(tile, jj, chunk);
+    }
+    return;
+  }
+  // fp32 inputs: split into bf16 hi + lo parts, [hi | hi | lo] along k
+  __bf16* tl = reinterpret_cast<__bf16*>(tile);
+  const int ldh = 3 * a.d;
   const int r = tid >> 2, c0 = (tid & 3) * 16;
   const int i = i0 + r;
   const bool live = i < ctl.n_active;
@@ -216,20 +264,18 @@ __global__ __launch_bounds__(256) void gather_kernel(GatherArgs a) {
 #pragma unroll
   for (int e = 0; e < 16; ++e) {
     __bf16 hi = (__bf16)0.f, lo = (__bf16)0.f;
-    if (live) {
-      if (a.is_f32) split_bf16(reinterpret_cast<const float*>(a.H)[src + e], hi, lo);
-      else hi = reinterpret_cast<const __bf16*>(a.H)[src + e];
-    }
+    if (live) split_bf16(reinterpret_cast<const float*>(a.H)[src + e], hi, lo);
     const size_t o = (size_t)i * ldh + j0 + c0 + e;
     a.Hc[o] = hi;
-    if (a.is_f32) { a.Hc[o + a.d] = hi; a.Hc[o + 2 * a.d] = lo; }
-    tile[r][c0 + e] = hi;
+    a.Hc[o + a.d] = hi;
+    a.Hc[o + 2 * a.d] = lo;
+    tl[r * TT_LD + c0 + e] = hi;
   }
   if (!a.HcT) return;
   __syncthreads();
   const int j = tid >> 2;
 #pragma unroll
-  for (int e = 0; e < 16; ++e) a.HcT[(size_t)(j0 + j) * a.ld_t + i0 + c0 + e] = tile[c0 + e][j];
+  for (int e = 0; e < 16; ++e) a.HcT[(size_t)(j0 + j) * a.ld_t + i0 + c0 + e] = tl[(c0 + e) * TT_LD + j];
 }
 void launch_gather(const GatherArgs& a, hipStream_t s) {
   hipLaunchKernelGGL(gather_kernel, dim3(a.t_cap / 64, a.d / 64), dim3(256), 0, s, a);
@@ -255,24 +301,35 @@ void launch_split_w(const float* W, __bf16* Wc, int64_t V, int d, hipStream_t s)
 // W rows [v0, v0+cols) -> WT[j][v - v0] (bf16; fp32 weights are rounded), zeros for v >= V.
 __global__ __launch_bounds__(256) void transpose_w_kernel(const void* W, int is_f32, long long V, int d, int v0,
                                                           int ldt, __bf16* WT) {
-  __shared__ __bf16 tile[64][66];
+  __shared__ __attribute__((aligned(16))) uint16_t tile[64 * TT_LD];
   const int vt = blockIdx.x * 64, j0 = blockIdx.y * 64;
   const int tid = threadIdx.x;
-  const int r = tid >> 2, c0 = (tid & 3) * 16;
-  const long long v = (long long)v0 + vt + r;
+  const int chunk = tid & 7;
 #pragma unroll
-  for (int e = 0; e < 16; ++e) {
-    __bf16 x = (__bf16)0.f;
+  for (int p = 0; p < 2; ++p) {
+    const int r = (tid >> 3) + 32 * p;
+    const long long v = (long long)v0 + vt + r;
+    i32x4 x = {0, 0, 0, 0};
     if (v < V) {
-      const size_t o = (size_t)v * d + j0 + c0 + e;
-      x = is_f32 ? (__bf16)reinterpret_cast<const float*>(W)[o] : reinterpret_cast<const __bf16*>(W)[o];
+      const size_t o = (size_t)v * d + j0 + chunk * 8;
+      if (is_f32) {
+        const float* src = reinterpret_cast<const float*>(W) + o;
+        bf16x8 h;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) h[e] = (__bf16)src[e];
+        x = __builtin_bit_cast(i32x4, h);
+      } else {
+        x = *reinterpret_cast<const i32x4*>(reinterpret_cast<const __bf16*>(W) + o);
+      }
     }
-    tile[r][c0 + e] = x;
+    tt_put(tile, r, chunk, x);
   }
   __syncthreads();
-  const int j = tid >> 2;
 #pragma unroll
-  for (int e = 0; e < 16; ++e) WT[(size_t)(j0 + j) * ldt + vt + c0 + e] = tile[c0 + e][j];
+  for (int p = 0; p < 2; ++p) {
+    const int jj = (tid >> 3) + 32 * p;
+    *reinterpret_cast<i32x4*>(WT + (size_t)(j0 + jj) * ldt + vt + chunk * 8) = tt_get(tile, jj, chunk);
+  }
 }
 void launch_transpose_w(const void* W, int is_f32, int64_t V, int d, int v0, int cols, int ldt, __bf16* WT,
                         hipStream_t s) {
