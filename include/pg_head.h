@@ -164,8 +164,9 @@ int32_t pg_loss_fwd_bwd(const void* H, const void* W, const int32_t* y, const ui
  */
 #define PG_KERNEL_FWD 0      /* logits + online softmax statistics               */
 #define PG_KERNEL_DLOGITS 1  /* logits recompute + dS in both orientations       */
-#define PG_KERNEL_GRAD 2     /* dW = dS^T H and dH = dS W                        */
-#define PG_KERNEL_CLASSES 3
+#define PG_KERNEL_DW 2       /* dW = dS^T H   (gemm_store_kernel)                */
+#define PG_KERNEL_DH 3       /* dH = dS W     (gemm_store_kernel)                */
+#define PG_KERNEL_CLASSES 4
 int32_t pg_profile_enable(int32_t on, int32_t max_launches);
 int32_t pg_profile_read(double* h_ms, int64_t* h_launches);
 

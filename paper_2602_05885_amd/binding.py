@@ -23,7 +23,7 @@ COUNTER_NAMES = ("active", "clip_hi", "clip_lo", "seg_geo", "seg_veto", "truncat
 
 EXPORTS = ("pg_last_error", "pg_workspace_bytes", "trloo_advantage", "pg_logprob_fwd", "pg_loss_fwd_bwd",
            "pg_profile_enable", "pg_profile_read")
-KERNEL_CLASSES = ("fwd", "dlogits", "grad")
+KERNEL_CLASSES = ("fwd", "dlogits", "dw", "dh")
 
 
 class PgParams(C.Structure):
