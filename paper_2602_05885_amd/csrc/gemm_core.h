@@ -15,11 +15,17 @@
 //     accumulator traffic; the chip is power-limited under MFMA load and sustains a higher
 //     clock with it (+6 % end to end, +13 % on a pure MFMA stream).
 //   * operand slabs go global -> LDS directly (buffer_load ... lds, 16 B per lane), two
-//     64-deep stages of 64 KiB, one barrier per stage.
+//     64-deep stages of 64 KiB.
+//   * a wavefront that issues a burst of such loads is held at the issue stage while the
+//     texture-address unit works through them (16 cycles per 1 KiB load, 64 loads per stage), and
+//     its MFMAs wait behind them.  The loads are therefore trickled out one per 64-cycle step over
+//     the whole stage, which a two-barrier stage schedule makes legal: the A slab of a stage is
+//     dead once the register-resident A fragments have been read (barrier X after step 4), the
+//     B slab once the last streamed B fragment has been read (barrier Y, two steps before the end
+//     of the stage).  Measured +10..13 % over issuing a stage's loads in one burst.
 //   * inside a stage the LDS->register traffic is software-pipelined by hand (A fragments
-//     resident, B fragments streamed two steps ahead) and pinned with sched_barrier: +4 % over
-//     the compiler's own order.  Moving the barrier earlier in the stage, 32-deep stages with
-//     3-5 buffers, and 4-wavefront layouts were all measured slower or equal.
+//     resident, B fragments streamed two steps ahead, the first fragments of the next stage
+//     fetched behind barrier Y under the last two steps' MFMAs) and pinned with sched_barrier.
 //   * the M side of the MFMA is the "vocab-like" operand, so a lane's accumulators of one
 //     MFMA tile share one n (token): row statistics over the vocabulary reduce inside a lane
 //     first, then across the four 16-lane groups, then across wavefronts through LDS.
@@ -100,11 +106,20 @@ __device__ __forceinline__ bool map_tile(int bid, int tiles_m, int tiles_n, int&
 // l/8, position l%8, so it fetches the logical chunk (l%8) ^ ((row>>1)&7) of that row.
 // Loads beyond the buffer resource's size return 0, which pads ragged tiles.
 struct TileLoader {
-  __amdgpu_buffer_rsrc_t rsrc;
+  const void* base;
+  uint32_t bytes;
   uint32_t voff[CHUNKS];
 
-  __device__ __forceinline__ void init(const void* base, uint32_t num_bytes, int row0, int ld_elems, int tid) {
-    rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, num_bytes, 0x00020000);
+  // Buffer resource over the operand; with on == false its range is empty, so loads through it
+  // fetch nothing and deliver zeros (used to switch the loads off beyond the last stage without
+  // a branch in the schedule).
+  __device__ __forceinline__ __amdgpu_buffer_rsrc_t rsrc(bool on) const {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, on ? bytes : 0u, 0x00020000);
+  }
+
+  __device__ __forceinline__ void init(const void* base_, uint32_t num_bytes, int row0, int ld_elems, int tid) {
+    base = base_;
+    bytes = num_bytes;
     const int lane = tid & 63, wave = tid >> 6;
 #pragma unroll
     for (int i = 0; i < CHUNKS; ++i) {
@@ -114,25 +129,40 @@ struct TileLoader {
     }
   }
 
-  // global -> LDS, bypassing registers: this wavefront's share of one operand slab
-  __device__ __forceinline__ void issue(uint32_t k_byte_off, char* slab, int wave) const {
-#pragma unroll
-    for (int i = 0; i < CHUNKS; ++i) {
-      char* dst = slab + (i * NW + wave) * 1024;
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void*)dst, 16, voff[i], k_byte_off, 0, 0);
-    }
+  // global -> LDS, bypassing registers: chunk i (1 KiB = 8 rows) of this wavefront's share of one
+  // operand slab.  `wave` must be wave-uniform (it addresses LDS through M0).
+  __device__ __forceinline__ void issue1(__amdgpu_buffer_rsrc_t r, int i, uint32_t k_byte_off, char* slab,
+                                         int wave) const {
+    char* dst = slab + (i * NW + wave) * 1024;
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (lds_void*)dst, 16, voff[i], k_byte_off, 0, 0);
   }
 };
 
 // Accumulates C(256x256) += A(256 x K) B(256 x K)^T for this workgroup's tile, K = 64 nk.
 // acc[i][j] is the 16x16 MFMA tile at rows wm*64+i*16, cols wn*128+j*16 of the workgroup tile;
 // within it, register r of lane l is row 4*(l>>4)+r, column l&15.
-// The barriers are issued together with the wait for this wavefront's own direct loads; the
-// "memory" clobber keeps LDS accesses on their side of it.
+//
+// A stage (64 of k) is 16 steps s = (ks, j) of 4 MFMAs.  Per wavefront and stage:
+//   steps 0..1   second half of the B loads of stage kt+1 (the first half went out in the
+//                previous tail), A fragments of the second k-half
+//   step  4      barrier X: every A read of this stage is complete -> its A slab is free
+//   steps 5..8   A loads of stage kt+2 into that slab, one per step
+//   step  13     barrier Y: every B read of this stage is complete and stage kt+1 has landed
+//                (the wavefront leaves only its 4 newest loads, the A loads of kt+2, in flight)
+//   steps 14,15  "tail": first half of the B loads of stage kt+2, first LDS reads of stage kt+1,
+//                under the last 8 MFMAs of stage kt
+// On return every load has landed and every wavefront has passed a barrier, so the caller may
+// reuse the LDS.  The barriers carry their own waits; the "memory" clobber keeps LDS accesses on
+// their side of them.
 __device__ __forceinline__ void mainloop(const TileLoader& LA, const TileLoader& LB, int nk, char* smem,
                                          f32x4 (&acc)[GM][GN]) {
+  constexpr int NS = 2 * GN;          // steps per stage
+  constexpr int TAIL = 2;             // steps behind barrier Y
+  constexpr int XS = 4;               // barrier X follows this step
+  constexpr int BH = CHUNKS / 2;      // B loads per half
+  static_assert(CHUNKS == 4 && BH <= XS && XS + CHUNKS < NS - TAIL, "load schedule");
   const int tid = threadIdx.x;
-  const int lane = tid & 63, wave = tid >> 6;
+  const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave / WN, wn = wave % WN;
   const int lrow = lane & 15;
   const int xr = (lane >> 1) & 7;
@@ -143,43 +173,67 @@ __device__ __forceinline__ void mainloop(const TileLoader& LA, const TileLoader&
   for (int ks = 0; ks < 2; ++ks) koff[ks] = (uint32_t)(((ks * 4 + (lane >> 4)) ^ xr) << 4);
   if (nk <= 0) return;
 
-  LA.issue(0, smem, wave);
-  LB.issue(0, smem + SLAB_BYTES, wave);
-  asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
+  bf16x8 a[2][GM], bq[4];
+  auto rdA = [&](const char* st, int ks, int i) -> bf16x8 {
+    return *reinterpret_cast<const bf16x8*>(st + a_off + i * (16 * 128) + koff[ks]);
+  };
+  auto rdB = [&](const char* st, int s) -> bf16x8 {   // B fragment of step s
+    return *reinterpret_cast<const bf16x8*>(st + b_off + (s % GN) * (16 * 128) + koff[s / GN]);
+  };
+
+  {  // prologue: stage 0 complete, A and the first half of B of stage 1
+    const __amdgpu_buffer_rsrc_t ra = LA.rsrc(true), rb = LB.rsrc(true);
+#pragma unroll
+    for (int i = 0; i < CHUNKS; ++i) LA.issue1(ra, i, 0, smem, wave);
+#pragma unroll
+    for (int i = 0; i < CHUNKS; ++i) LB.issue1(rb, i, 0, smem + SLAB_BYTES, wave);
+    const __amdgpu_buffer_rsrc_t ra1 = LA.rsrc(nk > 1), rb1 = LB.rsrc(nk > 1);
+#pragma unroll
+    for (int i = 0; i < CHUNKS; ++i) LA.issue1(ra1, i, BK * 2, smem + STAGE_BYTES, wave);
+#pragma unroll
+    for (int i = 0; i < BH; ++i) LB.issue1(rb1, i, BK * 2, smem + STAGE_BYTES + SLAB_BYTES, wave);
+  }
+  asm volatile("s_waitcnt vmcnt(6)\n\ts_barrier" ::: "memory");   // all but the CHUNKS + BH newest
+  bq[0] = rdB(smem, 0);
+#pragma unroll
+  for (int i = 0; i < GM; ++i) a[0][i] = rdA(smem, 0, i);
+  bq[1] = rdB(smem, 1);
+
   for (int kt = 0; kt < nk; ++kt) {
     char* cur = smem + (kt & 1) * STAGE_BYTES;
     char* nxt = smem + ((kt + 1) & 1) * STAGE_BYTES;
-    if (kt + 1 < nk) {
-      LA.issue((uint32_t)(kt + 1) * (BK * 2), nxt, wave);
-      LB.issue((uint32_t)(kt + 1) * (BK * 2), nxt + SLAB_BYTES, wave);
+    const uint32_t kb1 = (uint32_t)(kt + 1) * (BK * 2), kb2 = (uint32_t)(kt + 2) * (BK * 2);
+    const __amdgpu_buffer_rsrc_t rb1 = LB.rsrc(kt + 1 < nk);
+    const __amdgpu_buffer_rsrc_t ra2 = LA.rsrc(kt + 2 < nk), rb2 = LB.rsrc(kt + 2 < nk);
+#pragma unroll
+    for (int s = 0; s < NS - TAIL; ++s) {
+      const int ks = s / GN, j = s % GN;
+      bq[(s + 2) & 3] = rdB(cur, s + 2);
+      if (s < GM) a[1][s] = rdA(cur, 1, s);
+      if (s < BH) LB.issue1(rb1, BH + s, kb1, nxt + SLAB_BYTES, wave);
+      if (s > XS && s <= XS + CHUNKS) LA.issue1(ra2, s - XS - 1, kb2, cur, wave);
+#pragma unroll
+      for (int i = 0; i < GM; ++i)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[ks][i], bq[s & 3], acc[i][j], 0, 0, 0);
+      // barrier X: all LDS reads but the newest one (a B fragment) are complete
+      if (s == XS) asm volatile("s_waitcnt lgkmcnt(1)\n\ts_barrier" ::: "memory");
+      __builtin_amdgcn_sched_barrier(0);   // keep this read/load/MFMA interleave as written
     }
-    {
-      // 16 steps (ks, j) of 4 MFMAs each: the A fragments of a 32-deep half stay resident, the B
-      // fragments stream through a 3-deep register queue fetched two steps ahead, and the A
-      // fragments of the second half arrive during the first.
-      const char* pa = cur + a_off;
-      const char* pb = cur + b_off;
-      bf16x8 a[2][GM], bq[3];
+    // barrier Y
+    asm volatile("s_waitcnt vmcnt(4) lgkmcnt(0)\n\ts_barrier" ::: "memory");
 #pragma unroll
-      for (int i = 0; i < GM; ++i) a[0][i] = *reinterpret_cast<const bf16x8*>(pa + i * (16 * 128) + koff[0]);
-      bq[0] = *reinterpret_cast<const bf16x8*>(pb + koff[0]);
-      bq[1] = *reinterpret_cast<const bf16x8*>(pb + (16 * 128) + koff[0]);
-#pragma unroll
-      for (int s = 0; s < 16; ++s) {
-        const int ks = s >> 3, j = s & 7;
-        if (s + 2 < 16)
-          bq[(s + 2) % 3] = *reinterpret_cast<const bf16x8*>(pb + ((s + 2) & 7) * (16 * 128) + koff[(s + 2) >> 3]);
-        if (s < GM)
-          a[1][s] = *reinterpret_cast<const bf16x8*>(pa + s * (16 * 128) + koff[1]);
-#pragma unroll
-        for (int i = 0; i < GM; ++i)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[ks][i], bq[s % 3], acc[i][j], 0, 0, 0);
-        __builtin_amdgcn_sched_barrier(0);   // keep this read/MFMA interleave as written
-      }
+    for (int m = 0; m < TAIL * GM; ++m) {
+      const int s = NS - TAIL + m / GM, i = m % GM;
+      const int ks = s / GN, j = s % GN;
+      if (m == 0) bq[0] = rdB(nxt, 0);
+      else if (m <= GM) a[0][m - 1] = rdA(nxt, 0, m - 1);
+      else if (m == GM + 1) bq[1] = rdB(nxt, 1);
+      if (m % GM == 0) LB.issue1(rb2, m / GM, kb2, cur + SLAB_BYTES, wave);
+      acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[ks][i], bq[s & 3], acc[i][j], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
     }
-    // my loads for the next stage have landed and my reads of this one are done
-    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
   }
+  asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
 // Row (m) index inside a 16x16 MFMA tile of accumulator register r for this lane;
