@@ -24,6 +24,22 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA peak (published)
 
+# L2<->fabric bytes per gemm_store_kernel launch from the FETCH_SIZE / WRITE_SIZE counter runs
+# summarised in profiles/gemm_store_kernel_hbm_traffic.md (mean over a step's 14 launches, each
+# counter scaled by what it reads for a plain 1 GiB copy).  Valid only for the kernel sources the
+# counters were taken with: the digest below is of csrc/gemm_core.h + csrc/kernels_gemm.hip.
+TRAFFIC_GEMM_STORE = {"read_bytes": 6202174.4 * 1024 * 2.000, "write_bytes": 655465.0 * 1024 * 1.000,
+                      "sources_sha256": "031e97470876e5dbc1bab75625d4386e56714c75f593e390a301a963ed3f6eeb"}
+
+
+def kernel_sources_digest() -> str:
+    import hashlib
+    h = hashlib.sha256()
+    for name in ("gemm_core.h", "kernels_gemm.hip"):
+        with open(os.path.join(ROOT, "paper_2602_05885_amd", "csrc", name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()
+
 
 def cpu_baseline(spec, rows: int):
     """Times the fp64 oracle (as it stands) on `rows` active rows at the full d and V."""
@@ -61,6 +77,9 @@ def main():
     ap.add_argument("--mismatch-mode", type=int, default=2)
     ap.add_argument("--cpu-rows", type=int, default=2048, help="rows of the oracle's timed sample (0 = skip)")
     ap.add_argument("--scale-rows", type=float, default=1.0, help="shrink the packed microbatch (debugging)")
+    ap.add_argument("--calib-copy-mib", type=int, default=0,
+                    help="also run three plain device-to-device copies of this size (the known-size reference "
+                         "that hardware-counter byte counts are scaled by)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only; --gpus must be 1 "
@@ -108,6 +127,14 @@ def main():
         return B.pg_loss_fwd_bwd(H, W, y, loss_mask, cu, adv.reshape(-1), seg_sample, old_logp, rollout_logp, prm, ws,
                                  dW=dW, out=outbuf)
 
+    if args.calib_copy_mib > 0:
+        src = torch.zeros(args.calib_copy_mib << 20, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     for _ in range(args.warmup):
         out = step()
     torch.cuda.synchronize()
@@ -146,7 +173,10 @@ def main():
     b = by_kernel[dom]
     achieved = b["flop"] / (b["ms"] * 1e-3) / 1e12
     roofline = {"bound": "mfma", "kernel": dom, "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None,
+                "frac": achieved / PEAK_BF16_TFLOPS,
+                "traffic": (TRAFFIC_GEMM_STORE["read_bytes"] + TRAFFIC_GEMM_STORE["write_bytes"]
+                            if dom == "gemm_store_kernel" and kernel_sources_digest() == TRAFFIC_GEMM_STORE["sources_sha256"]
+                            else None),
                 "flops_per_launch": b["flop"] / b["launches"], "avg_launch_ms": b["ms"] / b["launches"],
                 "launches_per_step": b["launches"]}
     executed = 8.0 * d * V * n_active / (ms_step * 1e-3) / 1e12   # logits twice, dH, dW
