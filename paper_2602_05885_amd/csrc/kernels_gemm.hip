@@ -22,7 +22,9 @@ __device__ __forceinline__ void merge_state(float& m, float& s, float& u, float 
   m = mm;
 }
 
-constexpr float NEG_BIG = -1.0e30f;   // finite stand-in for -inf: keeps 0 * (t - m) finite
+// Finite stand-in for -inf (keeps 0 * (t - m) finite).  A power of two, so that its product
+// with the logit scale is exact and "t - max" of an all-masked column is exactly zero.
+constexpr float NEG_BIG = -0x1p100f;
 
 // ------------------------------------------------------------------------------------
 // Forward: one workgroup = 256 vocab rows x 256 compacted tokens.  The logits live only in
@@ -53,22 +55,23 @@ __global__ __launch_bounds__(NTHREADS) void lmhead_fwd_kernel(FwdArgs a) {
   for (int j = 0; j < GN; ++j) {
     const int tok_l = wn * WCOLS + j * 16 + (lane & 15);
     const int tok = tn * BN + tok_l;
-    float mx = NEG_BIG;
+    // max over the raw accumulators (scale > 0 keeps the order); the scale goes on inside the fma
+    float mr = NEG_BIG;
 #pragma unroll
     for (int i = 0; i < GM; ++i)
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
-        float t = acc[i][j][r] * a.scale;
-        if (ragged && (v_base + i * 16 + acc_row(r, lane) >= a.V)) t = NEG_BIG;
-        acc[i][j][r] = t;
-        mx = fmaxf(mx, t);
+        if (ragged && (v_base + i * 16 + acc_row(r, lane) >= a.V)) acc[i][j][r] = NEG_BIG;
+        mr = fmaxf(mr, acc[i][j][r]);
       }
+    float mx = mr * a.scale;
+    const float nmx = -mx;
     float s = 0.f, u = 0.f;
 #pragma unroll
     for (int i = 0; i < GM; ++i)
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
-        const float dlt = acc[i][j][r] - mx;
+        const float dlt = fmaf(acc[i][j][r], a.scale, nmx);
         const float e = __builtin_amdgcn_exp2f(dlt);
         s += e;
         u = fmaf(e, dlt, u);
@@ -83,7 +86,7 @@ __global__ __launch_bounds__(NTHREADS) void lmhead_fwd_kernel(FwdArgs a) {
       for (int i = 0; i < GM; ++i)
 #pragma unroll
         for (int r = 0; r < 4; ++r)
-          if (yrel == i * 16 + acc_row(r, lane)) zy = acc[i][j][r];
+          if (yrel == i * 16 + acc_row(r, lane)) zy = acc[i][j][r] * a.scale;
       if (mine) a.zy[tok] = zy;
     }
     // the other three 16-lane groups hold the other vocab rows of the same token
@@ -202,17 +205,32 @@ __global__ __launch_bounds__(NTHREADS) void lmhead_dlogits_kernel(DlogitsArgs a)
   }
   __syncthreads();
   // ---- orientation 2: dS^T[v][tok], staged as rows of 256 tokens ----
+  // A quad of lanes holds a 4 (vocab rows) x 4 (tokens) block, one token per lane.  Two
+  // butterfly exchanges inside the quad turn it so that lane q holds row q of all four tokens,
+  // which then goes to LDS as one 8-byte store (instead of sixteen 2-byte ones per block).
+  {
+    const int q = lane & 3;
+    const uint32_t sel = (q & 1) ? 0x03020706u : 0x05040100u;   // v_perm byte selectors, see below
+    const bool upper = q >= 2;
+    const int row_l = wm * WROWS + ((lane >> 4) << 2) + q;
+    const int tok0_l = wn * WCOLS + (((lane & 15) >> 2) << 2);
 #pragma unroll
-  for (int j = 0; j < GN; ++j) {
-    const int tok_l = wn * WCOLS + j * 16 + (lane & 15);
+    for (int j = 0; j < GN; ++j) {
 #pragma unroll
-    for (int i = 0; i < GM; ++i)
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const int v_l = wm * WROWS + i * 16 + acc_row(r, lane);
-        const uint32_t w = pk[i][j][r >> 1];
-        *reinterpret_cast<uint16_t*>(st + v_l * EPI_STRIDE + tok_l * 2) = (uint16_t)((r & 1) ? (w >> 16) : w);
+      for (int i = 0; i < GM; ++i) {
+        const uint32_t w0 = pk[i][j][0], w1 = pk[i][j][1];        // rows (0,1), (2,3) of my token
+        // neighbour in the lane pair: even lanes keep the even row of both tokens, odd lanes the odd row
+        const uint32_t p0 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)w0, 0xB1, 0xf, 0xf, false);
+        const uint32_t p1 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)w1, 0xB1, 0xf, 0xf, false);
+        const uint32_t x0 = __builtin_amdgcn_perm(p0, w0, sel);   // row (q&1),   tokens of my pair
+        const uint32_t x1 = __builtin_amdgcn_perm(p1, w1, sel);   // row 2+(q&1), tokens of my pair
+        // other pair of the quad: lanes 0,1 collect rows 0,1 and lanes 2,3 rows 2,3 of all four tokens
+        const uint32_t send = upper ? x0 : x1;
+        const uint32_t recv = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)send, 0x4E, 0xf, 0xf, false);
+        const uint2 two = upper ? make_uint2(recv, x1) : make_uint2(x0, recv);
+        *reinterpret_cast<uint2*>(st + (row_l + i * 16) * EPI_STRIDE_T + (tok0_l + j * 16) * 2) = two;
       }
+    }
   }
   __syncthreads();
   {
@@ -221,7 +239,7 @@ __global__ __launch_bounds__(NTHREADS) void lmhead_dlogits_kernel(DlogitsArgs a)
 #pragma unroll 4
     for (int ps = 0; ps < 256 / (NTHREADS / 32); ++ps) {
       const int row = r0 + ps * (NTHREADS / 32);
-      const i32x4 v = *reinterpret_cast<const i32x4*>(st + row * EPI_STRIDE + chunk * 16);
+      const i32x4 v = *reinterpret_cast<const i32x4*>(st + row * EPI_STRIDE_T + chunk * 16);
       __builtin_nontemporal_store(v, reinterpret_cast<i32x4*>(dst + (size_t)row * a.ld_t));
     }
   }
@@ -260,7 +278,7 @@ __global__ __launch_bounds__(NTHREADS) void gemm_store_kernel(StoreArgs a) {
   const Ctl ctl = *a.ctl;
   int tm, tn;
   const int m_lim = a.m_from_ctl ? min(a.M, ctl.n_pad) : a.M;
-  if (!map_tile(blockIdx.x, min(a.tiles_m, (m_lim + BM - 1) / BM), a.tiles_n, tm, tn)) return;
+  if (!map_tile_interleaved(blockIdx.x, min(a.tiles_m, (m_lim + BM - 1) / BM), a.tiles_n, tm, tn)) return;
   const int K = a.k_from_ctl ? ctl.n_pad : a.K;
 
   const int tid = threadIdx.x;

@@ -338,24 +338,38 @@ void launch_transpose_w(const void* W, int is_f32, int64_t V, int d, int v0, int
 }
 
 // ------------------------------------------------------------------ combine + surrogate
-// One thread per compacted row: merges the per-vocab-tile softmax partials (two sweeps: the
-// global max first, then the rescaled sums), emits log-prob / entropy / logsumexp, and for
-// the loss call evaluates the clipped surrogate and the coefficient that scales
-// (onehot - softmax) in the backward.
+// Merges the per-vocab-tile softmax partials of every compacted row with the online merge rule
+// (m, s, u) + (m2, s2, u2), emits log-prob / entropy / logsumexp, and for the loss call evaluates
+// the clipped surrogate and the coefficient that scales (onehot - softmax) in the backward.
 __global__ __launch_bounds__(256) void combine_kernel(CombineArgs a) {
+  // 64 tokens per workgroup; the four wavefronts each merge every fourth vocab tile's partial
+  // state (online, fixed order), then wavefront 0 merges the four results and finishes the row.
+  __shared__ float sh[3][3][64];
   const Ctl ctl = *a.ctl;
-  const int i = blockIdx.x * 256 + threadIdx.x;
-  if (i >= ctl.n_pad) return;
-  float M = a.part_m[i];
-  for (int k = 1; k < a.tiles_v; ++k) M = fmaxf(M, a.part_m[(size_t)k * a.t_cap + i]);
-  float s = 0.f, u = 0.f;
-  for (int k = 0; k < a.tiles_v; ++k) {
+  const int lane = threadIdx.x & 63, part = threadIdx.x >> 6;
+  const int i = blockIdx.x * 64 + lane;
+  if (blockIdx.x * 64 >= ctl.n_pad) return;      // whole workgroup beyond the padded rows
+  float M = -1.0e30f, s = 0.f, u = 0.f;
+  for (int k = part; k < a.tiles_v; k += 4) {
     const size_t o = (size_t)k * a.t_cap + i;
-    const float dm = a.part_m[o] - M;
-    const float w = __builtin_amdgcn_exp2f(dm);
-    const float sk = a.part_s[o];
-    s = fmaf(w, sk, s);
-    u = fmaf(w, fmaf(dm, sk, a.part_u[o]), u);
+    const float m2 = a.part_m[o], s2 = a.part_s[o], u2 = a.part_u[o];
+    const float mm = fmaxf(M, m2);
+    const float a1 = __builtin_amdgcn_exp2f(M - mm), a2 = __builtin_amdgcn_exp2f(m2 - mm);
+    u = a1 * (u + (M - mm) * s) + a2 * (u2 + (m2 - mm) * s2);
+    s = a1 * s + a2 * s2;
+    M = mm;
+  }
+  if (part > 0) { sh[part - 1][0][lane] = M; sh[part - 1][1][lane] = s; sh[part - 1][2][lane] = u; }
+  __syncthreads();
+  if (part > 0) return;
+#pragma unroll
+  for (int w = 0; w < 3; ++w) {
+    const float m2 = sh[w][0][lane], s2 = sh[w][1][lane], u2 = sh[w][2][lane];
+    const float mm = fmaxf(M, m2);
+    const float a1 = __builtin_amdgcn_exp2f(M - mm), a2 = __builtin_amdgcn_exp2f(m2 - mm);
+    u = a1 * (u + (M - mm) * s) + a2 * (u2 + (m2 - mm) * s2);
+    s = a1 * s + a2 * s2;
+    M = mm;
   }
   const float log2s = __builtin_amdgcn_logf(s);     // v_log_f32: log2
   const float lse2 = M + log2s;
@@ -384,7 +398,7 @@ __global__ __launch_bounds__(256) void combine_kernel(CombineArgs a) {
   a.lossterm[i] = c * l;
 }
 void launch_combine(const CombineArgs& a, hipStream_t s) {
-  hipLaunchKernelGGL(combine_kernel, dim3(a.t_cap / 256), dim3(256), 0, s, a);
+  hipLaunchKernelGGL(combine_kernel, dim3(a.t_cap / 64), dim3(256), 0, s, a);
 }
 
 // Single workgroup, fixed order, fp64: loss = (sum_t c_t l_t) / norm; publishes the counters.
