@@ -15,6 +15,16 @@ What follows the paper directly
   * gradient direction      -- App. A: grad of log pi(y|s) times the advantage;
                                for a softmax head d log pi(y) / d z = onehot - p.
 
+Stages around the path (Sec. 3.3, 4.2, 5.1, 5.2 and App. ablations)
+  * cold-start SFT loss     -- Sec. 3.3: token-mean cross-entropy of the same head
+                               (the paper names the stage, the loss is the textbook one)
+  * rewards                 -- Eq. (1) speedup reward with the cap of 3, Eq. (7) with the
+                               profiling ratio PR = T_generated / T_total added
+  * PRS                     -- Eq. (8): keep with probability clip((PR - tau) / s, 0, 1),
+                               and the hard-threshold variant of the PRS ablation
+  * monitors                -- Sec. 5.1: entropy, gradient norm and the perplexities of the
+                               trainer's and the rollout engine's log-probs
+
 What the paper does not write down and is fixed here by definition (each is a
 stated reading, "parity unpinned" beyond self-consistency): the PPO-style
 clipped surrogate and its epsilon, token-mean normalisation, the truncated
@@ -318,3 +328,129 @@ def dH_rows(H_rows, W, y_rows, coef_rows, tau: float):
     dS = -p * k[:, None]
     dS[np.arange(len(k)), np.asarray(y_rows, np.int64)] += k
     return dS @ np.asarray(W, np.float64)
+
+
+# --------------------------------------------------------------------------
+# Sec. 3.3 (cold-start SFT): token-mean cross-entropy of the LM head on the loss
+# tokens, L = -(1/norm) sum_t m_t log softmax(z_t)[y_t], and its gradients
+# dS = (softmax - onehot) / (norm tau), dH = dS W, dW = dS^T H.
+# --------------------------------------------------------------------------
+def sft_ce_fwd_bwd(H, W, y, loss_mask, tau: float = 1.0, norm_override: float = 0.0,
+                   dW_prev=None, block: int = 256):
+    H = np.asarray(H, dtype=np.float64)
+    W = np.asarray(W, dtype=np.float64)
+    y = np.asarray(y, dtype=np.int64)
+    T, d = H.shape
+    V = W.shape[0]
+    tau = _f32(tau)
+    act = np.asarray(loss_mask).astype(bool)
+    n = int(act.sum())
+    norm = _f32(norm_override) if norm_override > 0 else float(max(1, n))
+    logp = np.zeros(T)
+    ent = np.zeros(T)
+    dH = np.zeros((T, d))
+    dW = np.zeros((V, d)) if dW_prev is None else np.array(dW_prev, dtype=np.float64)
+    total = 0.0
+    rows = np.nonzero(act)[0]
+    for a in range(0, len(rows), block):
+        r_ = rows[a:a + block]
+        z = logits(H[r_], W, tau)
+        lp, en, _, p = logprob_entropy_from_logits(z, y[r_])
+        logp[r_], ent[r_] = lp, en
+        total += float(-lp.sum())
+        dS = p / (norm * tau)
+        dS[np.arange(len(r_)), y[r_]] -= 1.0 / (norm * tau)
+        dH[r_] = dS @ W
+        dW += dS.T @ H[r_]
+    return dict(loss=total / norm, dH=dH, dW=dW, logp=logp, entropy=ent, n=n, norm=norm)
+
+
+# --------------------------------------------------------------------------
+# Sec. 5.2, Eq. (6)-(7): profiling ratio PR = T_generated / T_total and the reward
+#   R = C + C * min(T_reference / T_kernel, cap) + C * PR      (PR term optional)
+# Times of incorrect kernels are irrelevant (C = 0 zeroes every term).
+# --------------------------------------------------------------------------
+def profiling_ratio(t_generated, t_total) -> np.ndarray:
+    return np.asarray(t_generated, np.float64) / np.asarray(t_total, np.float64)
+
+
+def turn_reward(correct, t_reference, t_kernel, t_generated=None, t_total=None, cap: float = 3.0):
+    C = (np.asarray(correct) != 0).astype(np.float64)
+    speedup = np.minimum(np.asarray(t_reference, np.float64) / np.asarray(t_kernel, np.float64), _f32(cap))
+    R = np.where(C > 0, 1.0 + speedup, 0.0)
+    pr = np.zeros_like(R)
+    if t_generated is not None:
+        pr = np.where(C > 0, profiling_ratio(t_generated, t_total), 0.0)
+        R = R + pr
+    return R, pr
+
+
+# --------------------------------------------------------------------------
+# Sec. 5.2, Eq. (8): PRS retention probability, and the Bernoulli draw.
+# The draw uses one Philox4x32-10 block per sample (Salmon et al., SC'11):
+# counter = (index, 0, 0, 0), key = (seed_lo, seed_hi); u = (x0 + 0.5) / 2^32;
+# keep iff u < p.  The hard-threshold variant of the PRS ablation keeps iff PR >= tau.
+# --------------------------------------------------------------------------
+def prs_probability(pr, tau: float = 0.3, s: float = 0.1) -> np.ndarray:
+    pr = np.asarray(pr, np.float64)
+    return np.clip((pr - _f32(tau)) / _f32(s), 0.0, 1.0)
+
+
+_PHILOX_M0, _PHILOX_M1 = 0xD2511F53, 0xCD9E8D57
+_PHILOX_W0, _PHILOX_W1 = 0x9E3779B9, 0xBB67AE85
+
+
+def philox4x32_10(counter, key):
+    """One block of Philox-4x32 with 10 rounds; counter: 4 words, key: 2 words (Python ints)."""
+    c0, c1, c2, c3 = (int(x) & 0xFFFFFFFF for x in counter)
+    k0, k1 = (int(x) & 0xFFFFFFFF for x in key)
+    for _ in range(10):
+        p0 = _PHILOX_M0 * c0
+        p1 = _PHILOX_M1 * c2
+        hi0, lo0 = p0 >> 32, p0 & 0xFFFFFFFF
+        hi1, lo1 = p1 >> 32, p1 & 0xFFFFFFFF
+        c0, c1, c2, c3 = (hi1 ^ c1 ^ k0) & 0xFFFFFFFF, lo1, (hi0 ^ c3 ^ k1) & 0xFFFFFFFF, lo0
+        k0 = (k0 + _PHILOX_W0) & 0xFFFFFFFF
+        k1 = (k1 + _PHILOX_W1) & 0xFFFFFFFF
+    return c0, c1, c2, c3
+
+
+def prs_uniform(index: int, seed: int) -> float:
+    x0 = philox4x32_10((index & 0xFFFFFFFF, (index >> 32) & 0xFFFFFFFF, 0, 0),
+                       (seed & 0xFFFFFFFF, (seed >> 32) & 0xFFFFFFFF))[0]
+    return (x0 + 0.5) / 4294967296.0
+
+
+def prs_retain(pr, valid, seed: int, tau: float = 0.3, s: float = 0.1, hard: bool = False):
+    """keep[i] (uint8) and p[i]; invalid samples (turn never generated) are not kept."""
+    pr = np.asarray(pr, np.float64).reshape(-1)
+    valid = np.asarray(valid).reshape(-1).astype(bool)
+    p = prs_probability(pr, tau, s)
+    keep = np.zeros(pr.shape[0], np.uint8)
+    for i in range(pr.shape[0]):
+        if not valid[i]:
+            continue
+        if hard:
+            keep[i] = 1 if pr[i] >= _f32(tau) else 0
+        else:
+            keep[i] = 1 if prs_uniform(i, seed) < p[i] else 0
+    return keep, p
+
+
+# --------------------------------------------------------------------------
+# Sec. 5.1 monitors over the loss tokens of a microbatch: mean entropy, perplexity
+# exp(-mean logp) of the trainer's and of the rollout engine's log-probs, and the
+# Euclidean norms of the head's gradients.
+# --------------------------------------------------------------------------
+def monitors(logp_train, logp_rollout, entropy, loss_mask, dH=None, dW=None):
+    m = np.asarray(loss_mask).astype(bool)
+    n = int(m.sum())
+    den = float(max(1, n))
+    out = dict(n=n)
+    out["entropy_mean"] = float(np.asarray(entropy, np.float64)[m].sum() / den) if entropy is not None else 0.0
+    out["ppl_train"] = float(np.exp(-np.asarray(logp_train, np.float64)[m].sum() / den))
+    out["ppl_rollout"] = (float(np.exp(-np.asarray(logp_rollout, np.float64)[m].sum() / den))
+                          if logp_rollout is not None else 0.0)
+    out["dH_norm"] = float(np.sqrt((np.asarray(dH, np.float64) ** 2).sum())) if dH is not None else 0.0
+    out["dW_norm"] = float(np.sqrt((np.asarray(dW, np.float64) ** 2).sum())) if dW is not None else 0.0
+    return out

@@ -1,0 +1,166 @@
+"""Pins for the oracle's stages around the path: SFT cross-entropy (Sec. 3.3), rewards with the
+profiling ratio (Sec. 4.2 Eq. 1, Sec. 5.2 Eq. 6-7), PRS (Eq. 8) and the monitors (Sec. 5.1).  CPU only."""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import pg_oracle as O
+
+
+def _rows(golden_dir, name):
+    return [l.split() for l in open(os.path.join(golden_dir, name)) if l.strip() and not l.startswith("#")]
+
+
+# ---------------------------------------------------------------- SFT cross-entropy
+def _sft_problem(seed=0, T=37, d=24, V=53):
+    rng = np.random.default_rng(seed)
+    H = rng.normal(size=(T, d))
+    W = rng.normal(size=(V, d)) * 0.3
+    y = rng.integers(0, V, size=T)
+    mask = (rng.random(T) < 0.7).astype(np.uint8)
+    return H, W, y, mask
+
+
+@pytest.mark.parametrize("tau", [1.0, 0.7])
+def test_sft_matches_library_cross_entropy_autograd(tau):
+    H, W, y, mask = _sft_problem()
+    out = O.sft_ce_fwd_bwd(H, W, y, mask, tau)
+    Ht = torch.tensor(H, dtype=torch.float64, requires_grad=True)
+    Wt = torch.tensor(W, dtype=torch.float64, requires_grad=True)
+    z = (Ht @ Wt.T) / float(np.float32(tau))
+    m = torch.tensor(mask.astype(bool))
+    loss = torch.nn.functional.cross_entropy(z[m], torch.tensor(y)[m], reduction="mean")
+    loss.backward()
+    assert abs(out["loss"] - loss.item()) < 1e-12
+    np.testing.assert_allclose(out["dH"], Ht.grad.numpy(), atol=1e-13)
+    np.testing.assert_allclose(out["dW"], Wt.grad.numpy(), atol=1e-13)
+    assert np.all(out["dH"][mask == 0] == 0)
+    assert np.all(out["logp"][mask == 0] == 0)
+
+
+def test_sft_zero_weights_is_log_vocab():
+    H, W, y, mask = _sft_problem(1)
+    out = O.sft_ce_fwd_bwd(H, np.zeros_like(W), y, mask)
+    assert abs(out["loss"] - np.log(W.shape[0])) < 1e-12
+    np.testing.assert_allclose(out["entropy"][mask != 0], np.log(W.shape[0]), atol=1e-12)
+
+
+def test_sft_norm_override_and_accumulate():
+    H, W, y, mask = _sft_problem(2)
+    a = O.sft_ce_fwd_bwd(H, W, y, mask)
+    n = int(mask.sum())
+    b = O.sft_ce_fwd_bwd(H, W, y, mask, norm_override=2.0 * n)
+    np.testing.assert_allclose(b["dW"], a["dW"] / 2, atol=1e-14)
+    assert abs(b["loss"] - a["loss"] / 2) < 1e-14
+    prev = np.full_like(W, 0.25)
+    c = O.sft_ce_fwd_bwd(H, W, y, mask, dW_prev=prev)
+    np.testing.assert_allclose(c["dW"], a["dW"] + 0.25, atol=1e-14)
+
+
+def test_sft_is_policy_gradient_with_unit_advantage():
+    """App. A: with A = 1 on every token and r = 1 the estimator's gradient is that of -mean log pi."""
+    H, W, y, mask = _sft_problem(3)
+    T = H.shape[0]
+    cu = np.array([0, T // 2, T], dtype=np.int32)
+    pg = O.pg_loss_fwd_bwd(H, W, y, mask, cu, np.ones(2), None, None, O.Params())
+    sft = O.sft_ce_fwd_bwd(H, W, y, mask)
+    np.testing.assert_allclose(pg["dW"], sft["dW"], atol=1e-14)
+    np.testing.assert_allclose(pg["dH"], sft["dH"], atol=1e-14)
+
+
+def test_sft_all_masked():
+    H, W, y, mask = _sft_problem(4)
+    out = O.sft_ce_fwd_bwd(H, W, y, np.zeros_like(mask))
+    assert out["loss"] == 0.0 and not out["dW"].any() and not out["dH"].any()
+
+
+# ---------------------------------------------------------------- rewards with the profiling ratio
+def test_turn_reward_reduces_to_eq1(golden_dir):
+    rows = np.array(_rows(golden_dir, "layernorm_case_rewards.txt"), dtype=np.float64)
+    speed, R_exp = rows[:, 1], rows[:, 2]
+    # speedup = T_reference / T_kernel: take T_kernel = 1
+    R, pr = O.turn_reward(np.ones(3), speed, np.ones(3))
+    np.testing.assert_allclose(R, R_exp, atol=1e-12)
+    assert not pr.any()
+
+
+def test_turn_reward_cap_incorrect_and_pr(golden_dir):
+    consts = {r[0]: float(r[1]) for r in _rows(golden_dir, "paper_constants.txt")}
+    cap = consts["speedup_cap"]
+    correct = np.array([1, 1, 0, 1])
+    t_ref = np.array([10.0, 9.0, 5.0, 2.0])
+    t_ker = np.array([1.0, 3.0, 1.0, 4.0])           # speedups 10 (capped), 3, -, 0.5
+    t_gen = np.array([0.5, 0.25, 0.9, 1.0])
+    t_tot = np.array([1.0, 1.0, 1.0, 1.0])
+    R, pr = O.turn_reward(correct, t_ref, t_ker, t_gen, t_tot, cap)
+    np.testing.assert_allclose(R, [1 + 3 + 0.5, 1 + 3 + 0.25, 0.0, 1 + 0.5 + 1.0], atol=1e-12)
+    np.testing.assert_allclose(pr, [0.5, 0.25, 0.0, 1.0])
+    # PR lies in [0, 1], so the capped speedup term (<= 3) dominates it (Sec. 5.2)
+    R0, _ = O.turn_reward(correct, t_ref, t_ker, None, None, cap)
+    assert np.all(R - R0 >= 0) and np.all(R - R0 <= 1)
+
+
+# ---------------------------------------------------------------- PRS
+def test_prs_probability_paper_values(golden_dir):
+    consts = {r[0]: float(r[1]) for r in _rows(golden_dir, "paper_constants.txt")}
+    tau, s = consts["prs_tau"], consts["prs_s"]
+    for name, pr, p in _rows(golden_dir, "profiling_case.txt"):
+        assert abs(O.prs_probability(float(pr), tau, s) - float(p)) < 1e-12
+    # the soft band [0.3, 0.4): linear from 0 to 1
+    np.testing.assert_allclose(O.prs_probability([0.3, 0.325, 0.35, 0.4, 0.41], tau, s), [0, 0.25, 0.5, 1, 1], atol=1e-6)
+
+
+def test_philox_known_answers(golden_dir):
+    for r in _rows(golden_dir, "philox4x32_10_kat.txt"):
+        w = [int(x, 16) for x in r]
+        assert list(O.philox4x32_10(w[0:4], w[4:6])) == w[6:10]
+
+
+def test_prs_retain_extremes_and_hard_variant():
+    # PR crosses the C boundary as float32, and so do tau and s: use those values here too
+    pr = np.array([0.0, 0.29, 0.3, 0.35, 0.39999, 0.4, 0.9, 0.9], dtype=np.float32)
+    valid = np.array([1, 1, 1, 1, 1, 1, 1, 0])
+    keep, p = O.prs_retain(pr, valid, seed=1234)
+    assert keep[0] == 0 and keep[1] == 0 and keep[2] == 0      # p = 0 is never kept
+    assert keep[5] == 1 and keep[6] == 1                       # p = 1 is always kept
+    assert keep[7] == 0                                        # never generated: not kept
+    hard, _ = O.prs_retain(pr, valid, seed=1234, hard=True)
+    np.testing.assert_array_equal(hard, [0, 0, 1, 1, 1, 1, 1, 0])
+
+
+def test_prs_retain_rate_and_determinism():
+    n = 20000
+    pr = np.full(n, 0.35)                                       # p = 0.5
+    keep, p = O.prs_retain(pr, np.ones(n), seed=7)
+    assert abs(p[0] - 0.5) < 1e-6
+    assert abs(keep.mean() - 0.5) < 0.015                       # 4 sigma of a fair coin over 20000
+    keep2, _ = O.prs_retain(pr, np.ones(n), seed=7)
+    np.testing.assert_array_equal(keep, keep2)
+    keep3, _ = O.prs_retain(pr, np.ones(n), seed=8)
+    assert (keep != keep3).mean() > 0.4                         # another seed, another draw
+    # monotone coupling: the same uniform decides every threshold
+    keep_hi, _ = O.prs_retain(np.full(n, 0.38), np.ones(n), seed=7)
+    assert np.all(keep_hi >= keep)
+
+
+# ---------------------------------------------------------------- monitors
+def test_monitors_closed_forms():
+    V, T = 1000, 64
+    rng = np.random.default_rng(0)
+    mask = (rng.random(T) < 0.6).astype(np.uint8)
+    logp = np.full(T, -np.log(V))
+    ent = np.full(T, np.log(V))
+    dH = rng.normal(size=(T, 8))
+    dW = rng.normal(size=(V, 8))
+    m = O.monitors(logp, logp + np.log(2.0), ent, mask, dH, dW)
+    assert abs(m["ppl_train"] - V) < 1e-9                       # uniform policy: perplexity = V
+    assert abs(m["ppl_rollout"] - V / 2) < 1e-9
+    assert abs(m["entropy_mean"] - np.log(V)) < 1e-12
+    assert abs(m["dH_norm"] - np.linalg.norm(dH)) < 1e-12
+    assert abs(m["dW_norm"] - np.linalg.norm(dW)) < 1e-12
+    assert m["n"] == int(mask.sum())
+    # masked tokens do not count
+    logp2 = logp.copy(); logp2[mask == 0] = -50.0
+    assert abs(O.monitors(logp2, None, None, mask)["ppl_train"] - V) < 1e-9
