@@ -11,6 +11,15 @@
  *   pg_loss_fwd_bwd   mismatch correction (Sec. 5.1), clipped surrogate whose gradient is
  *                     grad log pi * A (App. A), backward to dH and dW
  *
+ * and the small stages around that path:
+ *
+ *   pg_sft_fwd_bwd    token-mean cross-entropy of the same head, forward and backward
+ *                     (the cold-start SFT stage of Sec. 3.3)
+ *   grpo_advantage    turn returns and group-mean advantages          (Sec. 4.2, Eq. 2 and 3)
+ *   turn_reward       per-turn reward with speedup cap and profiling ratio (Eq. 1, Eq. 6-7)
+ *   prs_retain        profiling-based rejection sampling               (Sec. 5.2, Eq. 8)
+ *   pg_monitors       entropy, perplexities and gradient norms         (Sec. 5.1)
+ *
  * Conventions
  *   - Every pointer is a DEVICE pointer unless its name starts with h_ (pg_params is
  *     passed by host pointer).  The caller owns all buffers; the library allocates
@@ -153,6 +162,77 @@ int32_t pg_loss_fwd_bwd(const void* H, const void* W, const int32_t* y, const ui
                         int64_t T, int64_t d, int64_t V, const pg_params* h_params, float* loss_out,
                         void* dH, void* dW, float* logp_out, float* entropy_out, int64_t* counters_out,
                         void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Cold-start SFT (Sec. 3.3): token-mean cross-entropy of the head over the rows with
+ * loss_mask[t] != 0,
+ *   loss = -(1/norm) sum_t log softmax(H_t W^T / tau)[y_t],   dS = (softmax_t - onehot(y_t)) / (norm tau),
+ *   dH = dS W (0 on masked rows), dW = dS^T H (added to dW if accumulate_dW).
+ * Of pg_params only dtype, temperature, norm_override, accumulate_dW and dW_dtype are used.
+ * Outputs, workspace (pg_workspace_bytes with PG_CALL_LOSS_FWD_BWD, any S) and error behaviour
+ * as for pg_loss_fwd_bwd; counters_out[PG_CNT_ACTIVE] = counters_out[PG_CNT_LOSS_TOKENS] = the
+ * number of loss rows, the other counters are 0.
+ */
+int32_t pg_sft_fwd_bwd(const void* H, const void* W, const int32_t* y, const uint8_t* loss_mask, int64_t T,
+                       int64_t d, int64_t V, const pg_params* h_params, float* loss_out, void* dH, void* dW,
+                       float* logp_out, float* entropy_out, int64_t* counters_out, void* workspace,
+                       size_t workspace_bytes, void* stream);
+
+/*
+ * Sec. 4.2, Eq. (2) and Eq. (3): as trloo_advantage, but with the group-mean baseline the paper
+ * compares against, A = G - mean of the valid rollouts' G of the same prompt and turn (own
+ * return included); 0 for invalid entries.
+ */
+int32_t grpo_advantage(const float* rewards, const uint8_t* valid, int32_t P, int32_t K, int32_t Tmax,
+                       float gamma, double* returns_out, double* adv_out, int32_t* group_n_out,
+                       void* stream);
+
+/*
+ * Sec. 4.2, Eq. (1) and Sec. 5.2, Eq. (6)-(7), for n samples (one sample = one turn of one rollout):
+ *   speedup = min(t_reference / t_kernel, speedup_cap)        (the paper's cap is 3)
+ *   PR      = t_generated / t_total                            (only if both are given)
+ *   reward  = C + C speedup + C PR,   C = (correct != 0)
+ * correct [n] uint8, times [n] float32 (> 0 where correct; ignored where not), t_generated and
+ * t_total both NULL = Eq. (1) without the PR term.  rewards_out [n] float32; pr_out [n] float32
+ * (nullable) receives C * PR.  Arithmetic is fp64, results are rounded to float32.
+ */
+int32_t turn_reward(const uint8_t* correct, const float* t_reference, const float* t_kernel,
+                    const float* t_generated, const float* t_total, int64_t n, float speedup_cap,
+                    float* rewards_out, float* pr_out, void* stream);
+
+/*
+ * Sec. 5.2, Eq. (8): sample i is retained with probability p_i = clip((pr_i - tau) / s, 0, 1)
+ * (the paper's tau = 0.3, s = 0.1), or, with hard != 0, iff pr_i >= tau (the ablation without
+ * softness).  The draw is reproducible: u_i = (x + 0.5) / 2^32 with x the first output word of
+ * Philox-4x32-10 at counter (i mod 2^32, i div 2^32, 0, 0) and key (seed mod 2^32, seed div 2^32);
+ * keep_i = u_i < p_i, decided in fp64.  valid (nullable) = 0 marks samples that were never
+ * generated: they are not kept.  keep_out [n] uint8, p_out [n] float32 (nullable).  s > 0.
+ */
+int32_t prs_retain(const float* pr, const uint8_t* valid, int64_t n, float tau, float s, int32_t hard,
+                   uint64_t seed, uint8_t* keep_out, float* p_out, void* stream);
+
+/*
+ * Sec. 5.1 monitors over the rows with loss_mask[t] != 0 (n of them):
+ *   out[PG_MON_ENTROPY]      (1/n) sum entropy[t]                 (0 if entropy is NULL)
+ *   out[PG_MON_PPL_TRAIN]    exp(-(1/n) sum logp_train[t])
+ *   out[PG_MON_PPL_ROLLOUT]  exp(-(1/n) sum logp_rollout[t])       (0 if logp_rollout is NULL)
+ *   out[PG_MON_DH_NORM]      Euclidean norm of dH [dH_elems]       (0 if dH is NULL)
+ *   out[PG_MON_DW_NORM]      Euclidean norm of dW [dW_elems]       (0 if dW is NULL)
+ *   out[PG_MON_TOKENS]       n
+ * (n = 0 divides by 1.)  out is fp64 [8] in device memory.  dH_dtype / dW_dtype: 0 bf16, 1 fp32.
+ * Sums are fp64 in a fixed order (bitwise repeatable).  workspace: pg_monitors_workspace_bytes().
+ */
+#define PG_MON_ENTROPY 0
+#define PG_MON_PPL_TRAIN 1
+#define PG_MON_PPL_ROLLOUT 2
+#define PG_MON_DH_NORM 3
+#define PG_MON_DW_NORM 4
+#define PG_MON_TOKENS 5
+size_t pg_monitors_workspace_bytes(void);
+int32_t pg_monitors(const float* logp_train, const float* logp_rollout, const float* entropy,
+                    const uint8_t* loss_mask, int64_t T, const void* dH, int32_t dH_dtype, int64_t dH_elems,
+                    const void* dW, int32_t dW_dtype, int64_t dW_elems, double* out, void* workspace,
+                    size_t workspace_bytes, void* stream);
 
 /*
  * Measurement hooks (host-side state, not thread-safe; the only calls that create HIP events

@@ -22,7 +22,9 @@ CALL_LOSS_FWD_BWD = 1
 COUNTER_NAMES = ("active", "clip_hi", "clip_lo", "seg_geo", "seg_veto", "truncated", "loss_tokens", "reserved")
 
 EXPORTS = ("pg_last_error", "pg_workspace_bytes", "trloo_advantage", "pg_logprob_fwd", "pg_loss_fwd_bwd",
-           "pg_profile_enable", "pg_profile_read")
+           "pg_sft_fwd_bwd", "grpo_advantage", "turn_reward", "prs_retain", "pg_monitors_workspace_bytes",
+           "pg_monitors", "pg_profile_enable", "pg_profile_read")
+MONITOR_NAMES = ("entropy_mean", "ppl_train", "ppl_rollout", "dH_norm", "dW_norm", "n")
 KERNEL_CLASSES = ("fwd", "dlogits", "dw", "dh")
 
 
@@ -87,6 +89,24 @@ def lib() -> C.CDLL:
                                       C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int64,
                                       C.c_int64, C.POINTER(PgParams), C.c_void_p, C.c_void_p, C.c_void_p,
                                       C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.pg_sft_fwd_bwd.restype = C.c_int32
+        L.pg_sft_fwd_bwd.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_int64,
+                                     C.POINTER(PgParams), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                     C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.grpo_advantage.restype = C.c_int32
+        L.grpo_advantage.argtypes = L.trloo_advantage.argtypes
+        L.turn_reward.restype = C.c_int32
+        L.turn_reward.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_float,
+                                  C.c_void_p, C.c_void_p, C.c_void_p]
+        L.prs_retain.restype = C.c_int32
+        L.prs_retain.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_float, C.c_float, C.c_int32, C.c_uint64,
+                                 C.c_void_p, C.c_void_p, C.c_void_p]
+        L.pg_monitors_workspace_bytes.restype = C.c_size_t
+        L.pg_monitors_workspace_bytes.argtypes = []
+        L.pg_monitors.restype = C.c_int32
+        L.pg_monitors.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_int32,
+                                  C.c_int64, C.c_void_p, C.c_int32, C.c_int64, C.c_void_p, C.c_void_p, C.c_size_t,
+                                  C.c_void_p]
         L.pg_profile_enable.restype = C.c_int32
         L.pg_profile_enable.argtypes = [C.c_int32, C.c_int32]
         L.pg_profile_read.restype = C.c_int32
@@ -155,6 +175,63 @@ def trloo_advantage(rewards: torch.Tensor, valid: torch.Tensor, gamma: float = 1
     return adv, ret, gn
 
 
+def grpo_advantage(rewards: torch.Tensor, valid: torch.Tensor, gamma: float = 1.0, want_returns=True,
+                   want_group_n=True, stream=None):
+    """As trloo_advantage, with the group-mean baseline of Eq. (3)."""
+    P, K, Tm = rewards.shape
+    assert rewards.dtype == torch.float32 and valid.dtype == torch.uint8 and valid.shape == rewards.shape
+    adv = torch.empty((P, K, Tm), dtype=torch.float64, device=rewards.device)
+    ret = torch.empty_like(adv) if want_returns else None
+    gn = torch.empty((P, Tm), dtype=torch.int32, device=rewards.device) if want_group_n else None
+    _check(lib().grpo_advantage(_ptr(rewards), _ptr(valid), P, K, Tm, gamma, _ptr(ret), _ptr(adv), _ptr(gn),
+                                _stream(stream)))
+    return adv, ret, gn
+
+
+def turn_reward(correct, t_reference, t_kernel, t_generated=None, t_total=None, speedup_cap: float = 3.0,
+                want_pr=True, stream=None):
+    """correct uint8 [n], times float32 [n] (device).  Returns (rewards f32 [n], C*PR f32 [n] | None)."""
+    n = correct.numel()
+    assert correct.dtype == torch.uint8
+    for t in (t_reference, t_kernel, t_generated, t_total):
+        assert t is None or (t.dtype == torch.float32 and t.numel() == n)
+    R = torch.empty(n, dtype=torch.float32, device=correct.device)
+    pr = torch.empty(n, dtype=torch.float32, device=correct.device) if want_pr else None
+    _check(lib().turn_reward(_ptr(correct), _ptr(t_reference), _ptr(t_kernel), _ptr(t_generated), _ptr(t_total), n,
+                             speedup_cap, _ptr(R), _ptr(pr), _stream(stream)))
+    return R, pr
+
+
+def prs_retain(pr, valid, seed: int, tau: float = 0.3, s: float = 0.1, hard: bool = False, want_p=True, stream=None):
+    """pr float32 [n], valid uint8 [n] | None (device).  Returns (keep u8 [n], p f32 [n] | None)."""
+    n = pr.numel()
+    assert pr.dtype == torch.float32 and (valid is None or (valid.dtype == torch.uint8 and valid.numel() == n))
+    keep = torch.empty(n, dtype=torch.uint8, device=pr.device)
+    p = torch.empty(n, dtype=torch.float32, device=pr.device) if want_p else None
+    _check(lib().prs_retain(_ptr(pr), _ptr(valid), n, tau, s, 1 if hard else 0, seed & 0xFFFFFFFFFFFFFFFF, _ptr(keep),
+                            _ptr(p), _stream(stream)))
+    return keep, p
+
+
+def pg_monitors(logp_train, logp_rollout, entropy, loss_mask, dH=None, dW=None, stream=None):
+    """Returns a float64 [8] device tensor; entries named by MONITOR_NAMES."""
+    T = loss_mask.numel()
+    dev = loss_mask.device
+    out = torch.empty(8, dtype=torch.float64, device=dev)
+    ws = torch.empty(int(lib().pg_monitors_workspace_bytes()), dtype=torch.uint8, device=dev)
+
+    def dt(t):
+        if t is None:
+            return 0
+        assert t.dtype in (torch.bfloat16, torch.float32)
+        return 1 if t.dtype == torch.float32 else 0
+
+    _check(lib().pg_monitors(_ptr(logp_train), _ptr(logp_rollout), _ptr(entropy), _ptr(loss_mask), T, _ptr(dH), dt(dH),
+                             0 if dH is None else dH.numel(), _ptr(dW), dt(dW), 0 if dW is None else dW.numel(),
+                             _ptr(out), _ptr(ws), ws.numel(), _stream(stream)))
+    return out
+
+
 def pg_logprob_fwd(H, W, y, row_mask, params: Params, workspace: torch.Tensor, want_entropy=True, want_lse=True,
                    out=None, stream=None):
     """Returns (logp, entropy|None, lse|None), float32 [T] on the device of H."""
@@ -196,4 +273,29 @@ def pg_loss_fwd_bwd(H, W, y, loss_mask, cu_seqlens, adv, seg_sample, old_logp, r
                                  _ptr(seg_sample), _ptr(old_logp), _ptr(rollout_logp), T, d, V, C.byref(p),
                                  _ptr(loss), _ptr(dH), _ptr(dW), _ptr(logp), _ptr(ent), _ptr(counters),
                                  _ptr(workspace), workspace.numel(), _stream(stream)))
+    return dict(loss=loss, dH=dH, dW=dW, logp=logp, entropy=ent, counters=counters)
+
+
+def pg_sft_fwd_bwd(H, W, y, loss_mask, params: Params, workspace: torch.Tensor, dW: Optional[torch.Tensor] = None,
+                   out=None, stream=None):
+    """Token-mean cross-entropy of the head, forward and backward.  Returns the same dict as pg_loss_fwd_bwd."""
+    T, d = H.shape
+    V = W.shape[0]
+    dev = W.device
+    if out is None:
+        loss = torch.empty(1, dtype=torch.float32, device=dev)
+        dH = torch.empty_like(H)
+        logp = torch.empty(T, dtype=torch.float32, device=dev)
+        ent = torch.empty(T, dtype=torch.float32, device=dev)
+        counters = torch.empty(8, dtype=torch.int64, device=dev)
+    else:
+        loss, dH, logp, ent, counters = out
+    if dW is None:
+        if params.accumulate_dW:
+            raise ValueError("accumulate_dW needs an existing dW")
+        dW = torch.empty((V, d), dtype=torch.bfloat16 if params.dW_dtype else torch.float32, device=dev)
+    p = params.c_struct()
+    _check(lib().pg_sft_fwd_bwd(_ptr(H), _ptr(W), _ptr(y), _ptr(loss_mask), T, d, V, C.byref(p), _ptr(loss), _ptr(dH),
+                                _ptr(dW), _ptr(logp), _ptr(ent), _ptr(counters), _ptr(workspace), workspace.numel(),
+                                _stream(stream)))
     return dict(loss=loss, dH=dH, dW=dW, logp=logp, entropy=ent, counters=counters)

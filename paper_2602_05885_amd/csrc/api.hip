@@ -243,6 +243,27 @@ pg::PrepArgs base_prep(const Plan& pl, void* ws) {
   return a;
 }
 
+int32_t turn_advantage(const float* rewards, const uint8_t* valid, int32_t P, int32_t K, int32_t Tmax, float gamma,
+                       double* returns_out, double* adv_out, int32_t* group_n_out, int group_mean, void* stream,
+                       const char* what) {
+  if (!rewards || !valid || !adv_out) return fail(PG_ERR_INVALID_ARG, "rewards, valid and adv_out must not be NULL");
+  if (P < 1 || K < 1 || Tmax < 1) return fail(PG_ERR_INVALID_ARG, "P, K, Tmax must be >= 1");
+  if ((int64_t)P * K * Tmax > (1ll << 30)) return fail(PG_ERR_UNSUPPORTED_SHAPE, "P*K*Tmax too large");
+  if (!std::isfinite(gamma)) return fail(PG_ERR_INVALID_ARG, "gamma must be finite");
+  pg::TrlooArgs a{rewards, valid, P, K, Tmax, gamma, returns_out, adv_out, group_n_out, group_mean};
+  pg::launch_trloo(a, static_cast<hipStream_t>(stream));
+  return check_launches(what);
+}
+
+// Loss forward + backward shared by the policy-gradient call (sft = 0) and the SFT
+// cross-entropy call (sft = 1: no segments, no advantages, no mismatch correction).
+int32_t loss_fwd_bwd(int sft, const void* H, const void* W, const int32_t* y, const uint8_t* loss_mask,
+                     const int32_t* cu_seqlens, int32_t S, const double* adv, const int32_t* seg_sample,
+                     const float* old_logp, const float* rollout_logp, int64_t T, int64_t d, int64_t V,
+                     const pg_params* h_params, float* loss_out, void* dH, void* dW, float* logp_out,
+                     float* entropy_out, int64_t* counters_out, void* workspace, size_t workspace_bytes,
+                     void* stream);
+
 }  // namespace
 
 extern "C" {
@@ -286,13 +307,12 @@ size_t pg_workspace_bytes(int64_t T, int64_t d, int64_t V, int32_t S, const pg_p
 
 int32_t trloo_advantage(const float* rewards, const uint8_t* valid, int32_t P, int32_t K, int32_t Tmax, float gamma,
                         double* returns_out, double* adv_out, int32_t* group_n_out, void* stream) {
-  if (!rewards || !valid || !adv_out) return fail(PG_ERR_INVALID_ARG, "rewards, valid and adv_out must not be NULL");
-  if (P < 1 || K < 1 || Tmax < 1) return fail(PG_ERR_INVALID_ARG, "P, K, Tmax must be >= 1");
-  if ((int64_t)P * K * Tmax > (1ll << 30)) return fail(PG_ERR_UNSUPPORTED_SHAPE, "P*K*Tmax too large");
-  if (!std::isfinite(gamma)) return fail(PG_ERR_INVALID_ARG, "gamma must be finite");
-  pg::TrlooArgs a{rewards, valid, P, K, Tmax, gamma, returns_out, adv_out, group_n_out};
-  pg::launch_trloo(a, static_cast<hipStream_t>(stream));
-  return check_launches("trloo_advantage");
+  return turn_advantage(rewards, valid, P, K, Tmax, gamma, returns_out, adv_out, group_n_out, 0, stream, "trloo_advantage");
+}
+
+int32_t grpo_advantage(const float* rewards, const uint8_t* valid, int32_t P, int32_t K, int32_t Tmax, float gamma,
+                       double* returns_out, double* adv_out, int32_t* group_n_out, void* stream) {
+  return turn_advantage(rewards, valid, P, K, Tmax, gamma, returns_out, adv_out, group_n_out, 1, stream, "grpo_advantage");
 }
 
 int32_t pg_logprob_fwd(const void* H, const void* W, const int32_t* y, const uint8_t* row_mask, int64_t T, int64_t d,
@@ -324,6 +344,74 @@ int32_t pg_loss_fwd_bwd(const void* H, const void* W, const int32_t* y, const ui
                         const pg_params* h_params, float* loss_out, void* dH, void* dW, float* logp_out,
                         float* entropy_out, int64_t* counters_out, void* workspace, size_t workspace_bytes,
                         void* stream) {
+  return loss_fwd_bwd(0, H, W, y, loss_mask, cu_seqlens, S, adv, seg_sample, old_logp, rollout_logp, T, d, V, h_params,
+                      loss_out, dH, dW, logp_out, entropy_out, counters_out, workspace, workspace_bytes, stream);
+}
+
+int32_t pg_sft_fwd_bwd(const void* H, const void* W, const int32_t* y, const uint8_t* loss_mask, int64_t T, int64_t d,
+                       int64_t V, const pg_params* h_params, float* loss_out, void* dH, void* dW, float* logp_out,
+                       float* entropy_out, int64_t* counters_out, void* workspace, size_t workspace_bytes,
+                       void* stream) {
+  return loss_fwd_bwd(1, H, W, y, loss_mask, nullptr, 0, nullptr, nullptr, nullptr, nullptr, T, d, V, h_params,
+                      loss_out, dH, dW, logp_out, entropy_out, counters_out, workspace, workspace_bytes, stream);
+}
+
+int32_t turn_reward(const uint8_t* correct, const float* t_reference, const float* t_kernel, const float* t_generated,
+                    const float* t_total, int64_t n, float speedup_cap, float* rewards_out, float* pr_out,
+                    void* stream) {
+  if (n < 0) return fail(PG_ERR_INVALID_ARG, "n must be >= 0");
+  if (n == 0) return PG_OK;
+  if (!correct || !t_reference || !t_kernel || !rewards_out)
+    return fail(PG_ERR_INVALID_ARG, "correct, t_reference, t_kernel and rewards_out must not be NULL");
+  if ((t_generated == nullptr) != (t_total == nullptr))
+    return fail(PG_ERR_INVALID_ARG, "t_generated and t_total must be given together");
+  if (!(speedup_cap > 0.f) || !std::isfinite(speedup_cap)) return fail(PG_ERR_INVALID_ARG, "speedup_cap must be finite and > 0");
+  pg::RewardArgs a{correct, t_reference, t_kernel, t_generated, t_total, (long long)n, speedup_cap, rewards_out, pr_out};
+  pg::launch_turn_reward(a, static_cast<hipStream_t>(stream));
+  return check_launches("turn_reward");
+}
+
+int32_t prs_retain(const float* pr, const uint8_t* valid, int64_t n, float tau, float s, int32_t hard, uint64_t seed,
+                   uint8_t* keep_out, float* p_out, void* stream) {
+  if (n < 0) return fail(PG_ERR_INVALID_ARG, "n must be >= 0");
+  if (n == 0) return PG_OK;
+  if (!pr || !keep_out) return fail(PG_ERR_INVALID_ARG, "pr and keep_out must not be NULL");
+  if (!(s > 0.f) || !std::isfinite(s) || !std::isfinite(tau)) return fail(PG_ERR_INVALID_ARG, "tau must be finite and s finite and > 0");
+  pg::PrsArgs a{pr, valid, (long long)n, tau, s, hard != 0, (unsigned long long)seed, keep_out, p_out};
+  pg::launch_prs_retain(a, static_cast<hipStream_t>(stream));
+  return check_launches("prs_retain");
+}
+
+size_t pg_monitors_workspace_bytes(void) { return (size_t)6 * pg::MON_BLOCKS * sizeof(double); }
+
+int32_t pg_monitors(const float* logp_train, const float* logp_rollout, const float* entropy, const uint8_t* loss_mask,
+                    int64_t T, const void* dH, int32_t dH_dtype, int64_t dH_elems, const void* dW, int32_t dW_dtype,
+                    int64_t dW_elems, double* out, void* workspace, size_t workspace_bytes, void* stream) {
+  if (T < 0 || dH_elems < 0 || dW_elems < 0) return fail(PG_ERR_INVALID_ARG, "negative extent");
+  if (!out || !workspace) return fail(PG_ERR_INVALID_ARG, "out and workspace must not be NULL");
+  if (T > 0 && (!logp_train || !loss_mask)) return fail(PG_ERR_INVALID_ARG, "logp_train and loss_mask must not be NULL when T > 0");
+  if ((dH && dH_dtype != 0 && dH_dtype != 1) || (dW && dW_dtype != 0 && dW_dtype != 1))
+    return fail(PG_ERR_INVALID_ARG, "gradient dtype must be 0 (bf16) or 1 (fp32)");
+  if ((dH && misaligned(dH)) || (dW && misaligned(dW)) || (reinterpret_cast<uintptr_t>(workspace) & 7u))
+    return fail(PG_ERR_INVALID_ARG, "dH and dW must be 16-byte aligned, workspace 8-byte aligned");
+  if (workspace_bytes < pg_monitors_workspace_bytes())
+    return fail(PG_ERR_WORKSPACE_TOO_SMALL, "workspace has %zu bytes, %zu needed", workspace_bytes, pg_monitors_workspace_bytes());
+  pg::MonitorArgs a{logp_train, logp_rollout, entropy, loss_mask, (long long)T, dH, dH_dtype, (long long)dH_elems,
+                    dW, dW_dtype, (long long)dW_elems, static_cast<double*>(workspace), out};
+  pg::launch_monitors(a, static_cast<hipStream_t>(stream));
+  return check_launches("pg_monitors");
+}
+
+}  // extern "C"
+
+namespace {
+
+int32_t loss_fwd_bwd(int sft, const void* H, const void* W, const int32_t* y, const uint8_t* loss_mask,
+                     const int32_t* cu_seqlens, int32_t S, const double* adv, const int32_t* seg_sample,
+                     const float* old_logp, const float* rollout_logp, int64_t T, int64_t d, int64_t V,
+                     const pg_params* h_params, float* loss_out, void* dH, void* dW, float* logp_out,
+                     float* entropy_out, int64_t* counters_out, void* workspace, size_t workspace_bytes,
+                     void* stream) {
   Plan pl;
   int32_t rc = make_plan(T, d, V, S, h_params, PG_CALL_LOSS_FWD_BWD, pl);
   if (rc) return rc;
@@ -336,13 +424,16 @@ int32_t pg_loss_fwd_bwd(const void* H, const void* W, const int32_t* y, const ui
     pg::launch_fill_f32(loss_out, 1, 0.f, st);
     if (counters_out) pg::launch_fill_zero_bytes(counters_out, 8 * sizeof(int64_t), st);
     if (!p.accumulate_dW) pg::launch_fill_zero_bytes(dW, (size_t)V * d * dw_elem, st);
-    return check_launches("pg_loss_fwd_bwd (empty)");
+    return check_launches(sft ? "pg_sft_fwd_bwd (empty)" : "pg_loss_fwd_bwd (empty)");
   }
-  if (!H || !y || !loss_mask || !cu_seqlens || !adv || !dH || !workspace)
-    return fail(PG_ERR_INVALID_ARG, "H, y, loss_mask, cu_seqlens, adv, dH and workspace must not be NULL");
-  if (S < 1) return fail(PG_ERR_INVALID_ARG, "S must be >= 1 when T > 0");
-  if (p.mismatch_mode != PG_MISMATCH_NONE && (!old_logp || !rollout_logp))
-    return fail(PG_ERR_INVALID_ARG, "mismatch correction needs old_logp and rollout_logp");
+  if (!H || !y || !loss_mask || !dH || !workspace)
+    return fail(PG_ERR_INVALID_ARG, "H, y, loss_mask, dH and workspace must not be NULL");
+  if (!sft) {
+    if (!cu_seqlens || !adv) return fail(PG_ERR_INVALID_ARG, "cu_seqlens and adv must not be NULL");
+    if (S < 1) return fail(PG_ERR_INVALID_ARG, "S must be >= 1 when T > 0");
+    if (p.mismatch_mode != PG_MISMATCH_NONE && (!old_logp || !rollout_logp))
+      return fail(PG_ERR_INVALID_ARG, "mismatch correction needs old_logp and rollout_logp");
+  }
   if (misaligned(H) || misaligned(dH) || misaligned(workspace)) return fail(PG_ERR_INVALID_ARG, "H, dH and workspace must be 16-byte aligned");
   if (workspace_bytes < pl.total) return fail(PG_ERR_WORKSPACE_TOO_SMALL, "workspace has %zu bytes, %zu needed", workspace_bytes, pl.total);
   if ((rc = ensure_init())) return rc;
@@ -351,13 +442,13 @@ int32_t pg_loss_fwd_bwd(const void* H, const void* W, const int32_t* y, const ui
   pg::PrepArgs prep = base_prep(pl, ws);
   prep.mask = loss_mask; prep.cu = cu_seqlens; prep.S = S; prep.adv = adv; prep.seg_sample = seg_sample;
   prep.old_logp = old_logp; prep.rollout_logp = rollout_logp;
-  prep.mismatch_mode = p.mismatch_mode; prep.geo_lo = p.geo_lo; prep.geo_hi = p.geo_hi;
+  prep.mismatch_mode = sft ? PG_MISMATCH_NONE : p.mismatch_mode; prep.geo_lo = p.geo_lo; prep.geo_hi = p.geo_hi;
   prep.veto_ratio = p.veto_ratio; prep.trunc_c = p.trunc_c; prep.norm_override = p.norm_override;
   prep.out0 = logp_out; prep.out1 = entropy_out; prep.out2 = nullptr;
 
   pg::CombineArgs comb{};
   comb.logp_out = logp_out; comb.ent_out = entropy_out; comb.lse_out = nullptr;
-  comb.with_loss = 1; comb.old_logp = old_logp;
+  comb.with_loss = sft ? 2 : 1; comb.old_logp = old_logp;
   comb.c_tok = at<float>(ws, pl.c_tok); comb.a_tok = at<float>(ws, pl.a_tok);
   comb.eps_lo = p.clip_eps_lo; comb.eps_hi = p.clip_eps_hi; comb.inv_tau = 1.f / p.temperature;
   comb.coefc = at<float>(ws, pl.coefc); comb.lossterm = at<float>(ws, pl.lossterm);
@@ -412,7 +503,7 @@ int32_t pg_loss_fwd_bwd(const void* H, const void* W, const int32_t* y, const ui
 
   pg::ScatterArgs sc{at<float>(ws, pl.dHacc), at<int>(ws, pl.pos), dH, (int)pl.T, d_i, pl.is_f32};
   pg::launch_scatter_dh(sc, st);
-  return check_launches("pg_loss_fwd_bwd");
+  return check_launches(sft ? "pg_sft_fwd_bwd" : "pg_loss_fwd_bwd");
 }
 
-}  // extern "C"
+}  // namespace

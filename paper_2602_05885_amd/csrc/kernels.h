@@ -77,6 +77,7 @@ struct TrlooArgs {
   double* returns_out;
   double* adv_out;
   int* group_n_out;
+  int group_mean;      // 0: leave-one-out baseline (Eq. 5), 1: group-mean baseline (Eq. 3)
 };
 void launch_trloo(const TrlooArgs& a, hipStream_t s);
 
@@ -130,7 +131,7 @@ struct CombineArgs {
   const int* rows;
   float* lse2;
   float* logp_out; float* ent_out; float* lse_out;      // original-row indexed, nullable
-  // loss epilogue (with_loss != 0)
+  // loss epilogue: 0 none, 1 clipped surrogate, 2 cross-entropy (l = -logp, dl/dlogp = -1)
   int with_loss;
   const float* old_logp;     // original-row indexed, nullable
   const float* c_tok; const float* a_tok;
@@ -163,6 +164,42 @@ struct ScatterArgs {
   int out_f32;
 };
 void launch_scatter_dh(const ScatterArgs& a, hipStream_t s);
+
+// ---- stages around the path -------------------------------------------------------------
+struct RewardArgs {
+  const uint8_t* correct;
+  const float* t_reference; const float* t_kernel;
+  const float* t_generated; const float* t_total;   // both nullable
+  long long n;
+  float cap;
+  float* rewards_out;
+  float* pr_out;                                    // nullable
+};
+void launch_turn_reward(const RewardArgs& a, hipStream_t s);
+
+struct PrsArgs {
+  const float* pr;
+  const uint8_t* valid;     // nullable
+  long long n;
+  float tau, s;
+  int hard;
+  unsigned long long seed;
+  uint8_t* keep_out;
+  float* p_out;             // nullable
+};
+void launch_prs_retain(const PrsArgs& a, hipStream_t s);
+
+constexpr int MON_BLOCKS = 1024;     // partial sums per reduced quantity
+struct MonitorArgs {
+  const float* logp_train; const float* logp_rollout; const float* entropy;
+  const uint8_t* mask;
+  long long T;
+  const void* dH; int dH_f32; long long dH_elems;
+  const void* dW; int dW_f32; long long dW_elems;
+  double* partial;          // [6][MON_BLOCKS]
+  double* out;              // [8]
+};
+void launch_monitors(const MonitorArgs& a, hipStream_t s);
 
 void launch_fill_f32(float* p, size_t n, float v, hipStream_t s);
 void launch_fill_zero_bytes(void* p, size_t nbytes, hipStream_t s);   // nbytes multiple of 4

@@ -23,9 +23,10 @@ void launch_fill_zero_bytes(void* p, size_t nbytes, hipStream_t s) {
   launch_fill_f32(reinterpret_cast<float*>(p), nbytes / 4, 0.f, s);
 }
 
-// ------------------------------------------------------------------ TRLOO (Sec. 4.2, Eq. 2 and 5)
+// ------------------------------------------------------------------ TRLOO (Sec. 4.2, Eq. 2, 3 and 5)
 // One thread per (prompt, turn) group; fp64 throughout.  Returns are evaluated by Horner's
-// rule from the last turn backwards; the leave-one-out mean is (sum - own) / (N - 1).
+// rule from the last turn backwards; the leave-one-out mean is (sum - own) / (N - 1), the
+// group mean of the comparison baseline sum / N.
 __device__ __forceinline__ double turn_return(const float* r, int t, int Tmax, double gamma) {
   double g = 0.0;
   for (int tp = Tmax - 1; tp >= t; --tp) g = (double)r[tp] + gamma * g;
@@ -49,9 +50,10 @@ __global__ void trloo_kernel(TrlooArgs a) {
   for (int k = 0; k < a.K; ++k) {
     const size_t base = ((size_t)p * a.K + k) * a.Tmax;
     double A = 0.0;
-    if (n >= 2 && a.valid[base + t]) {
+    if (a.valid[base + t]) {
       const double G = turn_return(a.rewards + base, t, a.Tmax, gamma);
-      A = G - (sum - G) / (double)(n - 1);
+      if (a.group_mean) A = G - sum / (double)n;                    // Eq. (3); n >= 1 here
+      else if (n >= 2) A = G - (sum - G) / (double)(n - 1);         // Eq. (5)
     }
     a.adv_out[base + t] = A;
   }
@@ -180,6 +182,7 @@ __global__ __launch_bounds__(1024) void prep_compact_kernel(PrepArgs a) {
     a.ctl->norm = a.norm_override > 0.f ? a.norm_override : (float)max(total, 1);
     a.ctl->pad_ = 0;
     a.counters[0] = (unsigned long long)total;
+    if (!a.cu) a.counters[6] = (unsigned long long)total;   // no segments: every flagged row is a loss row
   }
 }
 
@@ -385,6 +388,11 @@ __global__ __launch_bounds__(256) void combine_kernel(CombineArgs a) {
   if (a.ent_out) a.ent_out[row] = (log2s - u / s) * LN2;
   if (a.lse_out) a.lse_out[row] = lse2 * LN2;
   if (!a.with_loss) return;
+  if (a.with_loss == 2) {            // cross-entropy: l = -logp, dl/dlogp = -1
+    a.coefc[i] = -1.f / ctl.norm * a.inv_tau;
+    a.lossterm[i] = -logp;
+    return;
+  }
   const float A = a.a_tok[row], c = a.c_tok[row];
   const float r = a.old_logp ? expf(logp - a.old_logp[row]) : 1.f;
   const float lo = 1.f - a.eps_lo, hi = 1.f + a.eps_hi;
@@ -442,6 +450,170 @@ __global__ __launch_bounds__(256) void scatter_dh_kernel(ScatterArgs a) {
 void launch_scatter_dh(const ScatterArgs& a, hipStream_t s) {
   if (a.T <= 0) return;
   hipLaunchKernelGGL(scatter_dh_kernel, dim3(a.T), dim3(256), 0, s, a);
+}
+
+// ------------------------------------------------------------------ rewards (Eq. 1, Eq. 6-7)
+__global__ void turn_reward_kernel(RewardArgs a) {
+  const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= a.n) return;
+  double R = 0.0, pr = 0.0;
+  if (a.correct[i]) {
+    const double speedup = fmin((double)a.t_reference[i] / (double)a.t_kernel[i], (double)a.cap);
+    R = 1.0 + speedup;
+    if (a.t_generated) {
+      pr = (double)a.t_generated[i] / (double)a.t_total[i];
+      R += pr;
+    }
+  }
+  a.rewards_out[i] = (float)R;
+  if (a.pr_out) a.pr_out[i] = (float)pr;
+}
+void launch_turn_reward(const RewardArgs& a, hipStream_t s) {
+  if (a.n <= 0) return;
+  hipLaunchKernelGGL(turn_reward_kernel, dim3((unsigned)((a.n + 255) / 256)), dim3(256), 0, s, a);
+}
+
+// ------------------------------------------------------------------ PRS (Sec. 5.2, Eq. 8)
+// Philox-4x32 with 10 rounds (Salmon et al., SC'11), one block per sample; only the first
+// output word is used.
+__device__ __forceinline__ uint32_t philox4x32_10_word0(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+                                                       uint32_t k0, uint32_t k1) {
+#pragma unroll
+  for (int r = 0; r < 10; ++r) {
+    const uint64_t p0 = (uint64_t)0xD2511F53u * c0;
+    const uint64_t p1 = (uint64_t)0xCD9E8D57u * c2;
+    const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+    const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+    c1 = (uint32_t)p1;
+    c3 = (uint32_t)p0;
+    c0 = n0;
+    c2 = n2;
+    k0 += 0x9E3779B9u;
+    k1 += 0xBB67AE85u;
+  }
+  return c0;
+}
+
+__global__ void prs_retain_kernel(PrsArgs a) {
+  const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= a.n) return;
+  const double pr = (double)a.pr[i];
+  double p = (pr - (double)a.tau) / (double)a.s;
+  p = fmin(fmax(p, 0.0), 1.0);
+  bool keep = false;
+  if (!a.valid || a.valid[i]) {
+    if (a.hard) {
+      keep = pr >= (double)a.tau;
+    } else {
+      const uint32_t x = philox4x32_10_word0((uint32_t)i, (uint32_t)((unsigned long long)i >> 32), 0u, 0u,
+                                             (uint32_t)a.seed, (uint32_t)(a.seed >> 32));
+      const double u = ((double)x + 0.5) * (1.0 / 4294967296.0);
+      keep = u < p;
+    }
+  }
+  a.keep_out[i] = keep ? 1 : 0;
+  if (a.p_out) a.p_out[i] = (float)p;
+}
+void launch_prs_retain(const PrsArgs& a, hipStream_t s) {
+  if (a.n <= 0) return;
+  hipLaunchKernelGGL(prs_retain_kernel, dim3((unsigned)((a.n + 255) / 256)), dim3(256), 0, s, a);
+}
+
+// ------------------------------------------------------------------ monitors (Sec. 5.1)
+// Stage 1: MON_BLOCKS workgroups; workgroup b sums a fixed, contiguous slice of every input in
+// fp64 (tree reduction in a fixed order).  Stage 2: one workgroup folds the partials, again in a
+// fixed order, and writes the six monitors.
+__device__ __forceinline__ double block_sum_256(double v, double* sh) {
+  const int tid = threadIdx.x;
+  sh[tid] = v;
+  __syncthreads();
+  for (int w = 128; w > 0; w >>= 1) {
+    if (tid < w) sh[tid] += sh[tid + w];
+    __syncthreads();
+  }
+  const double r = sh[0];
+  __syncthreads();
+  return r;
+}
+
+__device__ __forceinline__ double sumsq_slice(const void* p, int is_f32, long long n, int b, int tid) {
+  // slice b of MON_BLOCKS, in units of 8 elements so that loads stay 16-byte aligned
+  const long long units = (n + 7) / 8, per = (units + MON_BLOCKS - 1) / MON_BLOCKS;
+  const long long u0 = (long long)b * per, u1 = u0 + per < units ? u0 + per : units;
+  double acc = 0.0;
+  for (long long u = u0 + tid; u < u1; u += 256) {
+    const long long e0 = u * 8;
+    if (e0 + 8 <= n) {
+      if (is_f32) {
+        const float4 x = reinterpret_cast<const float4*>(p)[u * 2], y = reinterpret_cast<const float4*>(p)[u * 2 + 1];
+        acc += (double)x.x * x.x + (double)x.y * x.y + (double)x.z * x.z + (double)x.w * x.w +
+               (double)y.x * y.x + (double)y.y * y.y + (double)y.z * y.z + (double)y.w * y.w;
+      } else {
+        const bf16x8 x = reinterpret_cast<const bf16x8*>(p)[u];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) { const double v = (double)(float)x[e]; acc += v * v; }
+      }
+    } else {
+      for (long long e = e0; e < n; ++e) {
+        const double v = is_f32 ? (double)reinterpret_cast<const float*>(p)[e]
+                                : (double)(float)reinterpret_cast<const __bf16*>(p)[e];
+        acc += v * v;
+      }
+    }
+  }
+  return acc;
+}
+
+__global__ __launch_bounds__(256) void monitors_partial_kernel(MonitorArgs a) {
+  __shared__ double sh[256];
+  const int b = blockIdx.x, tid = threadIdx.x;
+  const long long per = (a.T + MON_BLOCKS - 1) / MON_BLOCKS;
+  const long long t0 = (long long)b * per, t1 = t0 + per < a.T ? t0 + per : a.T;
+  double s_ent = 0.0, s_tr = 0.0, s_ro = 0.0, s_n = 0.0;
+  for (long long t = t0 + tid; t < t1; t += 256) {
+    if (a.mask[t]) {
+      s_n += 1.0;
+      s_tr += (double)a.logp_train[t];
+      if (a.logp_rollout) s_ro += (double)a.logp_rollout[t];
+      if (a.entropy) s_ent += (double)a.entropy[t];
+    }
+  }
+  const double r0 = block_sum_256(s_ent, sh), r1 = block_sum_256(s_tr, sh), r2 = block_sum_256(s_ro, sh),
+               r5 = block_sum_256(s_n, sh);
+  const double r3 = a.dH ? block_sum_256(sumsq_slice(a.dH, a.dH_f32, a.dH_elems, b, tid), sh) : 0.0;
+  const double r4 = a.dW ? block_sum_256(sumsq_slice(a.dW, a.dW_f32, a.dW_elems, b, tid), sh) : 0.0;
+  if (tid == 0) {
+    a.partial[0 * MON_BLOCKS + b] = r0; a.partial[1 * MON_BLOCKS + b] = r1; a.partial[2 * MON_BLOCKS + b] = r2;
+    a.partial[3 * MON_BLOCKS + b] = r3; a.partial[4 * MON_BLOCKS + b] = r4; a.partial[5 * MON_BLOCKS + b] = r5;
+  }
+}
+
+__global__ __launch_bounds__(256) void monitors_final_kernel(MonitorArgs a) {
+  __shared__ double sh[256];
+  __shared__ double tot[6];
+  const int tid = threadIdx.x;
+  for (int q = 0; q < 6; ++q) {
+    double v = 0.0;
+    for (int b = tid; b < MON_BLOCKS; b += 256) v += a.partial[q * MON_BLOCKS + b];
+    const double r = block_sum_256(v, sh);
+    if (tid == 0) tot[q] = r;
+  }
+  __syncthreads();
+  if (tid == 0) {
+    const double n = tot[5], den = n > 0.0 ? n : 1.0;
+    a.out[0] = a.entropy ? tot[0] / den : 0.0;
+    a.out[1] = exp(-tot[1] / den);
+    a.out[2] = a.logp_rollout ? exp(-tot[2] / den) : 0.0;
+    a.out[3] = sqrt(tot[3]);
+    a.out[4] = sqrt(tot[4]);
+    a.out[5] = n;
+    a.out[6] = 0.0;
+    a.out[7] = 0.0;
+  }
+}
+void launch_monitors(const MonitorArgs& a, hipStream_t s) {
+  hipLaunchKernelGGL(monitors_partial_kernel, dim3(MON_BLOCKS), dim3(256), 0, s, a);
+  hipLaunchKernelGGL(monitors_final_kernel, dim3(1), dim3(256), 0, s, a);
 }
 
 }  // namespace pg

@@ -76,3 +76,27 @@ def test_invalid_arguments_return_error_codes():
     rc = lib.pg_loss_fwd_bwd(one, one, one, one, one, 1, one, None, None, None, 8, 64, 100, None, one, one, one,
                              None, None, None, one, 1 << 30, None)
     assert rc == -1 and "params" in B.pg_last_error()
+
+
+def test_stage_entry_points_validate_arguments():
+    lib = B.lib()
+    one = C.c_void_p(16)      # never dereferenced: validation fails first
+    assert lib.grpo_advantage(None, one, 1, 1, 1, 1.0, None, one, None, None) == -1
+    assert lib.turn_reward(None, one, one, None, None, 4, 3.0, one, None, None) == -1
+    assert lib.turn_reward(one, one, one, one, None, 4, 3.0, one, None, None) == -1 and "together" in B.pg_last_error()
+    assert lib.turn_reward(one, one, one, None, None, 4, 0.0, one, None, None) == -1
+    assert lib.turn_reward(one, one, one, None, None, -1, 3.0, one, None, None) == -1
+    assert lib.turn_reward(None, None, None, None, None, 0, 3.0, None, None, None) == 0      # nothing to do
+    assert lib.prs_retain(None, None, 4, 0.3, 0.1, 0, 1, one, None, None) == -1
+    assert lib.prs_retain(one, None, 4, 0.3, 0.0, 0, 1, one, None, None) == -1 and "> 0" in B.pg_last_error()
+    assert lib.prs_retain(None, None, 0, 0.3, 0.1, 0, 1, None, None, None) == 0
+    ws = int(lib.pg_monitors_workspace_bytes())
+    assert ws > 0
+    assert lib.pg_monitors(one, None, None, one, 4, None, 0, 0, None, 0, 0, None, one, ws, None) == -1
+    assert lib.pg_monitors(one, None, None, one, 4, None, 0, 0, None, 0, 0, one, one, ws - 1, None) == -3
+    assert lib.pg_monitors(one, None, None, one, 4, one, 5, 8, None, 0, 0, one, one, ws, None) == -1
+    p = B.Params().c_struct()
+    rc = lib.pg_sft_fwd_bwd(one, one, one, None, 8, 64, 100, C.byref(p), one, one, one, None, None, None, one, 1 << 30, None)
+    assert rc == -1 and "NULL" in B.pg_last_error()
+    rc = lib.pg_sft_fwd_bwd(one, one, one, one, 8, 64, 100, C.byref(p), one, one, one, None, None, None, one, 16, None)
+    assert rc == -3

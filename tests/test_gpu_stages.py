@@ -1,0 +1,153 @@
+"""Parity of the stages around the path with the fp64 oracle, through the C ABI: SFT cross-entropy
+(Sec. 3.3), GRPO baseline (Eq. 3), rewards with the profiling ratio (Eq. 1, 6-7), PRS (Eq. 8) and the
+monitors (Sec. 5.1).  Integer / byte outputs are compared exactly."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import pg_oracle as O
+from paper_2602_05885_amd import binding as B
+from paper_2602_05885_amd import synth
+from tests._cases import np64, rel_fro
+
+pytestmark = pytest.mark.gpu
+
+TOL_ADV, TOL_LOGP, TOL_LOSS, TOL_GRAD = 1e-6, 2e-3, 1e-3, 1e-2
+
+
+@pytest.fixture(scope="module")
+def dev():
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    return torch.device("cuda:0")
+
+
+# ------------------------------------------------------------------------------------ SFT
+@pytest.mark.parametrize("T,d,V,dtype,tau,seed,mask_frac", [
+    (1024, 64, 1000, "f32", 1.0, 11, 0.0),        # the tiny fp32 configuration's head
+    (700, 128, 3000, "bf16", 1.0, 12, 0.3),       # ragged rows and vocab, several tiles
+    (1500, 256, 5000, "bf16", 0.7, 13, 0.5),
+])
+def test_sft_parity(dev, T, d, V, dtype, tau, seed, mask_frac, monkeypatch):
+    monkeypatch.setenv("PG_HEAD_DS_BUDGET_BYTES", str(2 * 2048 * 1024))      # forces several vocab chunks
+    H, W, y = synth.make_head(T, d, V, dtype, seed, dev, unit_rms=(dtype == "bf16"),
+                              w_std=0.02 if dtype == "bf16" else 0.1)
+    rng = np.random.default_rng(seed)
+    mask = (rng.random(T) >= mask_frac).astype(np.uint8)
+    prm = B.Params(dtype=0 if dtype == "bf16" else 1, temperature=tau)
+    ws = B.alloc_workspace(T, d, V, 0, prm, B.CALL_LOSS_FWD_BWD, dev)
+    out = B.pg_sft_fwd_bwd(H, W, y, torch.from_numpy(mask).to(dev), prm, ws)
+    torch.cuda.synchronize()
+    ref = O.sft_ce_fwd_bwd(np64(H), np64(W), y.cpu().numpy(), mask, tau)
+    tol_logp = TOL_LOGP if dtype == "bf16" else 2e-4
+    assert abs(float(out["loss"][0]) - ref["loss"]) <= TOL_LOSS * abs(ref["loss"])
+    assert np.abs(out["logp"].cpu().numpy() - ref["logp"]).max() <= tol_logp
+    assert np.abs(out["entropy"].cpu().numpy() - ref["entropy"]).max() <= tol_logp
+    assert rel_fro(np64(out["dH"]), ref["dH"]) <= TOL_GRAD
+    assert rel_fro(np64(out["dW"]), ref["dW"]) <= TOL_GRAD
+    assert np.all(np64(out["dH"])[mask == 0] == 0)
+    cnt = out["counters"].cpu().numpy()
+    assert cnt[0] == ref["n"] and cnt[6] == ref["n"] and not cnt[1:6].any()
+
+
+def test_sft_accumulate_override_and_empty(dev):
+    T, d, V = 300, 64, 777
+    H, W, y = synth.make_head(T, d, V, "bf16", 21, dev, unit_rms=True)
+    mask = np.ones(T, np.uint8)
+    mask[::3] = 0
+    prm = B.Params(norm_override=1000.0, accumulate_dW=1)
+    ws = B.alloc_workspace(T, d, V, 0, prm, B.CALL_LOSS_FWD_BWD, dev)
+    prev = torch.full((V, d), 0.125, dtype=torch.float32, device=dev)
+    dW = prev.clone()
+    out = B.pg_sft_fwd_bwd(H, W, y, torch.from_numpy(mask).to(dev), prm, ws, dW=dW)
+    torch.cuda.synchronize()
+    ref = O.sft_ce_fwd_bwd(np64(H), np64(W), y.cpu().numpy(), mask, 1.0, norm_override=1000.0, dW_prev=np64(prev))
+    assert abs(float(out["loss"][0]) - ref["loss"]) <= TOL_LOSS * abs(ref["loss"])
+    assert rel_fro(np64(out["dW"]) - 0.125, ref["dW"] - 0.125) <= TOL_GRAD
+    # all rows masked: zero loss, zero gradients
+    prm0 = B.Params()
+    out0 = B.pg_sft_fwd_bwd(H, W, y, torch.zeros(T, dtype=torch.uint8, device=dev), prm0, ws)
+    torch.cuda.synchronize()
+    assert float(out0["loss"][0]) == 0.0 and not out0["dH"].any() and not out0["dW"].any()
+
+
+# ------------------------------------------------------------------------------------ GRPO
+@pytest.mark.parametrize("P,K,Tm,gamma,seed", [(4, 4, 2, 1.0, 0), (16, 8, 3, 1.0, 1), (3, 5, 7, 0.9, 4), (2, 1, 3, 0.0, 5)])
+def test_grpo_parity(dev, P, K, Tm, gamma, seed):
+    rng = np.random.default_rng(seed)
+    correct = rng.random((P, K, Tm)) < 0.5
+    R = np.where(correct, 1.0 + np.minimum(rng.lognormal(0, 0.5, (P, K, Tm)), 3.0), 0.0).astype(np.float32)
+    valid = (rng.random((P, K, Tm)) < 0.75).astype(np.uint8)
+    valid[0, :, 0] = 0                          # empty group
+    valid[-1, :, -1] = 0
+    valid[-1, 0, -1] = 1                        # singleton group: A = G - G = 0
+    adv, ret, gn = B.grpo_advantage(torch.from_numpy(R).to(dev), torch.from_numpy(valid).to(dev), gamma)
+    torch.cuda.synchronize()
+    A = O.grpo_advantage(R, valid, gamma)
+    assert np.abs(adv.cpu().numpy() - A).max() <= TOL_ADV
+    assert np.abs(ret.cpu().numpy() - O.returns(R, gamma)).max() <= TOL_ADV
+    assert np.array_equal(gn.cpu().numpy(), valid.sum(axis=1).astype(np.int32))
+
+
+# ------------------------------------------------------------------------------------ rewards, PRS
+@pytest.mark.parametrize("n,seed,with_pr", [(1, 0, True), (384, 1, True), (1000, 2, False), (70001, 3, True)])
+def test_turn_reward_parity(dev, n, seed, with_pr):
+    rng = np.random.default_rng(seed)
+    correct = (rng.random(n) < 0.5).astype(np.uint8)
+    t_ref = rng.lognormal(0.0, 0.5, n).astype(np.float32)
+    t_ker = (t_ref / np.maximum(rng.lognormal(0.0, 0.8, n), 0.05)).astype(np.float32)    # some speedups beyond the cap
+    t_tot = rng.lognormal(0.0, 0.5, n).astype(np.float32)
+    t_gen = (t_tot * rng.random(n)).astype(np.float32)
+    to = lambda a: torch.from_numpy(a).to(dev)
+    R, pr = B.turn_reward(to(correct), to(t_ref), to(t_ker), to(t_gen) if with_pr else None,
+                          to(t_tot) if with_pr else None, 3.0)
+    torch.cuda.synchronize()
+    R_ref, pr_ref = O.turn_reward(correct, t_ref, t_ker, t_gen if with_pr else None, t_tot if with_pr else None, 3.0)
+    assert np.abs(R.cpu().numpy() - R_ref).max() <= 1e-6 * 5
+    assert np.abs(pr.cpu().numpy() - pr_ref).max() <= 1e-6
+    assert (R_ref > 4.0 - 1e-9).any() or n < 100          # the cap is exercised
+
+
+@pytest.mark.parametrize("n,seed,hard", [(5, 7, False), (4096, 8, False), (70001, 9, False), (4096, 10, True)])
+def test_prs_retain_parity(dev, n, seed, hard):
+    rng = np.random.default_rng(seed)
+    pr = rng.random(n).astype(np.float32)
+    pr[: min(n, 4)] = np.float32([0.3, 0.4, 0.35, 0.29999])[: min(n, 4)]
+    valid = (rng.random(n) < 0.9).astype(np.uint8)
+    big_seed = (seed << 40) + 12345                       # exercises the high key word
+    keep, p = B.prs_retain(torch.from_numpy(pr).to(dev), torch.from_numpy(valid).to(dev), big_seed, 0.3, 0.1, hard)
+    torch.cuda.synchronize()
+    keep_ref, p_ref = O.prs_retain(pr, valid, big_seed, 0.3, 0.1, hard)
+    assert np.array_equal(keep.cpu().numpy(), keep_ref)                         # byte-exact decisions
+    assert np.abs(p.cpu().numpy() - p_ref).max() <= 1e-6
+    keep_nv, _ = B.prs_retain(torch.from_numpy(pr).to(dev), None, big_seed, 0.3, 0.1, hard)
+    torch.cuda.synchronize()
+    ref_nv, _ = O.prs_retain(pr, np.ones(n), big_seed, 0.3, 0.1, hard)
+    assert np.array_equal(keep_nv.cpu().numpy(), ref_nv)
+
+
+# ------------------------------------------------------------------------------------ monitors
+@pytest.mark.parametrize("T,d,V,gdtype,seed", [(1, 64, 100, torch.float32, 0), (5000, 64, 999, torch.float32, 1),
+                                               (3001, 128, 1001, torch.bfloat16, 2)])
+def test_monitors_parity(dev, T, d, V, gdtype, seed):
+    rng = np.random.default_rng(seed)
+    mask = (rng.random(T) < 0.7).astype(np.uint8)
+    lt = (-rng.gamma(2.0, 1.5, T)).astype(np.float32)
+    lr = (lt + rng.normal(0, 0.1, T)).astype(np.float32)
+    ent = rng.gamma(2.0, 1.0, T).astype(np.float32)
+    dH = torch.from_numpy(rng.normal(0, 1e-3, (T, d)).astype(np.float32)).to(dev).to(gdtype)
+    dW = torch.from_numpy(rng.normal(0, 1e-3, (V, d)).astype(np.float32)).to(dev)      # fp32 dW, element count not a multiple of 8 * 1024
+    to = lambda a: torch.from_numpy(a).to(dev)
+    out = B.pg_monitors(to(lt), to(lr), to(ent), to(mask), dH, dW)
+    torch.cuda.synchronize()
+    got = dict(zip(B.MONITOR_NAMES, out.cpu().numpy()[:6]))
+    ref = O.monitors(lt, lr, ent, mask, np64(dH), np64(dW))
+    for k in ("entropy_mean", "ppl_train", "ppl_rollout", "dH_norm", "dW_norm"):
+        assert abs(got[k] - ref[k]) <= 1e-9 * max(1.0, abs(ref[k])), (k, got[k], ref[k])
+    assert int(got["n"]) == ref["n"]
+    # optional inputs absent -> zeros; repeatable bit for bit
+    out2 = B.pg_monitors(to(lt), None, None, to(mask))
+    out3 = B.pg_monitors(to(lt), to(lr), to(ent), to(mask), dH, dW)
+    torch.cuda.synchronize()
+    o2 = out2.cpu().numpy()
+    assert o2[0] == 0 and o2[2] == 0 and o2[3] == 0 and o2[4] == 0 and abs(o2[1] - ref["ppl_train"]) <= 1e-9 * ref["ppl_train"]
+    assert torch.equal(out, out3)
