@@ -68,6 +68,39 @@ def cpu_baseline(spec, rows: int):
             "sample": f"{rows} active rows at d={spec.d}, V={spec.V}, fp64 numpy, fwd+bwd, {dt:.1f} s"}
 
 
+def aux_stage_times(B, torch, dev, rewards, valid, out, loss_mask, old_logp, rollout_logp, dW, reps: int = 20):
+    """Microseconds per call of the small stages around the path (outside the timed region): rewards
+    and PRS on the rollout batch's samples, both advantage baselines, the monitors on the step's outputs."""
+    n = rewards.numel()
+    g = torch.Generator(device="cpu").manual_seed(1)
+    correct = (torch.rand(n, generator=g) < 0.5).to(torch.uint8).to(dev)
+    t_ref = torch.rand(n, generator=g).add(0.5).to(dev)
+    t_ker = torch.rand(n, generator=g).add(0.25).to(dev)
+    t_tot = torch.rand(n, generator=g).add(0.5).to(dev)
+    t_gen = (t_tot * 0.5).contiguous()
+    vflat = valid.reshape(-1).contiguous()
+    calls = {
+        "turn_reward": lambda: B.turn_reward(correct, t_ref, t_ker, t_gen, t_tot, 3.0),
+        "prs_retain": lambda: B.prs_retain(t_gen, vflat, 1234, 0.3, 0.1),
+        "trloo_advantage": lambda: B.trloo_advantage(rewards, valid, 1.0),
+        "grpo_advantage": lambda: B.grpo_advantage(rewards, valid, 1.0),
+        "pg_monitors": lambda: B.pg_monitors(out["logp"], rollout_logp if rollout_logp is not None else old_logp,
+                                             out["entropy"], loss_mask, out["dH"], dW),
+    }
+    res = {}
+    for name, fn in calls.items():
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        res[name] = e0.elapsed_time(e1) / reps * 1e3
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -77,6 +110,8 @@ def main():
     ap.add_argument("--mismatch-mode", type=int, default=2)
     ap.add_argument("--cpu-rows", type=int, default=2048, help="rows of the oracle's timed sample (0 = skip)")
     ap.add_argument("--scale-rows", type=float, default=1.0, help="shrink the packed microbatch (debugging)")
+    ap.add_argument("--workload", choices=["pg", "sft"], default="pg",
+                    help="pg: trloo_advantage + pg_loss_fwd_bwd (the headline); sft: pg_sft_fwd_bwd at the same shape")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="also run three plain device-to-device copies of this size (the known-size reference "
                          "that hardware-counter byte counts are scaled by)")
@@ -123,6 +158,8 @@ def main():
               torch.empty(8, dtype=torch.int64, device=dev))
 
     def step():
+        if args.workload == "sft":
+            return B.pg_sft_fwd_bwd(H, W, y, loss_mask, prm, ws, dW=dW, out=outbuf)
         adv, _, _ = B.trloo_advantage(rewards, valid, 1.0, want_returns=False, want_group_n=False)
         return B.pg_loss_fwd_bwd(H, W, y, loss_mask, cu, adv.reshape(-1), seg_sample, old_logp, rollout_logp, prm, ws,
                                  dW=dW, out=outbuf)
@@ -182,10 +219,12 @@ def main():
     executed = 8.0 * d * V * n_active / (ms_step * 1e-3) / 1e12   # logits twice, dH, dW
     useful = 6.0 * d * V * n_active / (ms_step * 1e-3) / 1e12
 
-    cpu = cpu_baseline(spec, args.cpu_rows) if args.cpu_rows > 0 else None
+    cpu = cpu_baseline(spec, args.cpu_rows) if args.cpu_rows > 0 and args.workload == "pg" else None
+    aux = aux_stage_times(B, torch, dev, rewards, valid, out, loss_mask, old_logp, rollout_logp, dW)
 
     line = {
-        "metric": "loss fwd+bwd tokens/sec at 14B shape (h5120,V151936); % bf16 MFMA peak",
+        "metric": ("loss fwd+bwd tokens/sec at 14B shape (h5120,V151936); % bf16 MFMA peak" if args.workload == "pg" else
+                   "SFT cross-entropy fwd+bwd tokens/sec at 14B shape (h5120,V151936); % bf16 MFMA peak"),
         "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if dtype_id == 0 else "f32", "data": "synthetic",
@@ -193,11 +232,12 @@ def main():
                                f"packed microbatch of {S} segments, {T} rows, {n_loss} loss tokens",
                    "loss_tokens": n_loss, "active_tokens": n_active, "packed_rows": T, "segments": S,
                    "mismatch_mode": args.mismatch_mode, "temperature": spec.temperature,
-                   "dW": "fp32 overwrite", "step": "trloo_advantage + pg_loss_fwd_bwd"},
+                   "dW": "fp32 overwrite",
+                   "step": "trloo_advantage + pg_loss_fwd_bwd" if args.workload == "pg" else "pg_sft_fwd_bwd"},
         "pct_mfma_peak_executed_8dV": 100.0 * executed / PEAK_BF16_TFLOPS,
         "pct_mfma_peak_useful_6dV": 100.0 * useful / PEAK_BF16_TFLOPS,
         "loss": loss, "counters": {n: int(c) for n, c in zip(B.COUNTER_NAMES, counters)},
-        "kernels": kern, "roofline": roofline, "cpu_baseline": cpu,
+        "kernels": kern, "roofline": roofline, "cpu_baseline": cpu, "aux_stages_us": aux,
     }
     print(json.dumps(line))
 

@@ -189,3 +189,57 @@ def test_full_logprob_fwd_call(full_case):
     assert np.abs(lse.cpu().numpy()[rows] - fc["o_lse"]).max() <= 2e-3
     assert np.abs(ent.cpu().numpy()[rows] - fc["o_ent"]).max() <= 2e-3
     assert not logp[torch.from_numpy(~m).to(logp.device)].any()
+
+
+def test_full_sft_and_monitors(full_case):
+    """The SFT cross-entropy entry point (Sec. 3.3) at the same size and launch configuration, and the
+    monitors (Sec. 5.1) on its outputs: loss against the library log-probs, sampled dH and dW rows
+    against fp64 evaluations, norms against fp64 reductions of the same outputs."""
+    fc = full_case
+    tin, spec = fc["tin"], fc["spec"]
+    dev = tin["H"].device
+    T = tin["H"].shape[0]
+    tau = float(np.float32(spec.temperature))
+    prm = B.Params(temperature=spec.temperature)
+    ws = B.alloc_workspace(T, spec.d, spec.V, 0, prm, B.CALL_LOSS_FWD_BWD, dev)
+    out = B.pg_sft_fwd_bwd(tin["H"], tin["W"], tin["y"], tin["loss_mask"], prm, ws)
+    torch.cuda.synchronize()
+    del ws
+    m = fc["batch"].loss_mask.astype(bool)
+    n = int(m.sum())
+    lp = fc["lib_logp"].double().cpu().numpy()
+    ref_loss = float(-lp[m].sum() / n)
+    assert abs(float(out["loss"][0]) - ref_loss) <= 1e-3 * abs(ref_loss)
+    cnt = out["counters"].cpu().numpy()
+    assert cnt[0] == n and cnt[6] == n
+    # sampled rows of dH: coefficient -1/n on every loss row (fc["rows"] are loss rows)
+    rows = fc["rows"]
+    ref = O.dH_rows(fc["Hr"], fc["Wn"], fc["yn"][rows], np.full(len(rows), -1.0 / n), spec.temperature)
+    got = np64(out["dH"][torch.from_numpy(rows).to(dev)])
+    assert rel_fro(got, ref) <= 1e-2, rel_fro(got, ref)
+    assert not out["dH"][torch.from_numpy(np.nonzero(~m)[0]).to(dev)].any()
+    # sampled vocab rows of dW
+    act = np.nonzero(m)[0]
+    rng = np.random.default_rng(5)
+    vs = np.unique(np.concatenate([rng.choice(fc["yn"][act], N_VOCAB // 2), rng.integers(0, spec.V, N_VOCAB // 2),
+                                   [spec.V - 1, 0]]))
+    Ha = np64(tin["H"][torch.from_numpy(act).to(dev)])
+    lse = fc["lib_lse"].double().cpu().numpy()[act]
+    k = -1.0 / n / tau
+    z = (Ha @ fc["Wn"][vs].T) / tau
+    dS = -np.exp(z - lse[:, None]) * k
+    dS += (fc["yn"][act][:, None] == vs[None, :]) * k
+    got = np64(out["dW"][torch.from_numpy(vs).to(dev)])
+    assert rel_fro(got, dS.T @ Ha) <= 1e-2
+    # monitors on these outputs
+    mon = B.pg_monitors(out["logp"], fc["lib_logp"], out["entropy"], tin["loss_mask"], out["dH"], out["dW"])
+    torch.cuda.synchronize()
+    g = dict(zip(B.MONITOR_NAMES, mon.cpu().numpy()[:6]))
+    mt = torch.from_numpy(m).to(dev)
+    assert int(g["n"]) == n
+    assert abs(g["dW_norm"] - float(out["dW"].double().pow(2).sum().sqrt())) <= 1e-9 * g["dW_norm"]
+    assert abs(g["dH_norm"] - float(out["dH"].double().pow(2).sum().sqrt())) <= 1e-9 * g["dH_norm"]
+    assert abs(g["ppl_train"] - float(torch.exp(-out["logp"].double()[mt].sum() / n))) <= 1e-9 * g["ppl_train"]
+    assert abs(g["ppl_rollout"] - float(np.exp(-lp[m].sum() / n))) <= 1e-6 * g["ppl_rollout"]
+    assert abs(g["entropy_mean"] - float(out["entropy"].double()[mt].sum() / n)) <= 1e-9 * g["entropy_mean"]
+    assert abs(np.log(g["ppl_train"]) - ref_loss) <= 1e-3 * abs(ref_loss)          # perplexity = exp(cross-entropy)
