@@ -101,6 +101,44 @@ def aux_stage_times(B, torch, dev, rewards, valid, out, loss_mask, old_logp, rol
     return res
 
 
+def bench_forward_only(args, torch, B, synth, dev):
+    """pg_logprob_fwd (log-prob, entropy, logsumexp) over all rows of the chosen configuration."""
+    spec = synth.SPECS[args.config]
+    batch = synth.make_batch(spec, args.scale_rows)
+    T, d, V = batch.T, spec.d, spec.V
+    H, W, y = synth.make_head(T, d, V, spec.dtype, spec.seed, dev, spec.unit_rms)
+    prm = B.Params(dtype=0 if spec.dtype == "bf16" else 1, temperature=spec.temperature)
+    ws = B.alloc_workspace(T, d, V, 0, prm, B.CALL_LOGPROB_FWD, dev)
+    outbuf = tuple(torch.empty(T, dtype=torch.float32, device=dev) for _ in range(3))
+    for _ in range(args.warmup):
+        B.pg_logprob_fwd(H, W, y, None, prm, ws, out=outbuf)
+    torch.cuda.synchronize()
+    B.pg_profile_enable(True, 8 * max(args.steps, 1))
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        B.pg_logprob_fwd(H, W, y, None, prm, ws, out=outbuf)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    prof = B.pg_profile_read()
+    B.pg_profile_enable(False)
+    ms_step = dt / args.steps * 1e3
+    flops = 2.0 * d * V * T
+    k_ms = prof["fwd"][0] / max(prof["fwd"][1], 1)
+    ach = flops / (k_ms * 1e-3) / 1e12
+    line = {"metric": "LM-head log-prob forward tokens/sec (old-policy recompute); % bf16 MFMA peak",
+            "value": T * args.steps / dt, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+            "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+            "dtype": "bf16" if spec.dtype == "bf16" else "f32", "data": "synthetic",
+            "config": {"workload": f"configs[{args.config}] {spec.name}: d={d}, V={V}, {T} rows, forward only",
+                       "temperature": spec.temperature, "step": "pg_logprob_fwd"},
+            "pct_mfma_peak_2dV": 100.0 * flops / (ms_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+            "roofline": {"bound": "mfma", "kernel": "lmhead_fwd_kernel", "achieved": ach, "peak": PEAK_BF16_TFLOPS,
+                         "unit": "TFLOP/s", "frac": ach / PEAK_BF16_TFLOPS, "traffic": None,
+                         "flops_per_launch": flops, "avg_launch_ms": k_ms, "launches_per_step": 1.0},
+            "cpu_baseline": None}
+    print(json.dumps(line))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -110,8 +148,9 @@ def main():
     ap.add_argument("--mismatch-mode", type=int, default=2)
     ap.add_argument("--cpu-rows", type=int, default=2048, help="rows of the oracle's timed sample (0 = skip)")
     ap.add_argument("--scale-rows", type=float, default=1.0, help="shrink the packed microbatch (debugging)")
-    ap.add_argument("--workload", choices=["pg", "sft"], default="pg",
-                    help="pg: trloo_advantage + pg_loss_fwd_bwd (the headline); sft: pg_sft_fwd_bwd at the same shape")
+    ap.add_argument("--workload", choices=["pg", "sft", "fwd"], default="pg",
+                    help="pg: trloo_advantage + pg_loss_fwd_bwd (the headline); sft: pg_sft_fwd_bwd at the same shape; "
+                         "fwd: pg_logprob_fwd over every row (the old-policy recompute)")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="also run three plain device-to-device copies of this size (the known-size reference "
                          "that hardware-counter byte counts are scaled by)")
@@ -127,6 +166,8 @@ def main():
 
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    if args.workload == "fwd":
+        return bench_forward_only(args, torch, B, synth, dev)
     spec = synth.SPECS[args.config]
     batch = synth.make_batch(spec, args.scale_rows)
     T, d, V, S = batch.T, spec.d, spec.V, batch.S
