@@ -68,7 +68,7 @@ def cpu_baseline(spec, rows: int):
             "sample": f"{rows} active rows at d={spec.d}, V={spec.V}, fp64 numpy, fwd+bwd, {dt:.1f} s"}
 
 
-def aux_stage_times(B, torch, dev, rewards, valid, out, loss_mask, old_logp, rollout_logp, dW, reps: int = 20):
+def aux_stage_times(B, torch, dev, rewards, valid, out, loss_mask, old_logp, rollout_logp, dW, H, reps: int = 20):
     """Microseconds per call of the small stages around the path (outside the timed region): rewards
     and PRS on the rollout batch's samples, both advantage baselines, the monitors on the step's outputs."""
     n = rewards.numel()
@@ -87,6 +87,10 @@ def aux_stage_times(B, torch, dev, rewards, valid, out, loss_mask, old_logp, rol
         "pg_monitors": lambda: B.pg_monitors(out["logp"], rollout_logp if rollout_logp is not None else old_logp,
                                              out["entropy"], loss_mask, out["dH"], dW),
     }
+    gamma = torch.ones(H.shape[1], dtype=H.dtype, device=dev)
+    h_buf, dx_buf = torch.empty_like(H), torch.empty_like(H)
+    calls["pg_rmsnorm_fwd"] = lambda: B.pg_rmsnorm_fwd(H, gamma, 1e-6, want_rstd=False, out=h_buf)
+    calls["pg_rmsnorm_bwd"] = lambda: B.pg_rmsnorm_bwd(H, gamma, out["dH"], 1e-6, out=dx_buf)
     res = {}
     for name, fn in calls.items():
         fn()
@@ -98,6 +102,10 @@ def aux_stage_times(B, torch, dev, rewards, valid, out, loss_mask, old_logp, rol
         e1.record()
         torch.cuda.synchronize()
         res[name] = e0.elapsed_time(e1) / reps * 1e3
+    nbytes = H.numel() * H.element_size()
+    res["pg_rmsnorm_fwd_GBps"] = 2 * nbytes / (res["pg_rmsnorm_fwd"] * 1e-6) / 1e9       # x read, h written
+    res["pg_rmsnorm_bwd_GBps"] = 3 * nbytes / (res["pg_rmsnorm_bwd"] * 1e-6) / 1e9       # x, dh read, dx written
+    res["pg_monitors_GBps"] = ((dW.numel() * dW.element_size() + nbytes) / (res["pg_monitors"] * 1e-6) / 1e9)
     return res
 
 
@@ -261,7 +269,7 @@ def main():
     useful = 6.0 * d * V * n_active / (ms_step * 1e-3) / 1e12
 
     cpu = cpu_baseline(spec, args.cpu_rows) if args.cpu_rows > 0 and args.workload == "pg" else None
-    aux = aux_stage_times(B, torch, dev, rewards, valid, out, loss_mask, old_logp, rollout_logp, dW)
+    aux = aux_stage_times(B, torch, dev, rewards, valid, out, loss_mask, old_logp, rollout_logp, dW, H)
 
     line = {
         "metric": ("loss fwd+bwd tokens/sec at 14B shape (h5120,V151936); % bf16 MFMA peak" if args.workload == "pg" else
@@ -278,7 +286,7 @@ def main():
         "pct_mfma_peak_executed_8dV": 100.0 * executed / PEAK_BF16_TFLOPS,
         "pct_mfma_peak_useful_6dV": 100.0 * useful / PEAK_BF16_TFLOPS,
         "loss": loss, "counters": {n: int(c) for n, c in zip(B.COUNTER_NAMES, counters)},
-        "kernels": kern, "roofline": roofline, "cpu_baseline": cpu, "aux_stages_us": aux,
+        "kernels": kern, "roofline": roofline, "cpu_baseline": cpu, "aux_stages_us": aux,      # per call; the *_GBps entries are algorithmic bytes / time
     }
     print(json.dumps(line))
 

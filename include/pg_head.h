@@ -19,6 +19,7 @@
  *   turn_reward       per-turn reward with speedup cap and profiling ratio (Eq. 1, Eq. 6-7)
  *   prs_retain        profiling-based rejection sampling               (Sec. 5.2, Eq. 8)
  *   pg_monitors       entropy, perplexities and gradient norms         (Sec. 5.1)
+ *   pg_rmsnorm_fwd/bwd  the RMS normalisation in front of the head in the Qwen3 policies of Sec. 6.1
  *
  * Conventions
  *   - Every pointer is a DEVICE pointer unless its name starts with h_ (pg_params is
@@ -233,6 +234,24 @@ int32_t pg_monitors(const float* logp_train, const float* logp_rollout, const fl
                     const uint8_t* loss_mask, int64_t T, const void* dH, int32_t dH_dtype, int64_t dH_elems,
                     const void* dW, int32_t dW_dtype, int64_t dW_elems, double* out, void* workspace,
                     size_t workspace_bytes, void* stream);
+
+/*
+ * The step in front of the head in the policies the paper trains (Qwen3, Sec. 6.1): per row,
+ *   h = x * rstd * gamma,   rstd = 1 / sqrt(mean_j x_j^2 + eps),
+ * and its backward for g = dL/dh (e.g. dH of pg_loss_fwd_bwd):
+ *   xhat = x rstd,   dx = rstd (gamma g - xhat mean_j(gamma_j g_j xhat_j)),   dgamma = sum_rows g xhat.
+ * X, H_out, dH, dX_out are [T,d], gamma is [d], all in `dtype` (PG_DTYPE_*); arithmetic is fp32;
+ * rstd_out [T] float32 (nullable); dgamma_out [d] float32 (overwritten).  d must be a multiple of 8
+ * (and <= 8192 for the backward); X, gamma, H_out, dH, dX_out must be 16-byte aligned.  The backward
+ * needs pg_rmsnorm_bwd_workspace_bytes(d) bytes of workspace; its sums have a fixed order (bitwise
+ * repeatable).  dX_out may alias dH.
+ */
+int32_t pg_rmsnorm_fwd(const void* X, const void* gamma, int64_t T, int64_t d, float eps, int32_t dtype,
+                       void* H_out, float* rstd_out, void* stream);
+size_t pg_rmsnorm_bwd_workspace_bytes(int64_t d);
+int32_t pg_rmsnorm_bwd(const void* X, const void* gamma, const void* dH, int64_t T, int64_t d, float eps,
+                       int32_t dtype, void* dX_out, float* dgamma_out, void* workspace, size_t workspace_bytes,
+                       void* stream);
 
 /*
  * Measurement hooks (host-side state, not thread-safe; the only calls that create HIP events

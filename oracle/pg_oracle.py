@@ -24,6 +24,9 @@ Stages around the path (Sec. 3.3, 4.2, 5.1, 5.2 and App. ablations)
                                and the hard-threshold variant of the PRS ablation
   * monitors                -- Sec. 5.1: entropy, gradient norm and the perplexities of the
                                trainer's and the rollout engine's log-probs
+  * final RMSNorm           -- the trainer's step in front of the head (the policies of Sec. 6.1
+                               are Qwen3 models, whose last layer before the head is an RMSNorm);
+                               the paper does not mention it, the definition is the textbook one
 
 What the paper does not write down and is fixed here by definition (each is a
 stated reading, "parity unpinned" beyond self-consistency): the PPO-style
@@ -454,3 +457,29 @@ def monitors(logp_train, logp_rollout, entropy, loss_mask, dH=None, dW=None):
     out["dH_norm"] = float(np.sqrt((np.asarray(dH, np.float64) ** 2).sum())) if dH is not None else 0.0
     out["dW_norm"] = float(np.sqrt((np.asarray(dW, np.float64) ** 2).sum())) if dW is not None else 0.0
     return out
+
+
+# --------------------------------------------------------------------------
+# The step in front of the head in the Qwen3 policies of Sec. 6.1: root-mean-square
+# normalisation  h = x * rstd * gamma,  rstd = 1 / sqrt(mean_j x_j^2 + eps),  per row.
+# Backward, with g = dL/dh:  xhat = x * rstd,
+#   dx = rstd * (gamma g - xhat * mean_j(gamma_j g_j xhat_j)),   dgamma = sum_rows g * xhat.
+# --------------------------------------------------------------------------
+def rmsnorm_fwd(X, gamma, eps: float):
+    X = np.asarray(X, np.float64)
+    g = np.asarray(gamma, np.float64)
+    rstd = 1.0 / np.sqrt((X * X).mean(axis=1) + _f32(eps))
+    return X * rstd[:, None] * g[None, :], rstd
+
+
+def rmsnorm_bwd(X, gamma, eps: float, dH):
+    X = np.asarray(X, np.float64)
+    g = np.asarray(gamma, np.float64)
+    dH = np.asarray(dH, np.float64)
+    d = X.shape[1]
+    rstd = 1.0 / np.sqrt((X * X).mean(axis=1) + _f32(eps))
+    xhat = X * rstd[:, None]
+    gg = dH * g[None, :]
+    dX = rstd[:, None] * (gg - xhat * ((gg * xhat).sum(axis=1) / d)[:, None])
+    dgamma = (dH * xhat).sum(axis=0)
+    return dX, dgamma

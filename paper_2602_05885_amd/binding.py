@@ -23,7 +23,8 @@ COUNTER_NAMES = ("active", "clip_hi", "clip_lo", "seg_geo", "seg_veto", "truncat
 
 EXPORTS = ("pg_last_error", "pg_workspace_bytes", "trloo_advantage", "pg_logprob_fwd", "pg_loss_fwd_bwd",
            "pg_sft_fwd_bwd", "grpo_advantage", "turn_reward", "prs_retain", "pg_monitors_workspace_bytes",
-           "pg_monitors", "pg_profile_enable", "pg_profile_read")
+           "pg_monitors", "pg_rmsnorm_fwd", "pg_rmsnorm_bwd_workspace_bytes", "pg_rmsnorm_bwd",
+           "pg_profile_enable", "pg_profile_read")
 MONITOR_NAMES = ("entropy_mean", "ppl_train", "ppl_rollout", "dH_norm", "dW_norm", "n")
 KERNEL_CLASSES = ("fwd", "dlogits", "dw", "dh")
 
@@ -107,6 +108,14 @@ def lib() -> C.CDLL:
         L.pg_monitors.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_int32,
                                   C.c_int64, C.c_void_p, C.c_int32, C.c_int64, C.c_void_p, C.c_void_p, C.c_size_t,
                                   C.c_void_p]
+        L.pg_rmsnorm_fwd.restype = C.c_int32
+        L.pg_rmsnorm_fwd.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_float, C.c_int32, C.c_void_p,
+                                     C.c_void_p, C.c_void_p]
+        L.pg_rmsnorm_bwd_workspace_bytes.restype = C.c_size_t
+        L.pg_rmsnorm_bwd_workspace_bytes.argtypes = [C.c_int64]
+        L.pg_rmsnorm_bwd.restype = C.c_int32
+        L.pg_rmsnorm_bwd.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_float, C.c_int32,
+                                     C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
         L.pg_profile_enable.restype = C.c_int32
         L.pg_profile_enable.argtypes = [C.c_int32, C.c_int32]
         L.pg_profile_read.restype = C.c_int32
@@ -299,3 +308,33 @@ def pg_sft_fwd_bwd(H, W, y, loss_mask, params: Params, workspace: torch.Tensor, 
                                 _ptr(dW), _ptr(logp), _ptr(ent), _ptr(counters), _ptr(workspace), workspace.numel(),
                                 _stream(stream)))
     return dict(loss=loss, dH=dH, dW=dW, logp=logp, entropy=ent, counters=counters)
+
+
+def _norm_dtype(t: torch.Tensor) -> int:
+    assert t.dtype in (torch.bfloat16, torch.float32)
+    return 1 if t.dtype == torch.float32 else 0
+
+
+def pg_rmsnorm_fwd(X, gamma, eps: float, want_rstd=True, out=None, stream=None):
+    """h = x * rstd * gamma per row.  Returns (H in the dtype of X, rstd f32 [T] | None)."""
+    T, d = X.shape
+    assert gamma.dtype == X.dtype and gamma.numel() == d
+    H = torch.empty_like(X) if out is None else out
+    rstd = torch.empty(T, dtype=torch.float32, device=X.device) if want_rstd else None
+    _check(lib().pg_rmsnorm_fwd(_ptr(X), _ptr(gamma), T, d, eps, _norm_dtype(X), _ptr(H), _ptr(rstd), _stream(stream)))
+    return H, rstd
+
+
+def pg_rmsnorm_bwd(X, gamma, dH, eps: float, out=None, stream=None):
+    """Returns (dX in the dtype of X, dgamma f32 [d])."""
+    T, d = X.shape
+    assert gamma.dtype == X.dtype and dH.dtype == X.dtype and dH.shape == X.shape
+    dX = torch.empty_like(X) if out is None else out
+    dg = torch.empty(d, dtype=torch.float32, device=X.device)
+    n = int(lib().pg_rmsnorm_bwd_workspace_bytes(d))
+    if n == 0:
+        raise PgError(-2, f"d={d} is not supported by pg_rmsnorm_bwd")
+    ws = torch.empty(n, dtype=torch.uint8, device=X.device)
+    _check(lib().pg_rmsnorm_bwd(_ptr(X), _ptr(gamma), _ptr(dH), T, d, eps, _norm_dtype(X), _ptr(dX), _ptr(dg), _ptr(ws),
+                                ws.numel(), _stream(stream)))
+    return dX, dg

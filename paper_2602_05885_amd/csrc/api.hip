@@ -160,6 +160,7 @@ int32_t ensure_init() {
   if (dev < 0 || dev >= 64) return fail(PG_ERR_HIP, "device index %d out of range", dev);
   if (!done[dev]) {
     hipError_t e = pg::init_gemm_kernels();
+    if (e == hipSuccess) e = pg::init_row_kernels();
     if (e != hipSuccess) return fail(PG_ERR_HIP, "kernel attribute setup failed: %s", hipGetErrorString(e));
     done[dev] = true;
   }
@@ -400,6 +401,49 @@ int32_t pg_monitors(const float* logp_train, const float* logp_rollout, const fl
                     dW, dW_dtype, (long long)dW_elems, static_cast<double*>(workspace), out};
   pg::launch_monitors(a, static_cast<hipStream_t>(stream));
   return check_launches("pg_monitors");
+}
+
+int32_t pg_rmsnorm_fwd(const void* X, const void* gamma, int64_t T, int64_t d, float eps, int32_t dtype, void* H_out,
+                       float* rstd_out, void* stream) {
+  if (T < 0 || d < 1) return fail(PG_ERR_INVALID_ARG, "T must be >= 0 and d >= 1");
+  if (dtype != PG_DTYPE_BF16 && dtype != PG_DTYPE_F32) return fail(PG_ERR_INVALID_ARG, "unknown dtype %d", dtype);
+  if (d % 8 != 0 || d > (1 << 24)) return fail(PG_ERR_UNSUPPORTED_SHAPE, "d=%lld is not a multiple of 8", (long long)d);
+  if (!(eps >= 0.f) || !std::isfinite(eps)) return fail(PG_ERR_INVALID_ARG, "eps must be finite and >= 0");
+  if (T == 0) return PG_OK;
+  if (!X || !gamma || !H_out) return fail(PG_ERR_INVALID_ARG, "X, gamma and H_out must not be NULL");
+  if (misaligned(X) || misaligned(gamma) || misaligned(H_out)) return fail(PG_ERR_INVALID_ARG, "X, gamma and H_out must be 16-byte aligned");
+  pg::NormArgs a{};
+  a.X = X; a.gamma = gamma; a.T = T; a.d = (int)d; a.eps = eps; a.is_f32 = dtype == PG_DTYPE_F32;
+  a.H = H_out; a.rstd_out = rstd_out;
+  pg::launch_rmsnorm_fwd(a, static_cast<hipStream_t>(stream));
+  return check_launches("pg_rmsnorm_fwd");
+}
+
+size_t pg_rmsnorm_bwd_workspace_bytes(int64_t d) {
+  if (d < 1 || d % 8 != 0 || d > pg::NORM_MAX_D) return 0;
+  return (size_t)pg::NORM_BLOCKS * (size_t)d * sizeof(float);
+}
+
+int32_t pg_rmsnorm_bwd(const void* X, const void* gamma, const void* dH, int64_t T, int64_t d, float eps, int32_t dtype,
+                       void* dX_out, float* dgamma_out, void* workspace, size_t workspace_bytes, void* stream) {
+  if (T < 0 || d < 1) return fail(PG_ERR_INVALID_ARG, "T must be >= 0 and d >= 1");
+  if (dtype != PG_DTYPE_BF16 && dtype != PG_DTYPE_F32) return fail(PG_ERR_INVALID_ARG, "unknown dtype %d", dtype);
+  if (d % 8 != 0 || d > pg::NORM_MAX_D)
+    return fail(PG_ERR_UNSUPPORTED_SHAPE, "d=%lld must be a multiple of 8 and at most %d", (long long)d, pg::NORM_MAX_D);
+  if (!(eps >= 0.f) || !std::isfinite(eps)) return fail(PG_ERR_INVALID_ARG, "eps must be finite and >= 0");
+  if (!dgamma_out || !workspace) return fail(PG_ERR_INVALID_ARG, "dgamma_out and workspace must not be NULL");
+  if (T > 0 && (!X || !gamma || !dH || !dX_out)) return fail(PG_ERR_INVALID_ARG, "X, gamma, dH and dX_out must not be NULL");
+  if (misaligned(X) || misaligned(gamma) || misaligned(dH) || misaligned(dX_out) || misaligned(workspace))
+    return fail(PG_ERR_INVALID_ARG, "X, gamma, dH, dX_out and workspace must be 16-byte aligned");
+  if (workspace_bytes < pg_rmsnorm_bwd_workspace_bytes(d))
+    return fail(PG_ERR_WORKSPACE_TOO_SMALL, "workspace has %zu bytes, %zu needed", workspace_bytes, pg_rmsnorm_bwd_workspace_bytes(d));
+  int32_t rc = ensure_init();
+  if (rc) return rc;
+  pg::NormArgs a{};
+  a.X = X; a.gamma = gamma; a.T = T; a.d = (int)d; a.eps = eps; a.is_f32 = dtype == PG_DTYPE_F32;
+  a.dH = dH; a.dX = dX_out; a.partial = static_cast<float*>(workspace); a.dgamma = dgamma_out;
+  pg::launch_rmsnorm_bwd(a, static_cast<hipStream_t>(stream));
+  return check_launches("pg_rmsnorm_bwd");
 }
 
 }  // extern "C"

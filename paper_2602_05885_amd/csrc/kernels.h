@@ -201,6 +201,28 @@ struct MonitorArgs {
 };
 void launch_monitors(const MonitorArgs& a, hipStream_t s);
 
+constexpr int NORM_BLOCKS = 512;     // row strips of the RMSNorm backward (partial dgamma sums)
+constexpr int NORM_MAX_D = 8192;     // the backward keeps four fp32 copies of a dgamma strip in LDS
+hipError_t init_row_kernels();
+struct NormArgs {
+  const void* X;        // [T, d] bf16 or fp32
+  const void* gamma;    // [d]    same dtype
+  long long T;
+  int d;                // multiple of 8
+  float eps;
+  int is_f32;
+  // forward
+  void* H;              // [T, d] same dtype
+  float* rstd_out;      // [T], nullable
+  // backward
+  const void* dH;       // [T, d] same dtype
+  void* dX;             // [T, d] same dtype
+  float* partial;       // [NORM_BLOCKS, d]
+  float* dgamma;        // [d]
+};
+void launch_rmsnorm_fwd(const NormArgs& a, hipStream_t s);
+void launch_rmsnorm_bwd(const NormArgs& a, hipStream_t s);
+
 void launch_fill_f32(float* p, size_t n, float v, hipStream_t s);
 void launch_fill_zero_bytes(void* p, size_t nbytes, hipStream_t s);   // nbytes multiple of 4
 

@@ -616,4 +616,141 @@ void launch_monitors(const MonitorArgs& a, hipStream_t s) {
   hipLaunchKernelGGL(monitors_final_kernel, dim3(1), dim3(256), 0, s, a);
 }
 
+// ------------------------------------------------------------------ RMSNorm in front of the head
+// h = x * rstd * gamma, rstd = 1 / sqrt(mean x^2 + eps).  One wavefront per row, 16-byte (bf16) or
+// 32-byte (fp32) accesses of 8 consecutive elements per lane and step; fp32 arithmetic, the sum of
+// squares reduced in a fixed butterfly order.  Both kernels read their rows twice (the second
+// read comes from L2); they are HBM-bound.
+template <bool F32>
+__device__ __forceinline__ void load8(const void* p, long long elem, float (&v)[8]) {
+  if (F32) {
+    const float4 a = *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(p) + elem);
+    const float4 b = *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(p) + elem + 4);
+    v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+  } else {
+    const bf16x8 a = *reinterpret_cast<const bf16x8*>(reinterpret_cast<const __bf16*>(p) + elem);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] = (float)a[e];
+  }
+}
+template <bool F32>
+__device__ __forceinline__ void store8(void* p, long long elem, const float (&v)[8]) {
+  if (F32) {
+    *reinterpret_cast<float4*>(reinterpret_cast<float*>(p) + elem) = make_float4(v[0], v[1], v[2], v[3]);
+    *reinterpret_cast<float4*>(reinterpret_cast<float*>(p) + elem + 4) = make_float4(v[4], v[5], v[6], v[7]);
+  } else {
+    bf16x8 a;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) a[e] = (__bf16)v[e];
+    *reinterpret_cast<bf16x8*>(reinterpret_cast<__bf16*>(p) + elem) = a;
+  }
+}
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int sh = 32; sh >= 1; sh >>= 1) v += __shfl_xor(v, sh);
+  return v;
+}
+template <bool F32>
+__device__ __forceinline__ float row_rstd(const void* X, long long row, int d, float eps, int lane) {
+  float ss = 0.f;
+  for (int c = lane * 8; c < d; c += 64 * 8) {
+    float x[8];
+    load8<F32>(X, row * d + c, x);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) ss = fmaf(x[e], x[e], ss);
+  }
+  ss = wave_sum(ss);
+  return 1.f / sqrtf(ss / (float)d + eps);
+}
+
+template <bool F32>
+__global__ __launch_bounds__(256) void rmsnorm_fwd_kernel(NormArgs a) {
+  const int lane = threadIdx.x & 63;
+  const long long row = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= a.T) return;
+  const float rstd = row_rstd<F32>(a.X, row, a.d, a.eps, lane);
+  if (a.rstd_out && lane == 0) a.rstd_out[row] = rstd;
+  for (int c = lane * 8; c < a.d; c += 64 * 8) {
+    float x[8], g[8], h[8];
+    load8<F32>(a.X, row * a.d + c, x);
+    load8<F32>(a.gamma, c, g);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) h[e] = x[e] * rstd * g[e];
+    store8<F32>(a.H, row * a.d + c, h);
+  }
+}
+void launch_rmsnorm_fwd(const NormArgs& a, hipStream_t s) {
+  if (a.T <= 0) return;
+  const unsigned grid = (unsigned)((a.T + 3) / 4);
+  if (a.is_f32) hipLaunchKernelGGL(rmsnorm_fwd_kernel<true>, dim3(grid), dim3(256), 0, s, a);
+  else hipLaunchKernelGGL(rmsnorm_fwd_kernel<false>, dim3(grid), dim3(256), 0, s, a);
+}
+
+// Backward: dx = rstd (gamma g - xhat mean(gamma g xhat)), xhat = x rstd; dgamma = sum_rows g xhat.
+// Workgroup b owns the contiguous strip of rows [b R, (b+1) R); its four wavefronts take the
+// strip's rows round-robin, each adding g xhat into its own LDS copy of the dgamma partial (a lane
+// owns its columns, so there is no race); the copies are folded in a fixed order, the strips by
+// the second kernel.
+template <bool F32>
+__global__ __launch_bounds__(256) void rmsnorm_bwd_kernel(NormArgs a) {
+  extern __shared__ float sh_dg[];                 // [4][d]
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const long long R = (a.T + NORM_BLOCKS - 1) / NORM_BLOCKS;
+  const long long r0 = (long long)blockIdx.x * R, r1 = r0 + R < a.T ? r0 + R : a.T;
+  for (int c = threadIdx.x; c < 4 * a.d; c += 256) sh_dg[c] = 0.f;
+  __syncthreads();
+  float* mine = sh_dg + (size_t)wave * a.d;
+  for (long long row = r0 + wave; row < r1; row += 4) {
+    const float rstd = row_rstd<F32>(a.X, row, a.d, a.eps, lane);
+    float dot = 0.f;
+    for (int c = lane * 8; c < a.d; c += 512) {
+      float x[8], g[8], gr[8];
+      load8<F32>(a.X, row * a.d + c, x);
+      load8<F32>(a.gamma, c, g);
+      load8<F32>(a.dH, row * a.d + c, gr);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) dot = fmaf(g[e] * gr[e], x[e] * rstd, dot);
+    }
+    dot = wave_sum(dot) / (float)a.d;
+    for (int c = lane * 8; c < a.d; c += 512) {
+      float x[8], g[8], gr[8], dx[8];
+      load8<F32>(a.X, row * a.d + c, x);
+      load8<F32>(a.gamma, c, g);
+      load8<F32>(a.dH, row * a.d + c, gr);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const float xh = x[e] * rstd;
+        dx[e] = rstd * (g[e] * gr[e] - xh * dot);
+        mine[c + e] = fmaf(gr[e], xh, mine[c + e]);
+      }
+      store8<F32>(a.dX, row * a.d + c, dx);
+    }
+  }
+  __syncthreads();
+  float* part = a.partial + (size_t)blockIdx.x * a.d;
+  for (int c = threadIdx.x; c < a.d; c += 256)
+    part[c] = ((sh_dg[c] + sh_dg[a.d + c]) + sh_dg[2 * a.d + c]) + sh_dg[3 * a.d + c];
+}
+
+__global__ __launch_bounds__(256) void rmsnorm_dgamma_kernel(NormArgs a) {
+  const int c = blockIdx.x * 256 + threadIdx.x;
+  if (c >= a.d) return;
+  float acc = 0.f;
+  for (int b = 0; b < NORM_BLOCKS; ++b) acc += a.partial[(size_t)b * a.d + c];
+  a.dgamma[c] = acc;
+}
+hipError_t init_row_kernels() {
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(rmsnorm_bwd_kernel<true>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, 4 * NORM_MAX_D * (int)sizeof(float));
+  if (e != hipSuccess) return e;
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(rmsnorm_bwd_kernel<false>),
+                             hipFuncAttributeMaxDynamicSharedMemorySize, 4 * NORM_MAX_D * (int)sizeof(float));
+}
+void launch_rmsnorm_bwd(const NormArgs& a, hipStream_t s) {
+  const size_t lds = (size_t)4 * a.d * sizeof(float);
+  if (a.is_f32) hipLaunchKernelGGL(rmsnorm_bwd_kernel<true>, dim3(NORM_BLOCKS), dim3(256), lds, s, a);
+  else hipLaunchKernelGGL(rmsnorm_bwd_kernel<false>, dim3(NORM_BLOCKS), dim3(256), lds, s, a);
+  hipLaunchKernelGGL(rmsnorm_dgamma_kernel, dim3((a.d + 255) / 256), dim3(256), 0, s, a);
+}
+
 }  // namespace pg

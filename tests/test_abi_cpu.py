@@ -100,3 +100,17 @@ def test_stage_entry_points_validate_arguments():
     assert rc == -1 and "NULL" in B.pg_last_error()
     rc = lib.pg_sft_fwd_bwd(one, one, one, one, 8, 64, 100, C.byref(p), one, one, one, None, None, None, one, 16, None)
     assert rc == -3
+
+
+def test_rmsnorm_entry_points_validate_arguments():
+    lib = B.lib()
+    one = C.c_void_p(16)
+    assert lib.pg_rmsnorm_fwd(one, one, 4, 100, 1e-6, 0, one, None, None) == -2         # d not a multiple of 8
+    assert lib.pg_rmsnorm_fwd(one, one, 4, 64, 1e-6, 7, one, None, None) == -1
+    assert lib.pg_rmsnorm_fwd(None, one, 4, 64, 1e-6, 0, one, None, None) == -1
+    assert lib.pg_rmsnorm_fwd(None, None, 0, 64, 1e-6, 0, None, None, None) == 0
+    assert int(lib.pg_rmsnorm_bwd_workspace_bytes(5120)) == 512 * 5120 * 4
+    assert int(lib.pg_rmsnorm_bwd_workspace_bytes(8200)) == 0
+    assert lib.pg_rmsnorm_bwd(one, one, one, 4, 16384, 1e-6, 0, one, one, one, 1 << 30, None) == -2
+    assert lib.pg_rmsnorm_bwd(one, one, one, 4, 64, 1e-6, 0, one, one, one, 16, None) == -3
+    assert lib.pg_rmsnorm_bwd(one, one, one, 4, 64, -1.0, 0, one, one, one, 1 << 30, None) == -1

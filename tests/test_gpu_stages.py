@@ -151,3 +151,55 @@ def test_monitors_parity(dev, T, d, V, gdtype, seed):
     o2 = out2.cpu().numpy()
     assert o2[0] == 0 and o2[2] == 0 and o2[3] == 0 and o2[4] == 0 and abs(o2[1] - ref["ppl_train"]) <= 1e-9 * ref["ppl_train"]
     assert torch.equal(out, out3)
+
+
+# ------------------------------------------------------------------------------------ RMSNorm
+@pytest.mark.parametrize("T,d,dtype,seed", [(1, 64, torch.float32, 0), (37, 520, torch.float32, 1),
+                                            (1000, 5120, torch.bfloat16, 2), (4099, 4096, torch.bfloat16, 3),
+                                            (513, 8192, torch.bfloat16, 4)])
+def test_rmsnorm_parity(dev, T, d, dtype, seed):
+    rng = np.random.default_rng(seed)
+    eps = 1e-6
+    X = torch.from_numpy((rng.normal(size=(T, d)) * rng.uniform(0.2, 4.0, size=(T, 1))).astype(np.float32)).to(dev).to(dtype)
+    gamma = torch.from_numpy(rng.normal(1.0, 0.2, size=d).astype(np.float32)).to(dev).to(dtype)
+    G = torch.from_numpy((rng.normal(size=(T, d)) * 1e-3).astype(np.float32)).to(dev).to(dtype)
+    H, rstd = B.pg_rmsnorm_fwd(X, gamma, eps)
+    dX, dg = B.pg_rmsnorm_bwd(X, gamma, G, eps)
+    dX2, dg2 = B.pg_rmsnorm_bwd(X, gamma, G, eps)
+    torch.cuda.synchronize()
+    H_ref, rstd_ref = O.rmsnorm_fwd(np64(X), np64(gamma), eps)
+    dX_ref, dg_ref = O.rmsnorm_bwd(np64(X), np64(gamma), eps, np64(G))
+    tol = 1e-5 if dtype == torch.float32 else 3e-3          # output rounding to bf16: 2^-9 per element
+    assert rel_fro(np64(H), H_ref) <= tol
+    assert np.abs(rstd.cpu().numpy() / rstd_ref - 1).max() <= 1e-5
+    assert rel_fro(np64(dX), dX_ref) <= tol
+    assert rel_fro(dg.double().cpu().numpy(), dg_ref) <= 1e-4
+    assert torch.equal(dX, dX2) and torch.equal(dg, dg2)      # fixed reduction order
+    # in place on the incoming gradient
+    Gc = G.clone()
+    dX3, _ = B.pg_rmsnorm_bwd(X, gamma, Gc, eps, out=Gc)
+    torch.cuda.synchronize()
+    assert torch.equal(dX3, dX)
+
+
+def test_rmsnorm_feeds_the_head(dev):
+    """x -> RMSNorm -> fused head loss -> dH -> RMSNorm backward: the chain against the oracle's chain."""
+    T, d, V = 600, 256, 3000
+    rng = np.random.default_rng(5)
+    X = torch.from_numpy((rng.normal(size=(T, d)) * 3.0).astype(np.float32)).to(dev).bfloat16()
+    gamma = torch.from_numpy(rng.normal(1.0, 0.1, size=d).astype(np.float32)).to(dev).bfloat16()
+    _, W, y = synth.make_head(T, d, V, "bf16", 31, dev, unit_rms=True)
+    mask = (rng.random(T) < 0.8).astype(np.uint8)
+    H, _ = B.pg_rmsnorm_fwd(X, gamma, 1e-6, want_rstd=False)
+    prm = B.Params()
+    ws = B.alloc_workspace(T, d, V, 0, prm, B.CALL_LOSS_FWD_BWD, dev)
+    out = B.pg_sft_fwd_bwd(H, W, y, torch.from_numpy(mask).to(dev), prm, ws)
+    dX, dg = B.pg_rmsnorm_bwd(X, gamma, out["dH"], 1e-6)
+    torch.cuda.synchronize()
+    H_ref, _ = O.rmsnorm_fwd(np64(X), np64(gamma), 1e-6)
+    H_bits = torch.from_numpy(H_ref).bfloat16().double().numpy()          # the head sees bf16 hidden states
+    ref = O.sft_ce_fwd_bwd(H_bits, np64(W), y.cpu().numpy(), mask)
+    dX_ref, dg_ref = O.rmsnorm_bwd(np64(X), np64(gamma), 1e-6, ref["dH"])
+    assert abs(float(out["loss"][0]) - ref["loss"]) <= TOL_LOSS * abs(ref["loss"])
+    assert rel_fro(np64(dX), dX_ref) <= TOL_GRAD
+    assert rel_fro(dg.double().cpu().numpy(), dg_ref) <= TOL_GRAD

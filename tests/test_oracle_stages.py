@@ -164,3 +164,43 @@ def test_monitors_closed_forms():
     # masked tokens do not count
     logp2 = logp.copy(); logp2[mask == 0] = -50.0
     assert abs(O.monitors(logp2, None, None, mask)["ppl_train"] - V) < 1e-9
+
+
+# ---------------------------------------------------------------- RMSNorm in front of the head
+def test_rmsnorm_against_library_autograd():
+    rng = np.random.default_rng(0)
+    T, d, eps = 13, 48, 1e-6
+    X = rng.normal(size=(T, d)) * rng.uniform(0.1, 5.0, size=(T, 1))
+    gamma = rng.normal(1.0, 0.2, size=d)
+    G = rng.normal(size=(T, d))
+    Xt = torch.tensor(X, requires_grad=True)
+    gt = torch.tensor(gamma, requires_grad=True)
+    h = torch.nn.functional.rms_norm(Xt, (d,), gt, eps=float(np.float32(eps)))
+    (h * torch.tensor(G)).sum().backward()
+    H, rstd = O.rmsnorm_fwd(X, gamma, eps)
+    dX, dg = O.rmsnorm_bwd(X, gamma, eps, G)
+    np.testing.assert_allclose(H, h.detach().numpy(), atol=1e-12)
+    np.testing.assert_allclose(dX, Xt.grad.numpy(), atol=1e-12)
+    np.testing.assert_allclose(dg, gt.grad.numpy(), atol=1e-12)
+
+
+def test_rmsnorm_invariants():
+    rng = np.random.default_rng(1)
+    T, d = 7, 64
+    X = rng.normal(size=(T, d))
+    gamma = rng.normal(1.0, 0.3, size=d)
+    G = rng.normal(size=(T, d))
+    H, rstd = O.rmsnorm_fwd(X, gamma, 0.0)
+    H2, _ = O.rmsnorm_fwd(3.7 * X, gamma, 0.0)
+    np.testing.assert_allclose(H, H2, atol=1e-12)                       # scale invariance at eps = 0
+    np.testing.assert_allclose(((H / gamma) ** 2).mean(axis=1), 1.0, atol=1e-12)   # unit RMS before the gain
+    dX, dg = O.rmsnorm_bwd(X, gamma, 0.0, G)
+    np.testing.assert_allclose((dX * X).sum(axis=1), 0.0, atol=1e-12)   # hence the gradient is orthogonal to x
+    Xu = X / np.sqrt((X * X).mean(axis=1, keepdims=True))
+    Hu, _ = O.rmsnorm_fwd(Xu, np.ones(d), 0.0)
+    np.testing.assert_allclose(Hu, Xu, atol=1e-12)                      # unit-RMS rows, unit gain: identity
+    # central finite difference of <G, h(x)> in one coordinate
+    e = np.zeros_like(X); e[2, 5] = 1e-6
+    f = lambda Z: (O.rmsnorm_fwd(Z, gamma, 1e-6)[0] * G).sum()
+    fd = (f(X + e) - f(X - e)) / 2e-6
+    assert abs(fd - O.rmsnorm_bwd(X, gamma, 1e-6, G)[0][2, 5]) < 1e-6
