@@ -160,7 +160,6 @@ int32_t ensure_init() {
   if (dev < 0 || dev >= 64) return fail(PG_ERR_HIP, "device index %d out of range", dev);
   if (!done[dev]) {
     hipError_t e = pg::init_gemm_kernels();
-    if (e == hipSuccess) e = pg::init_row_kernels();
     if (e != hipSuccess) return fail(PG_ERR_HIP, "kernel attribute setup failed: %s", hipGetErrorString(e));
     done[dev] = true;
   }
@@ -421,7 +420,7 @@ int32_t pg_rmsnorm_fwd(const void* X, const void* gamma, int64_t T, int64_t d, f
 
 size_t pg_rmsnorm_bwd_workspace_bytes(int64_t d) {
   if (d < 1 || d % 8 != 0 || d > pg::NORM_MAX_D) return 0;
-  return (size_t)pg::NORM_BLOCKS * (size_t)d * sizeof(float);
+  return (size_t)pg::NORM_STRIPS * (size_t)d * sizeof(float);
 }
 
 int32_t pg_rmsnorm_bwd(const void* X, const void* gamma, const void* dH, int64_t T, int64_t d, float eps, int32_t dtype,
@@ -437,8 +436,6 @@ int32_t pg_rmsnorm_bwd(const void* X, const void* gamma, const void* dH, int64_t
     return fail(PG_ERR_INVALID_ARG, "X, gamma, dH, dX_out and workspace must be 16-byte aligned");
   if (workspace_bytes < pg_rmsnorm_bwd_workspace_bytes(d))
     return fail(PG_ERR_WORKSPACE_TOO_SMALL, "workspace has %zu bytes, %zu needed", workspace_bytes, pg_rmsnorm_bwd_workspace_bytes(d));
-  int32_t rc = ensure_init();
-  if (rc) return rc;
   pg::NormArgs a{};
   a.X = X; a.gamma = gamma; a.T = T; a.d = (int)d; a.eps = eps; a.is_f32 = dtype == PG_DTYPE_F32;
   a.dH = dH; a.dX = dX_out; a.partial = static_cast<float*>(workspace); a.dgamma = dgamma_out;

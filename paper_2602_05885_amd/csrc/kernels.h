@@ -201,9 +201,8 @@ struct MonitorArgs {
 };
 void launch_monitors(const MonitorArgs& a, hipStream_t s);
 
-constexpr int NORM_BLOCKS = 512;     // row strips of the RMSNorm backward (partial dgamma sums)
-constexpr int NORM_MAX_D = 8192;     // the backward keeps four fp32 copies of a dgamma strip in LDS
-hipError_t init_row_kernels();
+constexpr int NORM_STRIPS = 1024;    // row strips of the RMSNorm backward (one workgroup and one dgamma partial each)
+constexpr int NORM_MAX_D = 8192;     // the backward keeps a row in registers: 4 x 8 columns per thread of 256
 struct NormArgs {
   const void* X;        // [T, d] bf16 or fp32
   const void* gamma;    // [d]    same dtype
@@ -217,7 +216,7 @@ struct NormArgs {
   // backward
   const void* dH;       // [T, d] same dtype
   void* dX;             // [T, d] same dtype
-  float* partial;       // [NORM_BLOCKS, d]
+  float* partial;       // [NORM_STRIPS, d]
   float* dgamma;        // [d]
 };
 void launch_rmsnorm_fwd(const NormArgs& a, hipStream_t s);

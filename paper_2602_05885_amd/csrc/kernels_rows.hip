@@ -687,70 +687,112 @@ void launch_rmsnorm_fwd(const NormArgs& a, hipStream_t s) {
 }
 
 // Backward: dx = rstd (gamma g - xhat mean(gamma g xhat)), xhat = x rstd; dgamma = sum_rows g xhat.
-// Workgroup b owns the contiguous strip of rows [b R, (b+1) R); its four wavefronts take the
-// strip's rows round-robin, each adding g xhat into its own LDS copy of the dgamma partial (a lane
-// owns its columns, so there is no race); the copies are folded in a fixed order, the strips by
-// the second kernel.
-template <bool F32>
-__global__ __launch_bounds__(256) void rmsnorm_bwd_kernel(NormArgs a) {
-  extern __shared__ float sh_dg[];                 // [4][d]
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const long long R = (a.T + NORM_BLOCKS - 1) / NORM_BLOCKS;
-  const long long r0 = (long long)blockIdx.x * R, r1 = r0 + R < a.T ? r0 + R : a.T;
-  for (int c = threadIdx.x; c < 4 * a.d; c += 256) sh_dg[c] = 0.f;
+// Workgroup b owns the contiguous strip of rows [b R, (b+1) R) and walks it row by row; a thread
+// owns the same (up to) 4 x 8 columns of every row, holds x and g of the current row in registers
+// (each element is read once) and keeps the dgamma partial sums of its columns in registers.  The
+// two row sums (x^2 and gamma g xhat) are reduced over the workgroup in a fixed order.  The
+// strips' partials are folded by the second kernel.
+constexpr int NORM_NC = NORM_MAX_D / 2048;         // 8-column steps per thread
+
+__device__ __forceinline__ float block_sum4(float v, float* red, int lane, int wave) {
+  v = wave_sum(v);
+  if (lane == 0) red[wave] = v;
   __syncthreads();
-  float* mine = sh_dg + (size_t)wave * a.d;
-  for (long long row = r0 + wave; row < r1; row += 4) {
-    const float rstd = row_rstd<F32>(a.X, row, a.d, a.eps, lane);
-    float dot = 0.f;
-    for (int c = lane * 8; c < a.d; c += 512) {
-      float x[8], g[8], gr[8];
-      load8<F32>(a.X, row * a.d + c, x);
-      load8<F32>(a.gamma, c, g);
-      load8<F32>(a.dH, row * a.d + c, gr);
-#pragma unroll
-      for (int e = 0; e < 8; ++e) dot = fmaf(g[e] * gr[e], x[e] * rstd, dot);
-    }
-    dot = wave_sum(dot) / (float)a.d;
-    for (int c = lane * 8; c < a.d; c += 512) {
-      float x[8], g[8], gr[8], dx[8];
-      load8<F32>(a.X, row * a.d + c, x);
-      load8<F32>(a.gamma, c, g);
-      load8<F32>(a.dH, row * a.d + c, gr);
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const float xh = x[e] * rstd;
-        dx[e] = rstd * (g[e] * gr[e] - xh * dot);
-        mine[c + e] = fmaf(gr[e], xh, mine[c + e]);
-      }
-      store8<F32>(a.dX, row * a.d + c, dx);
-    }
-  }
-  __syncthreads();
-  float* part = a.partial + (size_t)blockIdx.x * a.d;
-  for (int c = threadIdx.x; c < a.d; c += 256)
-    part[c] = ((sh_dg[c] + sh_dg[a.d + c]) + sh_dg[2 * a.d + c]) + sh_dg[3 * a.d + c];
+  return (red[0] + red[1]) + (red[2] + red[3]);
 }
 
+template <bool F32>
+__global__ __launch_bounds__(256) void rmsnorm_bwd_kernel(NormArgs a) {
+  __shared__ float red[2][4];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const long long R = (a.T + NORM_STRIPS - 1) / NORM_STRIPS;
+  const long long r0 = (long long)blockIdx.x * R, r1 = r0 + R < a.T ? r0 + R : a.T;
+  float dg[NORM_NC][8], g[NORM_NC][8];
+#pragma unroll
+  for (int q = 0; q < NORM_NC; ++q) {
+    const int c = tid * 8 + q * 2048;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { dg[q][e] = 0.f; g[q][e] = 0.f; }
+    if (c < a.d) load8<F32>(a.gamma, c, g[q]);
+  }
+  const float inv_d = 1.f / (float)a.d;
+  for (long long row = r0; row < r1; ++row) {
+    float x[NORM_NC][8], gr[NORM_NC][8];
+    float ss = 0.f;
+#pragma unroll
+    for (int q = 0; q < NORM_NC; ++q) {
+      const int c = tid * 8 + q * 2048;
+      if (c < a.d) {
+        load8<F32>(a.X, row * a.d + c, x[q]);
+        load8<F32>(a.dH, row * a.d + c, gr[q]);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) ss = fmaf(x[q][e], x[q][e], ss);
+      }
+    }
+    const float rstd = 1.f / sqrtf(block_sum4(ss, red[0], lane, wave) * inv_d + a.eps);
+    float dot = 0.f;
+#pragma unroll
+    for (int q = 0; q < NORM_NC; ++q) {
+      const int c = tid * 8 + q * 2048;
+      if (c < a.d) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) dot = fmaf(g[q][e] * gr[q][e], x[q][e] * rstd, dot);
+      }
+    }
+    dot = block_sum4(dot, red[1], lane, wave) * inv_d;
+#pragma unroll
+    for (int q = 0; q < NORM_NC; ++q) {
+      const int c = tid * 8 + q * 2048;
+      if (c < a.d) {
+        float dx[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const float xh = x[q][e] * rstd;
+          dx[e] = rstd * (g[q][e] * gr[q][e] - xh * dot);
+          dg[q][e] = fmaf(gr[q][e], xh, dg[q][e]);
+        }
+        store8<F32>(a.dX, row * a.d + c, dx);
+      }
+    }
+  }
+  float* part = a.partial + (size_t)blockIdx.x * a.d;
+#pragma unroll
+  for (int q = 0; q < NORM_NC; ++q) {
+    const int c = tid * 8 + q * 2048;
+    if (c < a.d) {
+      *reinterpret_cast<float4*>(part + c) = make_float4(dg[q][0], dg[q][1], dg[q][2], dg[q][3]);
+      *reinterpret_cast<float4*>(part + c + 4) = make_float4(dg[q][4], dg[q][5], dg[q][6], dg[q][7]);
+    }
+  }
+}
+
+// dgamma[c] = sum over the strips' partials, in a fixed order: workgroup = 32 columns x 8 strip
+// groups; group k adds strips k, k+8, ... in four interleaved chains, then the groups are folded.
 __global__ __launch_bounds__(256) void rmsnorm_dgamma_kernel(NormArgs a) {
-  const int c = blockIdx.x * 256 + threadIdx.x;
-  if (c >= a.d) return;
-  float acc = 0.f;
-  for (int b = 0; b < NORM_BLOCKS; ++b) acc += a.partial[(size_t)b * a.d + c];
-  a.dgamma[c] = acc;
+  __shared__ float sh[8][32];
+  const int col = threadIdx.x & 31, grp = threadIdx.x >> 5;
+  const int c = blockIdx.x * 32 + col;
+  float acc[4] = {0.f, 0.f, 0.f, 0.f};
+  if (c < a.d) {
+    for (int b = grp; b < NORM_STRIPS; b += 32)
+#pragma unroll
+      for (int k = 0; k < 4; ++k) acc[k] += a.partial[(size_t)(b + 8 * k) * a.d + c];
+  }
+  sh[grp][col] = (acc[0] + acc[1]) + (acc[2] + acc[3]);
+  __syncthreads();
+  if (grp == 0 && c < a.d) {
+    float v = 0.f;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) v += sh[k][col];
+    a.dgamma[c] = v;
+  }
 }
-hipError_t init_row_kernels() {
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(rmsnorm_bwd_kernel<true>),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, 4 * NORM_MAX_D * (int)sizeof(float));
-  if (e != hipSuccess) return e;
-  return hipFuncSetAttribute(reinterpret_cast<const void*>(rmsnorm_bwd_kernel<false>),
-                             hipFuncAttributeMaxDynamicSharedMemorySize, 4 * NORM_MAX_D * (int)sizeof(float));
-}
+static_assert(NORM_STRIPS % 32 == 0, "strip groups");
+
 void launch_rmsnorm_bwd(const NormArgs& a, hipStream_t s) {
-  const size_t lds = (size_t)4 * a.d * sizeof(float);
-  if (a.is_f32) hipLaunchKernelGGL(rmsnorm_bwd_kernel<true>, dim3(NORM_BLOCKS), dim3(256), lds, s, a);
-  else hipLaunchKernelGGL(rmsnorm_bwd_kernel<false>, dim3(NORM_BLOCKS), dim3(256), lds, s, a);
-  hipLaunchKernelGGL(rmsnorm_dgamma_kernel, dim3((a.d + 255) / 256), dim3(256), 0, s, a);
+  if (a.is_f32) hipLaunchKernelGGL(rmsnorm_bwd_kernel<true>, dim3(NORM_STRIPS), dim3(256), 0, s, a);
+  else hipLaunchKernelGGL(rmsnorm_bwd_kernel<false>, dim3(NORM_STRIPS), dim3(256), 0, s, a);
+  hipLaunchKernelGGL(rmsnorm_dgamma_kernel, dim3((a.d + 31) / 32), dim3(256), 0, s, a);
 }
 
 }  // namespace pg

@@ -109,7 +109,7 @@ def test_rmsnorm_entry_points_validate_arguments():
     assert lib.pg_rmsnorm_fwd(one, one, 4, 64, 1e-6, 7, one, None, None) == -1
     assert lib.pg_rmsnorm_fwd(None, one, 4, 64, 1e-6, 0, one, None, None) == -1
     assert lib.pg_rmsnorm_fwd(None, None, 0, 64, 1e-6, 0, None, None, None) == 0
-    assert int(lib.pg_rmsnorm_bwd_workspace_bytes(5120)) == 512 * 5120 * 4
+    assert int(lib.pg_rmsnorm_bwd_workspace_bytes(5120)) == 1024 * 5120 * 4
     assert int(lib.pg_rmsnorm_bwd_workspace_bytes(8200)) == 0
     assert lib.pg_rmsnorm_bwd(one, one, one, 4, 16384, 1e-6, 0, one, one, one, 1 << 30, None) == -2
     assert lib.pg_rmsnorm_bwd(one, one, one, 4, 64, 1e-6, 0, one, one, one, 16, None) == -3
