@@ -225,3 +225,45 @@ def test_repeatable_bitwise(dev):
     b, _, _ = _run_loss(dev, spec, B.Params(mismatch_mode=2), "token", on_policy=False)
     for k in ("loss", "dH", "dW", "logp", "entropy", "counters"):
         assert torch.equal(a[k], b[k]), k
+
+
+def test_hip_graph_replay_matches_eager(dev):
+    """The whole step (advantages + loss forward/backward) captured in a HIP graph: the library enqueues
+    only kernels on the caller's stream, so a replay must reproduce the eager result bit for bit, also
+    after other work has run in between."""
+    spec = synth.small_spec(seed=4321)
+    batch, tin, nin = build_loss_case(spec, dev, oracle_logp, mismatch_kind="token")
+    prm = B.Params(mismatch_mode=2)
+    T, d, V, S = batch.T, spec.d, spec.V, batch.S
+    ws = B.alloc_workspace(T, d, V, S, prm, B.CALL_LOSS_FWD_BWD, dev)
+    adv = torch.empty((batch.P, batch.K, batch.Tmax), dtype=torch.float64, device=dev)
+    dW = torch.empty((V, d), dtype=torch.float32, device=dev)
+    outbuf = (torch.empty(1, dtype=torch.float32, device=dev), torch.empty_like(tin["H"]),
+              torch.empty(T, dtype=torch.float32, device=dev), torch.empty(T, dtype=torch.float32, device=dev),
+              torch.empty(8, dtype=torch.int64, device=dev))
+
+    def step(stream=None):
+        B._check(B.lib().trloo_advantage(B._ptr(tin["rewards"]), B._ptr(tin["valid"]), batch.P, batch.K, batch.Tmax, 1.0,
+                                         None, B._ptr(adv), None, B._stream(stream)))
+        return B.pg_loss_fwd_bwd(tin["H"], tin["W"], tin["y"], tin["loss_mask"], tin["cu"], adv.reshape(-1),
+                                 tin["seg_sample"], tin["old"], tin["rollout"], prm, ws, dW=dW, out=outbuf, stream=stream)
+
+    out = step()                                   # eager (also initialises the kernel attributes)
+    torch.cuda.synchronize()
+    eager = {k: v.clone() for k, v in out.items()}
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            step(side)
+    for rep in range(3):
+        for t in outbuf:
+            t.zero_()
+        dW.zero_()
+        ws.random_(0, 255)                         # the workspace holds nothing between calls
+        graph.replay()
+        torch.cuda.synchronize()
+        for k in ("loss", "dH", "dW", "logp", "entropy", "counters"):
+            assert torch.equal(out[k], eager[k]), (rep, k)
+        _ = (tin["H"].float() @ tin["W"].float().T).sum()      # unrelated work between replays
+        torch.cuda.synchronize()
