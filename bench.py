@@ -28,8 +28,8 @@ PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA peak (published)
 # summarised in profiles/gemm_store_kernel_hbm_traffic.md (mean over a step's 14 launches, each
 # counter scaled by what it reads for a plain 1 GiB copy).  Valid only for the kernel sources the
 # counters were taken with: the digest below is of csrc/gemm_core.h + csrc/kernels_gemm.hip.
-TRAFFIC_GEMM_STORE = {"read_bytes": 6202174.4 * 1024 * 2.000, "write_bytes": 655465.0 * 1024 * 1.000,
-                      "sources_sha256": "031e97470876e5dbc1bab75625d4386e56714c75f593e390a301a963ed3f6eeb"}
+TRAFFIC_GEMM_STORE = {"read_bytes": 5874220.5 * 1024 * 2.000, "write_bytes": 659024.3 * 1024 * 1.000,
+                      "sources_sha256": "91d3411a36bf9db4e2c5744e642764b9ef3473a3cf4f233a66452180cd01b413"}
 
 
 def kernel_sources_digest() -> str:
