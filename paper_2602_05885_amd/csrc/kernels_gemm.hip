@@ -1,10 +1,12 @@
 // The three MFMA kernels of the policy-gradient head (see gemm_core.h for the tile engine).
 //
 // Accumulator layout they all rely on: acc[i][j][r] of lane l is
-//   vocab-like row  m = wm*64  + i*16 + 4*(l>>4) + r      (i < 4, r < 4)
-//   token-like col  n = wn*128 + j*16 + (l & 15)          (j < 8)
-// so one lane holds 16 m-values of each of its 8 columns, and the four 16-lane groups of a
-// wavefront hold the other 48 m-values of the same columns.
+//   engine row     wm*64  + i*16 + 4*(l>>4) + r      (i < 4, r < 4)
+//   engine column  wn*128 + j*16 + (l & 15)          (j < 8)
+// so one lane holds 16 rows of each of its 8 columns, and the four 16-lane groups of a
+// wavefront hold the other 48 rows of the same columns.  The two logits kernels put the
+// vocabulary on the rows (a token's statistics then reduce inside a lane first); the store
+// kernel puts the output's contiguous dimension there (4 consecutive elements per lane).
 #include "kernels.h"
 #include "gemm_core.h"
 
