@@ -267,3 +267,24 @@ def test_hip_graph_replay_matches_eager(dev):
             assert torch.equal(out[k], eager[k]), (rep, k)
         _ = (tin["H"].float() @ tin["W"].float().T).sum()      # unrelated work between replays
         torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("seed", list(range(12)))
+def test_loss_random_shapes(dev, seed, monkeypatch):
+    """Seeded sweep over ragged shapes, modes and parameters (sizes the oracle finishes in a second)."""
+    rng = np.random.default_rng(9000 + seed)
+    d = int(rng.choice([64, 128, 192, 320, 448]))
+    V = int(rng.integers(257, 3500))
+    spec = synth.small_spec(name=f"rand{seed}", d=d, V=V, P=int(rng.integers(1, 5)), K=int(rng.integers(2, 7)),
+                            Tmax=int(rng.integers(1, 5)), len_lo=int(rng.integers(1, 30)), len_hi=int(rng.integers(30, 140)),
+                            ctx_frac=float(rng.choice([0.0, 0.3, 1.0])), dtype=str(rng.choice(["bf16", "bf16", "f32"])),
+                            seed=700 + seed, stop_prob=float(rng.choice([0.0, 0.2, 0.5])),
+                            temperature=float(rng.choice([1.0, 0.7, 1.3])))
+    mode = int(rng.integers(0, 3))
+    kind = {0: "none", 1: "window", 2: "token"}[mode]
+    prm = B.Params(dtype=0 if spec.dtype == "bf16" else 1, temperature=spec.temperature, mismatch_mode=mode,
+                   clip_eps_lo=0.2, clip_eps_hi=0.2, dW_dtype=int(rng.integers(0, 2)),
+                   norm_override=float(rng.choice([0.0, 0.0, 777.0])))
+    out, ref, batch = _run_loss(dev, spec, prm, kind, on_policy=bool(rng.integers(0, 2)), monkeypatch=monkeypatch,
+                                budget_tiles=int(rng.integers(1, 6)))
+    _compare(out, ref, TOL_LOGP if spec.dtype == "bf16" else 2e-4)
