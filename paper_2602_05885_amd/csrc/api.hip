@@ -7,6 +7,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <vector>
 
 #include "../../include/pg_head.h"
@@ -155,6 +156,8 @@ bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) !
 
 int32_t ensure_init() {
   static bool done[64] = {};
+  static std::mutex mu;
+  std::lock_guard<std::mutex> lock(mu);
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess) return fail(PG_ERR_HIP, "hipGetDevice failed");
   if (dev < 0 || dev >= 64) return fail(PG_ERR_HIP, "device index %d out of range", dev);
