@@ -28,8 +28,8 @@ PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA peak (published)
 # summarised in profiles/gemm_store_kernel_hbm_traffic.md (mean over a step's 14 launches, each
 # counter scaled by what it reads for a plain 1 GiB copy).  Valid only for the kernel sources the
 # counters were taken with: the digest below is of csrc/gemm_core.h + csrc/kernels_gemm.hip.
-TRAFFIC_GEMM_STORE = {"read_bytes": 5874220.5 * 1024 * 2.000, "write_bytes": 659024.3 * 1024 * 1.000,
-                      "sources_sha256": "91d3411a36bf9db4e2c5744e642764b9ef3473a3cf4f233a66452180cd01b413"}
+TRAFFIC_GEMM_STORE = {"read_bytes": 5825120.6 * 1024 * 2.000, "write_bytes": 546809.9 * 1024 * 1.000,
+                      "sources_sha256": "0c45713e79516eceb0a14f4b7c8658fa0a7fc32d1741fc96530d7a5054598a32"}
 
 
 def kernel_sources_digest() -> str:
