@@ -225,13 +225,35 @@ def main():
         out = step()
     torch.cuda.synchronize()
     B.pg_profile_enable(True, 64 * max(args.steps, 1))
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]   # step boundaries, same stream
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for i in range(args.steps):
+        marks[i].record()
         out = step()
+    marks[args.steps].record()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     prof = B.pg_profile_read()
     B.pg_profile_enable(False)
+    step_ms = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps))
+
+    # the same step once more with dW += (gradient accumulation over microbatches), outside the timed region
+    acc_ms = None
+    if args.workload == "pg" and args.steps > 0:
+        prm_acc = B.Params(dtype=dtype_id, temperature=spec.temperature, mismatch_mode=args.mismatch_mode,
+                           accumulate_dW=1)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        adv0, _, _ = B.trloo_advantage(rewards, valid, 1.0, want_returns=False, want_group_n=False)
+        n_acc = 3
+        e0.record()
+        for _ in range(n_acc):
+            B.pg_loss_fwd_bwd(H, W, y, loss_mask, cu, adv0.reshape(-1), seg_sample, old_logp, rollout_logp, prm_acc, ws,
+                              dW=dW, out=outbuf)
+        e1.record()
+        torch.cuda.synchronize()
+        acc_ms = e0.elapsed_time(e1) / n_acc
+        out = step()                       # leave dW and the outputs as one overwrite step produces them
+        torch.cuda.synchronize()
 
     counters = out["counters"].cpu().numpy()
     n_active = int(counters[0])
@@ -275,7 +297,9 @@ def main():
         "metric": ("loss fwd+bwd tokens/sec at 14B shape (h5120,V151936); % bf16 MFMA peak" if args.workload == "pg" else
                    "SFT cross-entropy fwd+bwd tokens/sec at 14B shape (h5120,V151936); % bf16 MFMA peak"),
         "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "ms_per_step": ms_step, "ms_per_step_median": step_ms[len(step_ms) // 2] if step_ms else None,
+        "ms_per_step_min": step_ms[0] if step_ms else None, "ms_per_step_accumulate_dW": acc_ms,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if dtype_id == 0 else "f32", "data": "synthetic",
         "config": {"workload": f"configs[{args.config}] {spec.name}: d={d}, V={V}, {batch.P}x{batch.K}x{batch.Tmax} rollout batch, "
                                f"packed microbatch of {S} segments, {T} rows, {n_loss} loss tokens",

@@ -2,7 +2,10 @@
 // checksum instead of an epilogue, at the three contraction shapes of the 14B head
 // (logits: M=V, N=tokens, K=d;  dW chunk: M=vc, N=d, K=tokens;  dH chunk: M=tokens, N=d, K=vc).
 // Usage: tile_bench [iters [shape]]   iters timed launches per shape (default 3); shape 0..2 runs
-// that shape only.  It first verifies a small ragged product against a naive kernel.
+// that shape only, shape 3 only the register-resident MFMA loop.  It first verifies a small ragged
+// product against a naive kernel, then times the MFMA instruction alone (operands and accumulators
+// in registers, no memory traffic: the rate the matrix pipes sustain on this chip, which the
+// published peak is compared with) and then the three shapes.
 #include <hip/hip_runtime.h>
 
 #include <cmath>
@@ -52,6 +55,34 @@ __global__ __launch_bounds__(NTHREADS) void tile_kernel(const __bf16* A, const _
         for (int r = 0; r < 4; ++r) s += acc[i][j][r];
     out[(size_t)blockIdx.x * NTHREADS + tid] = s;
   }
+}
+
+// The engine's per-wavefront register tile (4 x 8 MFMA tiles, 8 wavefronts per workgroup, one
+// workgroup per CU) with every operand already in registers.  clk[0..1] = shader-clock and
+// 100 MHz wall-clock ticks of workgroup 0 over the loop.
+__global__ __launch_bounds__(NTHREADS) void mfma_only_kernel(float* out, int iters, long long* clk) {
+  const int lane = threadIdx.x & 63;
+  bf16x8 a[GM], b[GN];
+  for (int i = 0; i < GM; ++i)
+    for (int e = 0; e < 8; ++e) a[i][e] = (__bf16)(0.01f * (float)((lane * 7 + e * 3 + i) % 17 - 8));
+  for (int j = 0; j < GN; ++j)
+    for (int e = 0; e < 8; ++e) b[j][e] = (__bf16)(0.02f * (float)((lane * 5 + e + j) % 13 - 6));
+  f32x4 acc[GM][GN];
+  zero_acc(acc);
+  const long long c0 = clock64(), w0 = wall_clock64();
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int j = 0; j < GN; ++j)
+#pragma unroll
+      for (int i = 0; i < GM; ++i) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+  }
+  const long long c1 = clock64(), w1 = wall_clock64();
+  float s = 0.f;
+  for (int i = 0; i < GM; ++i)
+    for (int j = 0; j < GN; ++j)
+      for (int r = 0; r < 4; ++r) s += acc[i][j][r];
+  out[(size_t)blockIdx.x * NTHREADS + threadIdx.x] = s;
+  if (blockIdx.x == 0 && threadIdx.x == 0) { clk[0] = c1 - c0; clk[1] = w1 - w0; }
 }
 
 __global__ void naive_kernel(const __bf16* A, const __bf16* B, float* out, int M, int N, int K) {
@@ -109,6 +140,33 @@ int main(int argc, char** argv) {
     fflush(stdout);
     CK(hipFree(A)); CK(hipFree(B)); CK(hipFree(out)); CK(hipFree(ref));
     if (bad) return 1;
+  }
+  if (only < 0 || only == 3) {  // the MFMA instruction alone, one workgroup per CU and four per CU
+    float* out;
+    long long* clk;
+    const int n_it = 20000;
+    CK(hipMalloc(&out, (size_t)1024 * NTHREADS * 4)); CK(hipMalloc(&clk, 16));
+    for (int pass = 0; pass < 4; ++pass) {
+      const int wg_per_cu = 1 + (pass & 1);
+      const int grid = 256 * wg_per_cu;
+      mfma_only_kernel<<<grid, NTHREADS>>>(out, n_it / 2, clk);   // long enough for the clock to settle
+      CK(hipDeviceSynchronize());
+      hipEvent_t e0, e1;
+      CK(hipEventCreate(&e0)); CK(hipEventCreate(&e1));
+      CK(hipEventRecord(e0));
+      mfma_only_kernel<<<grid, NTHREADS>>>(out, n_it, clk);
+      CK(hipEventRecord(e1)); CK(hipEventSynchronize(e1));
+      float ms;
+      CK(hipEventElapsedTime(&ms, e0, e1));
+      long long h[2];
+      CK(hipMemcpy(h, clk, 16, hipMemcpyDeviceToHost));
+      const double fl = (double)grid * (NTHREADS / 64) * n_it * (GM * GN) * 16384.0;
+      printf("[mfma ] registers only, %d workgroup(s) of %d wavefronts per CU: %.3f ms  %.1f TFLOP/s  (%.1f%% of 2500)  "
+             "shader clock %.3f GHz\n", wg_per_cu, NTHREADS / 64, ms, fl / ms / 1e9, fl / ms / 1e9 / 25.0,
+             h[1] ? (double)h[0] / (double)h[1] * 0.1 : 0.0);
+      fflush(stdout);
+    }
+    CK(hipFree(out)); CK(hipFree(clk));
   }
   struct Shape { const char* name; int M, N, K; } shapes[] = {
       {"logits  (V x tokens x d)", 151936, 8192, 5120},
