@@ -156,9 +156,11 @@ def main():
     ap.add_argument("--mismatch-mode", type=int, default=2)
     ap.add_argument("--cpu-rows", type=int, default=2048, help="rows of the oracle's timed sample (0 = skip)")
     ap.add_argument("--scale-rows", type=float, default=1.0, help="shrink the packed microbatch (debugging)")
-    ap.add_argument("--workload", choices=["pg", "sft", "fwd"], default="pg",
+    ap.add_argument("--workload", choices=["pg", "sft", "fwd", "shard"], default="pg",
                     help="pg: trloo_advantage + pg_loss_fwd_bwd (the headline); sft: pg_sft_fwd_bwd at the same shape; "
-                         "fwd: pg_logprob_fwd over every row (the old-policy recompute)")
+                         "fwd: pg_logprob_fwd over every row (the old-policy recompute); shard: one vocab shard's "
+                         "share of the step (pg_head_shard_fwd + pg_head_partials_merge + pg_loss_shard_bwd)")
+    ap.add_argument("--vocab-shards", type=int, default=2, help="number of vocab shards for --workload shard")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="also run three plain device-to-device copies of this size (the known-size reference "
                          "that hardware-counter byte counts are scaled by)")
@@ -200,9 +202,29 @@ def main():
     if args.mismatch_mode == 0:
         rollout_logp = None
 
+    V_full = V
+    if args.workload == "shard":
+        # this process plays shard 0 of --vocab-shards equal shards; the other shards' softmax states
+        # (what the exchange would deliver) are prepared once, outside the timed region
+        g = args.vocab_shards
+        assert g >= 2 and V // g >= 1
+        Vs = V // g
+        others = None
+        for k in range(1, g):
+            a, b = k * Vs, (V if k == g - 1 else (k + 1) * Vs)
+            wsk = B.alloc_workspace(T, d, b - a, 0, prm, B.CALL_LOGPROB_FWD, dev)
+            pk = B.pg_head_shard_fwd(H, W[a:b], y, loss_mask, a, prm, wsk)
+            others = pk if others is None else B.pg_head_partials_merge(others, pk, out=others)
+            torch.cuda.synchronize()
+            del wsk
+        W = W[:Vs]
+        V = Vs
+        part = torch.empty((T, 4), dtype=torch.float32, device=dev)
+        merged = torch.empty_like(part)
     ws = B.alloc_workspace(T, d, V, S, prm, B.CALL_LOSS_FWD_BWD, dev)
     dW = torch.empty((V, d), dtype=torch.float32, device=dev)
-    outbuf = (torch.empty(1, dtype=torch.float32, device=dev), torch.empty_like(H),
+    outbuf = (torch.empty(1, dtype=torch.float32, device=dev),
+              torch.empty((T, d), dtype=torch.float32, device=dev) if args.workload == "shard" else torch.empty_like(H),
               torch.empty(T, dtype=torch.float32, device=dev), torch.empty(T, dtype=torch.float32, device=dev),
               torch.empty(8, dtype=torch.int64, device=dev))
 
@@ -210,6 +232,11 @@ def main():
         if args.workload == "sft":
             return B.pg_sft_fwd_bwd(H, W, y, loss_mask, prm, ws, dW=dW, out=outbuf)
         adv, _, _ = B.trloo_advantage(rewards, valid, 1.0, want_returns=False, want_group_n=False)
+        if args.workload == "shard":
+            B.pg_head_shard_fwd(H, W, y, loss_mask, 0, prm, ws, out=part)
+            B.pg_head_partials_merge(part, others, out=merged)
+            return B.pg_loss_shard_bwd(H, W, y, loss_mask, cu, adv.reshape(-1), seg_sample, old_logp, rollout_logp,
+                                       merged, 0, prm, ws, dH_f32=True, dW=dW, out=outbuf)
         return B.pg_loss_fwd_bwd(H, W, y, loss_mask, cu, adv.reshape(-1), seg_sample, old_logp, rollout_logp, prm, ws,
                                  dW=dW, out=outbuf)
 
@@ -291,11 +318,14 @@ def main():
     useful = 6.0 * d * V * n_active / (ms_step * 1e-3) / 1e12
 
     cpu = cpu_baseline(spec, args.cpu_rows) if args.cpu_rows > 0 and args.workload == "pg" else None
-    aux = aux_stage_times(B, torch, dev, rewards, valid, out, loss_mask, old_logp, rollout_logp, dW, H)
+    aux = (aux_stage_times(B, torch, dev, rewards, valid, out, loss_mask, old_logp, rollout_logp, dW, H)
+           if args.workload != "shard" else None)
 
     line = {
-        "metric": ("loss fwd+bwd tokens/sec at 14B shape (h5120,V151936); % bf16 MFMA peak" if args.workload == "pg" else
-                   "SFT cross-entropy fwd+bwd tokens/sec at 14B shape (h5120,V151936); % bf16 MFMA peak"),
+        "metric": {"pg": "loss fwd+bwd tokens/sec at 14B shape (h5120,V151936); % bf16 MFMA peak",
+                   "sft": "SFT cross-entropy fwd+bwd tokens/sec at 14B shape (h5120,V151936); % bf16 MFMA peak",
+                   "shard": f"loss fwd+bwd tokens/sec of one of {args.vocab_shards} vocab shards of the head; % bf16 MFMA peak",
+                   }[args.workload],
         "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_step, "ms_per_step_median": step_ms[len(step_ms) // 2] if step_ms else None,
         "ms_per_step_min": step_ms[0] if step_ms else None, "ms_per_step_accumulate_dW": acc_ms,
@@ -306,7 +336,10 @@ def main():
                    "loss_tokens": n_loss, "active_tokens": n_active, "packed_rows": T, "segments": S,
                    "mismatch_mode": args.mismatch_mode, "temperature": spec.temperature,
                    "dW": "fp32 overwrite",
-                   "step": "trloo_advantage + pg_loss_fwd_bwd" if args.workload == "pg" else "pg_sft_fwd_bwd"},
+                   "step": {"pg": "trloo_advantage + pg_loss_fwd_bwd", "sft": "pg_sft_fwd_bwd",
+                            "shard": "trloo_advantage + pg_head_shard_fwd + pg_head_partials_merge + pg_loss_shard_bwd"
+                            }[args.workload],
+                   **({"vocab_shards": args.vocab_shards, "V_shard": V, "V": V_full} if args.workload == "shard" else {})},
         "pct_mfma_peak_executed_8dV": 100.0 * executed / PEAK_BF16_TFLOPS,
         "pct_mfma_peak_useful_6dV": 100.0 * useful / PEAK_BF16_TFLOPS,
         "loss": loss, "counters": {n: int(c) for n, c in zip(B.COUNTER_NAMES, counters)},

@@ -20,6 +20,9 @@
  *   prs_retain        profiling-based rejection sampling               (Sec. 5.2, Eq. 8)
  *   pg_monitors       entropy, perplexities and gradient norms         (Sec. 5.1)
  *   pg_rmsnorm_fwd/bwd  the RMS normalisation in front of the head in the Qwen3 policies of Sec. 6.1
+ *   pg_head_shard_fwd, pg_head_partials_merge, pg_loss_shard_bwd
+ *                     pg_logprob_fwd / pg_loss_fwd_bwd with the head's vocabulary rows split over
+ *                     devices: one device's share of the work and the reduction operator of the exchange
  *
  * Conventions
  *   - Every pointer is a DEVICE pointer unless its name starts with h_ (pg_params is
@@ -252,6 +255,48 @@ size_t pg_rmsnorm_bwd_workspace_bytes(int64_t d);
 int32_t pg_rmsnorm_bwd(const void* X, const void* gamma, const void* dH, int64_t T, int64_t d, float eps,
                        int32_t dtype, void* dX_out, float* dgamma_out, void* workspace, size_t workspace_bytes,
                        void* stream);
+
+/*
+ * Vocab-sharded head: the quantities of pg_logprob_fwd and pg_loss_fwd_bwd (pi_train of Sec. 5.1,
+ * the estimator of App. A) when W is split by vocabulary rows and each device holds
+ * W_shard = W[v_offset : v_offset + V_shard, :].  y holds token ids of the WHOLE vocabulary.
+ * One device's share is two calls with one exchange between them:
+ *
+ * pg_head_shard_fwd: for the rows with row_mask[t] != 0 (NULL = all rows) writes the row's softmax
+ * state over this shard's logits z = H_t W_shard^T / tau,
+ *   partials_out[t] = (m, s, u, z_y) = (max_v z_v, sum_v e^(z_v - m), sum_v e^(z_v - m)(z_v - m),
+ *                                      z at y[t] if v_offset <= y[t] < v_offset + V_shard else 0),
+ * [T][4] fp32, natural-log units; rows that are masked out are written as (0, 0, 0, 0), the empty
+ * state.  Workspace: pg_workspace_bytes(T, d, V_shard, 0, params, PG_CALL_LOGPROB_FWD).
+ *
+ * pg_head_partials_merge: out[t] = a[t] (+) b[t], the state of the union of two disjoint vocab
+ * ranges: m = max(m_a, m_b), s = e^(m_a - m) s_a + e^(m_b - m) s_b,
+ * u = e^(m_a - m)(u_a + (m_a - m) s_a) + e^(m_b - m)(u_b + (m_b - m) s_b), z_y = z_y,a + z_y,b;
+ * an empty state (s = 0) is the neutral element.  This is the operator an all-reduce over the
+ * shards applies (16 bytes per token); on one device it merges states computed one after the
+ * other.  out may alias a or b.  From the merged state: logsumexp = m + ln s,
+ * log-prob = z_y - logsumexp, entropy = ln s - u / s.
+ *
+ * pg_loss_shard_bwd: arguments, loss, counters, logp_out and entropy_out as pg_loss_fwd_bwd, except
+ * that the forward contraction is not run: the rows' log-prob, entropy and logsumexp are taken
+ * from `partials` ([T][4], the state merged over ALL shards; read on active rows only).  Writes
+ *   dW_shard   = dS[:, shard]^T H            [V_shard, d], complete (added to if accumulate_dW),
+ *   dH_partial = dS[:, shard] W_shard        [T, d], this shard's term of the sum over shards that
+ *                gives dH; fp32 if dH_f32 != 0 (what a sum all-reduce wants), else the dtype of H.
+ * loss_out, logp_out, entropy_out and the counters are the same on every shard.
+ * Workspace: pg_workspace_bytes(T, d, V_shard, S, params, PG_CALL_LOSS_FWD_BWD).
+ * Errors as for pg_loss_fwd_bwd; partials and partials_out must be 16-byte aligned.
+ */
+int32_t pg_head_shard_fwd(const void* H, const void* W_shard, const int32_t* y, const uint8_t* row_mask, int64_t T,
+                          int64_t d, int64_t V_shard, int64_t v_offset, const pg_params* h_params, float* partials_out,
+                          void* workspace, size_t workspace_bytes, void* stream);
+int32_t pg_head_partials_merge(const float* a, const float* b, float* out, int64_t T, void* stream);
+int32_t pg_loss_shard_bwd(const void* H, const void* W_shard, const int32_t* y, const uint8_t* loss_mask,
+                          const int32_t* cu_seqlens, int32_t S, const double* adv, const int32_t* seg_sample,
+                          const float* old_logp, const float* rollout_logp, const float* partials, int64_t T, int64_t d,
+                          int64_t V_shard, int64_t v_offset, const pg_params* h_params, float* loss_out, void* dH_partial,
+                          int32_t dH_f32, void* dW_shard, float* logp_out, float* entropy_out, int64_t* counters_out,
+                          void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * Measurement hooks (host-side state, not thread-safe; the only calls that create HIP events

@@ -28,6 +28,11 @@ Stages around the path (Sec. 3.3, 4.2, 5.1, 5.2 and App. ablations)
                                are Qwen3 models, whose last layer before the head is an RMSNorm);
                                the paper does not mention it, the definition is the textbook one
 
+  * vocab-sharded head      -- the same head with W split by vocabulary rows (how a head is
+                               spread over devices); the paper does not mention it.  Each
+                               shard's per-row softmax state, the merge of two states, and a
+                               shard's share of the gradients, all by direct definition
+
 What the paper does not write down and is fixed here by definition (each is a
 stated reading, "parity unpinned" beyond self-consistency): the PPO-style
 clipped surrogate and its epsilon, token-mean normalisation, the truncated
@@ -196,6 +201,60 @@ def merge_softmax_partials(parts):
 
 
 # --------------------------------------------------------------------------
+# Vocab-sharded head.  A shard holds W[v0:v1]; its state of row t is
+#   m = max_v z_v,  s = sum_v e^(z_v - m),  u = sum_v e^(z_v - m)(z_v - m)   over v0 <= v < v1,
+#   z_y = z at y_t if the shard holds row y_t of W, else 0,
+# with z = H_t W^T / tau.  Rows that are masked out carry the empty state (0, 0, 0, 0).
+# --------------------------------------------------------------------------
+def head_shard_partials(H, W_shard, y, v_offset: int, tau: float = 1.0, row_mask=None) -> np.ndarray:
+    H = np.asarray(H, dtype=np.float64)
+    y = np.asarray(y, dtype=np.int64)
+    T = H.shape[0]
+    Vs = np.asarray(W_shard).shape[0]
+    act = np.ones(T, bool) if row_mask is None else np.asarray(row_mask).astype(bool)
+    out = np.zeros((T, 4))
+    for t in np.nonzero(act)[0]:
+        z = logits(H[t:t + 1], W_shard, tau)[0]
+        m = z.max()
+        e = np.exp(z - m)
+        yl = y[t] - v_offset
+        out[t] = (m, e.sum(), (e * (z - m)).sum(), z[yl] if 0 <= yl < Vs else 0.0)
+    return out
+
+
+def merge_shard_partials(a: np.ndarray, b: np.ndarray) -> np.ndarray:
+    """State of the union of two disjoint vocab ranges, row by row; the empty state is neutral."""
+    a = np.asarray(a, np.float64)
+    b = np.asarray(b, np.float64)
+    out = np.zeros_like(a)
+    for t in range(a.shape[0]):
+        (m1, s1, u1, z1), (m2, s2, u2, z2) = a[t], b[t]
+        if s1 == 0.0:
+            out[t] = (m2, s2, u2, z1 + z2)
+        elif s2 == 0.0:
+            out[t] = (m1, s1, u1, z1 + z2)
+        else:
+            m = max(m1, m2)
+            a1, a2 = np.exp(m1 - m), np.exp(m2 - m)          # re-reference both sums to the common max
+            out[t] = (m, a1 * s1 + a2 * s2,
+                      a1 * (u1 + (m1 - m) * s1) + a2 * (u2 + (m2 - m) * s2), z1 + z2)
+    return out
+
+
+def finish_shard_partials(parts: np.ndarray):
+    """(log-prob, entropy, logsumexp) per row from states merged over the whole vocabulary; 0 on empty rows."""
+    parts = np.asarray(parts, np.float64)
+    T = parts.shape[0]
+    logp, ent, lse = np.zeros(T), np.zeros(T), np.zeros(T)
+    live = parts[:, 1] > 0
+    m, s_, u, zy = (parts[live, k] for k in range(4))
+    lse[live] = m + np.log(s_)
+    logp[live] = zy - lse[live]
+    ent[live] = np.log(s_) - u / s_
+    return logp, ent, lse
+
+
+# --------------------------------------------------------------------------
 # Sec. 5.1: mismatch correction from trainer-vs-rollout log-probs of the sampled
 # tokens.  One segment = one training sample = one (prompt, rollout, turn); |T|
 # is the number of its loss (response) tokens.  No gradient flows through it.
@@ -262,10 +321,13 @@ def surrogate(logp, old_logp, A, prm: Params):
 
 
 def pg_loss_fwd_bwd(H, W, y, loss_mask, cu_seqlens, adv_seg, old_logp, rollout_logp,
-                    prm: Params, dW_prev=None, block: int = 256):
+                    prm: Params, dW_prev=None, block: int = 256, vocab_slice=None):
     """Loss, dH, dW, per-token log-prob/entropy and counters, all float64.
 
     adv_seg[s] is the advantage of segment s, broadcast to its loss tokens.
+    vocab_slice = (v0, v1): one vocab shard's share of the gradients -- the softmax still runs
+    over all of W, but only the columns v0 <= v < v1 of dS are contracted: dW has the v1 - v0
+    rows of that range and dH is that range's term of the sum over v (dW_prev likewise).
     """
     H = np.asarray(H, dtype=np.float64)
     W = np.asarray(W, dtype=np.float64)
@@ -289,7 +351,8 @@ def pg_loss_fwd_bwd(H, W, y, loss_mask, cu_seqlens, adv_seg, old_logp, rollout_l
     logp = np.zeros(T)
     ent = np.zeros(T)
     dH = np.zeros((T, d))
-    dW = np.zeros((V, d)) if dW_prev is None else np.array(dW_prev, dtype=np.float64)
+    v0, v1 = (0, V) if vocab_slice is None else vocab_slice
+    dW = np.zeros((v1 - v0, d)) if dW_prev is None else np.array(dW_prev, dtype=np.float64)
     total = 0.0
     n_hi = n_lo = 0
     rows = np.nonzero(active)[0]
@@ -305,7 +368,8 @@ def pg_loss_fwd_bwd(H, W, y, loss_mask, cu_seqlens, adv_seg, old_logp, rollout_l
         coef = c[r_] * g / norm                       # d(loss)/d(logp_t)
         dS = -p * (coef / tau)[:, None]               # (coef/tau) * (onehot - p)
         dS[np.arange(len(r_)), y[r_]] += coef / tau
-        dH[r_] = dS @ W
+        dS = dS[:, v0:v1]
+        dH[r_] = dS @ W[v0:v1]
         dW += dS.T @ H[r_]
     counters = np.array([n_active, n_hi, n_lo, mm["geo"], mm["veto"], mm["trunc"],
                          int(loss_mask.sum()), 0], dtype=np.int64)

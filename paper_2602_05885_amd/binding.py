@@ -22,8 +22,8 @@ CALL_LOSS_FWD_BWD = 1
 COUNTER_NAMES = ("active", "clip_hi", "clip_lo", "seg_geo", "seg_veto", "truncated", "loss_tokens", "reserved")
 
 EXPORTS = ("pg_last_error", "pg_workspace_bytes", "trloo_advantage", "pg_logprob_fwd", "pg_loss_fwd_bwd",
-           "pg_sft_fwd_bwd", "grpo_advantage", "turn_reward", "prs_retain", "pg_monitors_workspace_bytes",
-           "pg_monitors", "pg_rmsnorm_fwd", "pg_rmsnorm_bwd_workspace_bytes", "pg_rmsnorm_bwd",
+           "pg_sft_fwd_bwd", "pg_head_shard_fwd", "pg_head_partials_merge", "pg_loss_shard_bwd", "grpo_advantage",
+           "turn_reward", "prs_retain", "pg_monitors_workspace_bytes", "pg_monitors", "pg_rmsnorm_fwd", "pg_rmsnorm_bwd_workspace_bytes", "pg_rmsnorm_bwd",
            "pg_profile_enable", "pg_profile_read")
 MONITOR_NAMES = ("entropy_mean", "ppl_train", "ppl_rollout", "dH_norm", "dW_norm", "n")
 KERNEL_CLASSES = ("fwd", "dlogits", "dw", "dh")
@@ -94,6 +94,17 @@ def lib() -> C.CDLL:
         L.pg_sft_fwd_bwd.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_int64,
                                      C.POINTER(PgParams), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                      C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.pg_head_shard_fwd.restype = C.c_int32
+        L.pg_head_shard_fwd.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_int64,
+                                        C.c_int64, C.POINTER(PgParams), C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.pg_head_partials_merge.restype = C.c_int32
+        L.pg_head_partials_merge.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
+        L.pg_loss_shard_bwd.restype = C.c_int32
+        L.pg_loss_shard_bwd.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
+                                        C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64,
+                                        C.c_int64, C.c_int64, C.c_int64, C.POINTER(PgParams), C.c_void_p, C.c_void_p,
+                                        C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                        C.c_size_t, C.c_void_p]
         L.grpo_advantage.restype = C.c_int32
         L.grpo_advantage.argtypes = L.trloo_advantage.argtypes
         L.turn_reward.restype = C.c_int32
@@ -307,6 +318,57 @@ def pg_sft_fwd_bwd(H, W, y, loss_mask, params: Params, workspace: torch.Tensor, 
     _check(lib().pg_sft_fwd_bwd(_ptr(H), _ptr(W), _ptr(y), _ptr(loss_mask), T, d, V, C.byref(p), _ptr(loss), _ptr(dH),
                                 _ptr(dW), _ptr(logp), _ptr(ent), _ptr(counters), _ptr(workspace), workspace.numel(),
                                 _stream(stream)))
+    return dict(loss=loss, dH=dH, dW=dW, logp=logp, entropy=ent, counters=counters)
+
+
+def pg_head_shard_fwd(H, W_shard, y, row_mask, v_offset: int, params: Params, workspace: torch.Tensor, out=None,
+                      stream=None):
+    """Softmax state (m, s, u, z_y) of every row over one vocab shard.  Returns partials [T, 4] f32."""
+    T, d = H.shape
+    Vs = W_shard.shape[0]
+    parts = torch.empty((T, 4), dtype=torch.float32, device=W_shard.device) if out is None else out
+    p = params.c_struct()
+    _check(lib().pg_head_shard_fwd(_ptr(H), _ptr(W_shard), _ptr(y), _ptr(row_mask), T, d, Vs, int(v_offset), C.byref(p),
+                                   _ptr(parts), _ptr(workspace), workspace.numel(), _stream(stream)))
+    return parts
+
+
+def pg_head_partials_merge(a, b, out=None, stream=None):
+    """Row-wise merge of two [T, 4] softmax states of disjoint vocab ranges (out may be a or b)."""
+    assert a.shape == b.shape and a.dtype == b.dtype == torch.float32 and a.shape[-1] == 4
+    out = torch.empty_like(a) if out is None else out
+    _check(lib().pg_head_partials_merge(_ptr(a), _ptr(b), _ptr(out), a.shape[0], _stream(stream)))
+    return out
+
+
+def pg_loss_shard_bwd(H, W_shard, y, loss_mask, cu_seqlens, adv, seg_sample, old_logp, rollout_logp, partials,
+                      v_offset: int, params: Params, workspace: torch.Tensor, dH_f32: bool = True,
+                      dW: Optional[torch.Tensor] = None, out=None, stream=None):
+    """One vocab shard's loss + backward from the states merged over all shards.
+
+    Returns dict(loss, dH (this shard's partial sum), dW (the shard's rows), logp, entropy, counters)."""
+    T, d = H.shape
+    Vs = W_shard.shape[0]
+    S = cu_seqlens.numel() - 1
+    dev = W_shard.device
+    if out is None:
+        loss = torch.empty(1, dtype=torch.float32, device=dev)
+        dH = torch.empty((T, d), dtype=torch.float32 if dH_f32 else H.dtype, device=dev)
+        logp = torch.empty(T, dtype=torch.float32, device=dev)
+        ent = torch.empty(T, dtype=torch.float32, device=dev)
+        counters = torch.empty(8, dtype=torch.int64, device=dev)
+    else:
+        loss, dH, logp, ent, counters = out
+    if dW is None:
+        if params.accumulate_dW:
+            raise ValueError("accumulate_dW needs an existing dW")
+        dW = torch.empty((Vs, d), dtype=torch.bfloat16 if params.dW_dtype else torch.float32, device=dev)
+    p = params.c_struct()
+    _check(lib().pg_loss_shard_bwd(_ptr(H), _ptr(W_shard), _ptr(y), _ptr(loss_mask), _ptr(cu_seqlens), S, _ptr(adv),
+                                   _ptr(seg_sample), _ptr(old_logp), _ptr(rollout_logp), _ptr(partials), T, d, Vs,
+                                   int(v_offset), C.byref(p), _ptr(loss), _ptr(dH), 1 if dH_f32 else 0, _ptr(dW),
+                                   _ptr(logp), _ptr(ent), _ptr(counters), _ptr(workspace), workspace.numel(),
+                                   _stream(stream)))
     return dict(loss=loss, dH=dH, dW=dW, logp=logp, entropy=ent, counters=counters)
 
 

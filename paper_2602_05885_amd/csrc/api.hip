@@ -204,8 +204,10 @@ template <typename T>
 T* at(void* ws, size_t off) { return reinterpret_cast<T*>(static_cast<char*>(ws) + off); }
 
 // Steps shared by both calls: pre-pass, operand staging, forward contraction, combine.
+// y_offset: first vocab row of W within the whole vocabulary (0 unless W is a vocab shard).  With
+// comb.partials_in set, the contraction is skipped and the rows' states come from there.
 void run_forward(const Plan& pl, const pg_params& p, void* ws, const void* H, const void* W, const int32_t* y,
-                 const pg::PrepArgs& prep, pg::CombineArgs comb, bool need_HT, hipStream_t st) {
+                 int64_t y_offset, const pg::PrepArgs& prep, pg::CombineArgs comb, bool need_HT, hipStream_t st) {
   pg::launch_prepass(prep, st);
   const void* Wop = W;
   if (pl.is_f32) {
@@ -217,6 +219,7 @@ void run_forward(const Plan& pl, const pg_params& p, void* ws, const void* H, co
   g.rows = at<int>(ws, pl.rows); g.Hc = at<__bf16>(ws, pl.Hc);
   g.HcT = need_HT ? at<__bf16>(ws, pl.HcT) : nullptr;
   g.yc = at<int>(ws, pl.yc); g.ctl = at<pg::Ctl>(ws, pl.ctl); g.ld_t = pl.ld_t;
+  g.y_offset = (int)y_offset; g.V = (int)pl.V;
   pg::launch_gather(g, st);
 
   pg::FwdArgs f{};
@@ -228,9 +231,9 @@ void run_forward(const Plan& pl, const pg_params& p, void* ws, const void* H, co
   f.yc = at<int>(ws, pl.yc); f.zy = at<float>(ws, pl.zy);
   f.part_m = at<float>(ws, pl.part_m); f.part_s = at<float>(ws, pl.part_s); f.part_u = at<float>(ws, pl.part_u);
   f.ctl = at<pg::Ctl>(ws, pl.ctl);
-  { ProfScope ps(PG_KERNEL_FWD, st); pg::launch_lmhead_fwd(f, st); }
+  if (!comb.partials_in) { ProfScope ps(PG_KERNEL_FWD, st); pg::launch_lmhead_fwd(f, st); }
 
-  comb.tiles_v = pl.tiles_v; comb.t_cap = pl.t_cap;
+  comb.tiles_v = comb.partials_in ? 0 : pl.tiles_v; comb.t_cap = pl.t_cap;
   comb.part_m = f.part_m; comb.part_s = f.part_s; comb.part_u = f.part_u;
   comb.zy = f.zy; comb.rows = at<int>(ws, pl.rows); comb.lse2 = at<float>(ws, pl.lse2);
   comb.ctl = f.ctl;
@@ -258,6 +261,16 @@ int32_t turn_advantage(const float* rewards, const uint8_t* valid, int32_t P, in
   return check_launches(what);
 }
 
+// W as one vocab shard of a larger head: rows [v_offset, v_offset + V) of the vocabulary, the rows'
+// softmax states merged over all shards (nullptr: W is the whole head and the forward
+// contraction runs here), and whether dH (a partial sum over this shard) is written as fp32.
+struct Shard {
+  const float* partials = nullptr;
+  int64_t v_offset = 0;
+  int dH_f32 = 0;
+  const char* what = nullptr;
+};
+
 // Loss forward + backward shared by the policy-gradient call (sft = 0) and the SFT
 // cross-entropy call (sft = 1: no segments, no advantages, no mismatch correction).
 int32_t loss_fwd_bwd(int sft, const void* H, const void* W, const int32_t* y, const uint8_t* loss_mask,
@@ -265,7 +278,7 @@ int32_t loss_fwd_bwd(int sft, const void* H, const void* W, const int32_t* y, co
                      const float* old_logp, const float* rollout_logp, int64_t T, int64_t d, int64_t V,
                      const pg_params* h_params, float* loss_out, void* dH, void* dW, float* logp_out,
                      float* entropy_out, int64_t* counters_out, void* workspace, size_t workspace_bytes,
-                     void* stream);
+                     void* stream, const Shard& shard);
 
 }  // namespace
 
@@ -337,7 +350,7 @@ int32_t pg_logprob_fwd(const void* H, const void* W, const int32_t* y, const uin
   pg::CombineArgs comb{};
   comb.logp_out = logp_out; comb.ent_out = entropy_out; comb.lse_out = lse_out;
   comb.with_loss = 0;
-  run_forward(pl, *h_params, workspace, H, W, y, prep, comb, false, st);
+  run_forward(pl, *h_params, workspace, H, W, y, 0, prep, comb, false, st);
   return check_launches("pg_logprob_fwd");
 }
 
@@ -348,7 +361,59 @@ int32_t pg_loss_fwd_bwd(const void* H, const void* W, const int32_t* y, const ui
                         float* entropy_out, int64_t* counters_out, void* workspace, size_t workspace_bytes,
                         void* stream) {
   return loss_fwd_bwd(0, H, W, y, loss_mask, cu_seqlens, S, adv, seg_sample, old_logp, rollout_logp, T, d, V, h_params,
-                      loss_out, dH, dW, logp_out, entropy_out, counters_out, workspace, workspace_bytes, stream);
+                      loss_out, dH, dW, logp_out, entropy_out, counters_out, workspace, workspace_bytes, stream, Shard{});
+}
+
+int32_t pg_head_shard_fwd(const void* H, const void* W_shard, const int32_t* y, const uint8_t* row_mask, int64_t T,
+                          int64_t d, int64_t V_shard, int64_t v_offset, const pg_params* h_params, float* partials_out,
+                          void* workspace, size_t workspace_bytes, void* stream) {
+  Plan pl;
+  int32_t rc = make_plan(T, d, V_shard, 0, h_params, PG_CALL_LOGPROB_FWD, pl);
+  if (rc) return rc;
+  if (v_offset < 0 || v_offset > (1ll << 30)) return fail(PG_ERR_INVALID_ARG, "v_offset out of range");
+  if (T == 0) return PG_OK;
+  if (!H || !W_shard || !y || !partials_out || !workspace)
+    return fail(PG_ERR_INVALID_ARG, "H, W_shard, y, partials_out and workspace must not be NULL");
+  if (misaligned(H) || misaligned(W_shard) || misaligned(workspace) || misaligned(partials_out))
+    return fail(PG_ERR_INVALID_ARG, "H, W_shard, partials_out and workspace must be 16-byte aligned");
+  if (workspace_bytes < pl.total) return fail(PG_ERR_WORKSPACE_TOO_SMALL, "workspace has %zu bytes, %zu needed", workspace_bytes, pl.total);
+  if ((rc = ensure_init())) return rc;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+
+  pg::launch_fill_zero_bytes(partials_out, (size_t)T * 4 * sizeof(float), st);   // rows that are masked out stay empty
+  pg::PrepArgs prep = base_prep(pl, workspace);
+  prep.mask = row_mask;
+  pg::CombineArgs comb{};
+  comb.with_loss = 0;
+  comb.partials_out = partials_out;
+  run_forward(pl, *h_params, workspace, H, W_shard, y, v_offset, prep, comb, false, st);
+  return check_launches("pg_head_shard_fwd");
+}
+
+int32_t pg_head_partials_merge(const float* a, const float* b, float* out, int64_t T, void* stream) {
+  if (T < 0) return fail(PG_ERR_INVALID_ARG, "T must be >= 0");
+  if (T == 0) return PG_OK;
+  if (!a || !b || !out) return fail(PG_ERR_INVALID_ARG, "a, b and out must not be NULL");
+  if (misaligned(a) || misaligned(b) || misaligned(out)) return fail(PG_ERR_INVALID_ARG, "a, b and out must be 16-byte aligned");
+  pg::launch_merge_partials(a, b, out, T, static_cast<hipStream_t>(stream));
+  return check_launches("pg_head_partials_merge");
+}
+
+int32_t pg_loss_shard_bwd(const void* H, const void* W_shard, const int32_t* y, const uint8_t* loss_mask,
+                          const int32_t* cu_seqlens, int32_t S, const double* adv, const int32_t* seg_sample,
+                          const float* old_logp, const float* rollout_logp, const float* partials, int64_t T, int64_t d,
+                          int64_t V_shard, int64_t v_offset, const pg_params* h_params, float* loss_out, void* dH_partial,
+                          int32_t dH_f32, void* dW_shard, float* logp_out, float* entropy_out, int64_t* counters_out,
+                          void* workspace, size_t workspace_bytes, void* stream) {
+  if (v_offset < 0 || v_offset > (1ll << 30)) return fail(PG_ERR_INVALID_ARG, "v_offset out of range");
+  if (dH_f32 != 0 && dH_f32 != 1) return fail(PG_ERR_INVALID_ARG, "dH_f32 must be 0 or 1");
+  if (T > 0 && !partials) return fail(PG_ERR_INVALID_ARG, "partials must not be NULL");
+  if (misaligned(partials)) return fail(PG_ERR_INVALID_ARG, "partials must be 16-byte aligned");
+  Shard sh;
+  sh.partials = partials; sh.v_offset = v_offset; sh.dH_f32 = dH_f32; sh.what = "pg_loss_shard_bwd";
+  return loss_fwd_bwd(0, H, W_shard, y, loss_mask, cu_seqlens, S, adv, seg_sample, old_logp, rollout_logp, T, d, V_shard,
+                      h_params, loss_out, dH_partial, dW_shard, logp_out, entropy_out, counters_out, workspace,
+                      workspace_bytes, stream, sh);
 }
 
 int32_t pg_sft_fwd_bwd(const void* H, const void* W, const int32_t* y, const uint8_t* loss_mask, int64_t T, int64_t d,
@@ -356,7 +421,7 @@ int32_t pg_sft_fwd_bwd(const void* H, const void* W, const int32_t* y, const uin
                        float* entropy_out, int64_t* counters_out, void* workspace, size_t workspace_bytes,
                        void* stream) {
   return loss_fwd_bwd(1, H, W, y, loss_mask, nullptr, 0, nullptr, nullptr, nullptr, nullptr, T, d, V, h_params,
-                      loss_out, dH, dW, logp_out, entropy_out, counters_out, workspace, workspace_bytes, stream);
+                      loss_out, dH, dW, logp_out, entropy_out, counters_out, workspace, workspace_bytes, stream, Shard{});
 }
 
 int32_t turn_reward(const uint8_t* correct, const float* t_reference, const float* t_kernel, const float* t_generated,
@@ -455,7 +520,7 @@ int32_t loss_fwd_bwd(int sft, const void* H, const void* W, const int32_t* y, co
                      const float* old_logp, const float* rollout_logp, int64_t T, int64_t d, int64_t V,
                      const pg_params* h_params, float* loss_out, void* dH, void* dW, float* logp_out,
                      float* entropy_out, int64_t* counters_out, void* workspace, size_t workspace_bytes,
-                     void* stream) {
+                     void* stream, const Shard& shard) {
   Plan pl;
   int32_t rc = make_plan(T, d, V, S, h_params, PG_CALL_LOSS_FWD_BWD, pl);
   if (rc) return rc;
@@ -468,7 +533,7 @@ int32_t loss_fwd_bwd(int sft, const void* H, const void* W, const int32_t* y, co
     pg::launch_fill_f32(loss_out, 1, 0.f, st);
     if (counters_out) pg::launch_fill_zero_bytes(counters_out, 8 * sizeof(int64_t), st);
     if (!p.accumulate_dW) pg::launch_fill_zero_bytes(dW, (size_t)V * d * dw_elem, st);
-    return check_launches(sft ? "pg_sft_fwd_bwd (empty)" : "pg_loss_fwd_bwd (empty)");
+    return check_launches(shard.what ? shard.what : sft ? "pg_sft_fwd_bwd (empty)" : "pg_loss_fwd_bwd (empty)");
   }
   if (!H || !y || !loss_mask || !dH || !workspace)
     return fail(PG_ERR_INVALID_ARG, "H, y, loss_mask, dH and workspace must not be NULL");
@@ -497,7 +562,8 @@ int32_t loss_fwd_bwd(int sft, const void* H, const void* W, const int32_t* y, co
   comb.eps_lo = p.clip_eps_lo; comb.eps_hi = p.clip_eps_hi; comb.inv_tau = 1.f / p.temperature;
   comb.coefc = at<float>(ws, pl.coefc); comb.lossterm = at<float>(ws, pl.lossterm);
   comb.counters = at<unsigned long long>(ws, pl.counters);
-  run_forward(pl, p, ws, H, W, y, prep, comb, true, st);
+  comb.partials_in = shard.partials;
+  run_forward(pl, p, ws, H, W, y, shard.v_offset, prep, comb, true, st);
 
   pg::FinishArgs fin{at<float>(ws, pl.lossterm), at<unsigned long long>(ws, pl.counters), loss_out,
                      reinterpret_cast<long long*>(counters_out), at<pg::Ctl>(ws, pl.ctl)};
@@ -545,9 +611,9 @@ int32_t loss_fwd_bwd(int sft, const void* H, const void* W, const int32_t* y, co
     { ProfScope ps(PG_KERNEL_DH, st); pg::launch_gemm_store(h, st); }
   }
 
-  pg::ScatterArgs sc{at<float>(ws, pl.dHacc), at<int>(ws, pl.pos), dH, (int)pl.T, d_i, pl.is_f32};
+  pg::ScatterArgs sc{at<float>(ws, pl.dHacc), at<int>(ws, pl.pos), dH, (int)pl.T, d_i, pl.is_f32 || shard.dH_f32};
   pg::launch_scatter_dh(sc, st);
-  return check_launches(sft ? "pg_sft_fwd_bwd" : "pg_loss_fwd_bwd");
+  return check_launches(shard.what ? shard.what : sft ? "pg_sft_fwd_bwd" : "pg_loss_fwd_bwd");
 }
 
 }  // namespace

@@ -116,7 +116,8 @@ struct GatherArgs {
   __bf16* Hc;           // [t_cap, ldh]   bf16: ldh = d;  fp32: ldh = 3d = [hi | hi | lo]
   __bf16* HcT;          // [d, ld_t] (nullable)
   int ld_t;
-  int* yc;
+  int* yc;              // y - y_offset where that lies in [0, V), else -1
+  int y_offset, V;      // first vocab row and number of vocab rows of the weight operand
   const Ctl* ctl;
 };
 void launch_gather(const GatherArgs& a, hipStream_t s);
@@ -139,6 +140,11 @@ struct CombineArgs {
   float* coefc;              // [t_cap]
   float* lossterm;           // [t_cap]
   unsigned long long* counters;
+  // vocab-sharded head: partials_out != null writes the merged state of the row as
+  // (m, s, u, z_y) in natural-log units at [row][4] and stops; partials_in != null takes the
+  // row's state from there (the state merged over all shards) instead of from part_*.
+  float* partials_out;
+  const float* partials_in;
   const Ctl* ctl;
 };
 void launch_combine(const CombineArgs& a, hipStream_t s);
@@ -164,6 +170,9 @@ struct ScatterArgs {
   int out_f32;
 };
 void launch_scatter_dh(const ScatterArgs& a, hipStream_t s);
+
+// out[t] = merge(a[t], b[t]) of two per-row softmax states (m, s, u, z_y), [T][4] each.
+void launch_merge_partials(const float* a, const float* b, float* out, long long T, hipStream_t s);
 
 // ---- stages around the path -------------------------------------------------------------
 struct RewardArgs {

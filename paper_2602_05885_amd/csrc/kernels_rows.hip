@@ -234,7 +234,12 @@ __global__ __launch_bounds__(256) void gather_kernel(GatherArgs a) {
   const int tid = threadIdx.x;
   if (blockIdx.y == 0 && tid < 64) {
     const int i = i0 + tid;
-    a.yc[i] = (i < ctl.n_active) ? a.y[a.rows[i]] : -1;
+    int yl = -1;
+    if (i < ctl.n_active) {
+      yl = a.y[a.rows[i]] - a.y_offset;
+      if (yl < 0 || yl >= a.V) yl = -1;
+    }
+    a.yc[i] = yl;
   }
   if (!a.is_f32) {
     const int chunk = tid & 7;
@@ -374,16 +379,29 @@ __global__ __launch_bounds__(256) void combine_kernel(CombineArgs a) {
     s = a1 * s + a2 * s2;
     M = mm;
   }
+  const float LN2 = 0.693147180559945309f, LOG2E = 1.44269504088896341f;
+  if (a.partials_out) {      // this shard's state of the row, natural-log units
+    if (i < ctl.n_active)
+      *reinterpret_cast<float4*>(a.partials_out + (size_t)a.rows[i] * 4) = make_float4(M * LN2, s, u * LN2, a.zy[i] * LN2);
+    return;
+  }
+  float zy = a.zy[i];
+  if (a.partials_in) {       // state merged over all shards; padded rows get lse = 0
+    M = 0.f; s = 1.f; u = 0.f; zy = 0.f;
+    if (i < ctl.n_active) {
+      const float4 q = *reinterpret_cast<const float4*>(a.partials_in + (size_t)a.rows[i] * 4);
+      M = q.x * LOG2E; s = q.y; u = q.z * LOG2E; zy = q.w * LOG2E;
+    }
+  }
   const float log2s = __builtin_amdgcn_logf(s);     // v_log_f32: log2
   const float lse2 = M + log2s;
   a.lse2[i] = lse2;
-  const float LN2 = 0.693147180559945309f;
   if (i >= ctl.n_active) {
     if (a.with_loss) { a.coefc[i] = 0.f; a.lossterm[i] = 0.f; }
     return;
   }
   const int row = a.rows[i];
-  const float logp = (a.zy[i] - lse2) * LN2;
+  const float logp = (zy - lse2) * LN2;
   if (a.logp_out) a.logp_out[row] = logp;
   if (a.ent_out) a.ent_out[row] = (log2s - u / s) * LN2;
   if (a.lse_out) a.lse_out[row] = lse2 * LN2;
@@ -447,6 +465,35 @@ __global__ __launch_bounds__(256) void scatter_dh_kernel(ScatterArgs a) {
     }
   }
 }
+// ------------------------------------------------------------------ vocab-sharded head
+// The reduction operator of the exchange between vocab shards: per row, the softmax states
+// (m, s, u) of two disjoint vocab ranges merge by the online-softmax rule and the sampled
+// token's logit (held by one shard, 0 elsewhere) by addition.  Rows nobody computed are all
+// zeros and stay so.  out may alias a or b.
+__global__ void merge_partials_kernel(const float* a, const float* b, float* out, long long T) {
+  const long long t = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (t >= T) return;
+  const float4 p = *reinterpret_cast<const float4*>(a + t * 4), q = *reinterpret_cast<const float4*>(b + t * 4);
+  float4 r;
+  if (p.y == 0.f) {          // empty state on one side: the other side unchanged
+    r = make_float4(q.x, q.y, q.z, p.w + q.w);
+  } else if (q.y == 0.f) {
+    r = make_float4(p.x, p.y, p.z, p.w + q.w);
+  } else {
+    const float mm = fmaxf(p.x, q.x);
+    const float a1 = expf(p.x - mm), a2 = expf(q.x - mm);
+    r.x = mm;
+    r.y = a1 * p.y + a2 * q.y;
+    r.z = a1 * (p.z + (p.x - mm) * p.y) + a2 * (q.z + (q.x - mm) * q.y);
+    r.w = p.w + q.w;
+  }
+  *reinterpret_cast<float4*>(out + t * 4) = r;
+}
+void launch_merge_partials(const float* a, const float* b, float* out, long long T, hipStream_t s) {
+  if (T <= 0) return;
+  hipLaunchKernelGGL(merge_partials_kernel, dim3((unsigned)((T + 255) / 256)), dim3(256), 0, s, a, b, out, T);
+}
+
 void launch_scatter_dh(const ScatterArgs& a, hipStream_t s) {
   if (a.T <= 0) return;
   hipLaunchKernelGGL(scatter_dh_kernel, dim3(a.T), dim3(256), 0, s, a);

@@ -114,3 +114,27 @@ def test_rmsnorm_entry_points_validate_arguments():
     assert lib.pg_rmsnorm_bwd(one, one, one, 4, 16384, 1e-6, 0, one, one, one, 1 << 30, None) == -2
     assert lib.pg_rmsnorm_bwd(one, one, one, 4, 64, 1e-6, 0, one, one, one, 16, None) == -3
     assert lib.pg_rmsnorm_bwd(one, one, one, 4, 64, -1.0, 0, one, one, one, 1 << 30, None) == -1
+
+
+def test_shard_entry_points_validate_arguments():
+    lib = B.lib()
+    one = C.c_void_p(16)      # never dereferenced: validation fails first
+    p = B.Params().c_struct()
+    big = 1 << 30
+    assert lib.pg_head_shard_fwd(one, one, one, None, 8, 64, 100, 0, C.byref(p), None, one, big, None) == -1
+    assert lib.pg_head_shard_fwd(one, one, one, None, 8, 64, 100, -1, C.byref(p), one, one, big, None) == -1
+    assert "v_offset" in B.pg_last_error()
+    assert lib.pg_head_shard_fwd(one, one, one, None, 8, 64, 100, 0, C.byref(p), C.c_void_p(8), one, big, None) == -1
+    assert lib.pg_head_shard_fwd(one, one, one, None, 8, 64, 100, 0, C.byref(p), one, one, 16, None) == -3
+    assert lib.pg_head_shard_fwd(one, one, one, None, 8, 72, 100, 0, C.byref(p), one, one, big, None) == -2
+    assert lib.pg_head_shard_fwd(None, None, None, None, 0, 64, 100, 0, C.byref(p), None, None, 0, None) == 0   # T = 0
+    assert lib.pg_head_partials_merge(one, None, one, 4, None) == -1
+    assert lib.pg_head_partials_merge(one, C.c_void_p(4), one, 4, None) == -1 and "aligned" in B.pg_last_error()
+    assert lib.pg_head_partials_merge(one, one, one, -1, None) == -1
+    assert lib.pg_head_partials_merge(None, None, None, 0, None) == 0
+    args = lambda partials, voff, f32, ws: (one, one, one, one, one, 1, one, None, None, None, partials, 8, 64, 100, voff,
+                                            C.byref(p), one, one, f32, one, None, None, None, one, ws, None)
+    assert lib.pg_loss_shard_bwd(*args(None, 0, 1, big)) == -1 and "partials" in B.pg_last_error()
+    assert lib.pg_loss_shard_bwd(*args(one, -5, 1, big)) == -1
+    assert lib.pg_loss_shard_bwd(*args(one, 0, 2, big)) == -1 and "dH_f32" in B.pg_last_error()
+    assert lib.pg_loss_shard_bwd(*args(one, 0, 1, 16)) == -3

@@ -243,3 +243,75 @@ def test_full_sft_and_monitors(full_case):
     assert abs(g["ppl_rollout"] - float(np.exp(-lp[m].sum() / n))) <= 1e-6 * g["ppl_rollout"]
     assert abs(g["entropy_mean"] - float(out["entropy"].double()[mt].sum() / n)) <= 1e-9 * g["entropy_mean"]
     assert abs(np.log(g["ppl_train"]) - ref_loss) <= 1e-3 * abs(ref_loss)          # perplexity = exp(cross-entropy)
+
+
+def test_full_vocab_shards(full_case):
+    """The head split in two vocab shards of 75968 rows (not a multiple of the 256-row tile), each at the
+    full token count: merged forward states against the library reference and the oracle's sampled
+    rows; each shard's dH term on sampled rows and dW on sampled vocab rows against fp64; the two dH
+    terms together and the two dW blocks against the unsharded call."""
+    fc = full_case
+    tin, spec, batch = fc["tin"], fc["spec"], fc["batch"]
+    dev = tin["H"].device
+    T, d, V, S = tin["H"].shape[0], spec.d, spec.V, batch.S
+    tau = float(np.float32(spec.temperature))
+    prm = B.Params(mismatch_mode=2, temperature=spec.temperature)
+    half = V // 2
+    shards = [(0, half), (half, V)]
+    parts = []
+    for a, b in shards:
+        ws = B.alloc_workspace(T, d, b - a, 0, prm, B.CALL_LOGPROB_FWD, dev)
+        parts.append(B.pg_head_shard_fwd(tin["H"], tin["W"][a:b], tin["y"], tin["loss_mask"], a, prm, ws))
+        torch.cuda.synchronize()
+        del ws
+    merged = B.pg_head_partials_merge(parts[0], parts[1])
+    torch.cuda.synchronize()
+    logp, ent, lse = O.finish_shard_partials(merged.cpu().numpy())
+    m = batch.loss_mask.astype(bool)
+    rows = fc["rows"]
+    assert np.abs(logp[m] - fc["lib_logp"].cpu().numpy()[m]).max() <= 2e-3
+    assert np.abs(lse[m] - fc["lib_lse"].cpu().numpy()[m]).max() <= 2e-3
+    assert np.abs(logp[rows] - fc["o_logp"]).max() <= 2e-3 and np.abs(ent[rows] - fc["o_ent"]).max() <= 2e-3
+    assert not merged[torch.from_numpy(~m).to(dev)].any()
+    owner = (parts[0][:, 3] != 0).cpu().numpy().astype(int) + (parts[1][:, 3] != 0).cpu().numpy().astype(int)
+    assert np.all(owner[m] <= 1) and owner[m].mean() > 0.999          # a logit of exactly 0 is possible, not likely
+
+    # oracle on the sampled rows as a sub-problem: one-token segments carrying the full problem's
+    # advantage, weights and normaliser (the sampled rows are active, so none of them is vetoed)
+    n_r = len(rows)
+    rollout = tin["rollout"].cpu().numpy()
+    sub_prm = O.Params(mismatch_mode=2, temperature=spec.temperature, norm_override=fc["norm"])
+    act = np.nonzero(fc["active"])[0]
+    Ha = np64(tin["H"][torch.from_numpy(act).to(dev)])
+    lp_a = fc["lib_logp"].double().cpu().numpy()[act]
+    lse_a = fc["lib_lse"].double().cpu().numpy()[act]
+    _, g, _, _, _ = O.surrogate(lp_a, fc["old"].astype(np.float64)[act], fc["A_tok"][act], fc["oprm"])
+    k = fc["c"][act] * g / fc["norm"] / tau
+    rng = np.random.default_rng(9)
+    dH_sum = None
+    ws = B.alloc_workspace(T, d, V - half, S, prm, B.CALL_LOSS_FWD_BWD, dev)
+    for a, b in shards:
+        out = B.pg_loss_shard_bwd(tin["H"], tin["W"][a:b], tin["y"], tin["loss_mask"], tin["cu"], fc["adv"].reshape(-1),
+                                  tin["seg_sample"], tin["old"], tin["rollout"], merged, a, prm, ws, dH_f32=True)
+        torch.cuda.synchronize()
+        assert torch.equal(out["counters"], fc["out"]["counters"])
+        assert abs(float(out["loss"][0]) - float(fc["out"]["loss"][0])) <= 1e-5 * abs(float(fc["out"]["loss"][0]))
+        assert (out["logp"] - fc["out"]["logp"]).abs().max().item() <= 1e-4
+        ref = O.pg_loss_fwd_bwd(fc["Hr"], fc["Wn"], fc["yn"][rows], np.ones(n_r, np.uint8), np.arange(n_r + 1),
+                                fc["A_tok"][rows], fc["old"][rows], rollout[rows], sub_prm, vocab_slice=(a, b))
+        got = np64(out["dH"][torch.from_numpy(rows).to(dev)])
+        assert rel_fro(got, ref["dH"]) <= 1e-2, ((a, b), rel_fro(got, ref["dH"]))
+        # sampled vocab rows of this shard's dW (fp64 dS^T H over all active rows, logsumexp from the library reference)
+        vs = np.unique(np.concatenate([rng.choice(fc["yn"][act][(fc["yn"][act] >= a) & (fc["yn"][act] < b)], N_VOCAB // 2),
+                                       rng.integers(a, b, N_VOCAB // 2), [a, b - 1]]))
+        z = (Ha @ fc["Wn"][vs].T) / tau
+        dS = -np.exp(z - lse_a[:, None]) * k[:, None] + (fc["yn"][act][:, None] == vs[None, :]) * k[:, None]
+        got_w = np64(out["dW"][torch.from_numpy(vs - a).to(dev)])
+        assert rel_fro(got_w, dS.T @ Ha) <= 1e-2, ((a, b), rel_fro(got_w, dS.T @ Ha))
+        # against the unsharded call (same kernels; the states crossed the boundary in natural-log units)
+        blk = fc["out"]["dW"][a:b]
+        assert float((out["dW"] - blk).double().norm() / blk.double().norm()) <= 2e-3
+        dH_sum = out["dH"].double() if dH_sum is None else dH_sum + out["dH"].double()
+        del out
+    full = fc["out"]["dH"].double()
+    assert float((dH_sum - full).norm() / full.norm()) <= 1e-2
