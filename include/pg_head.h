@@ -78,7 +78,8 @@ extern "C" {
 #define PG_CNT_SEG_GEO 3     /* samples outside the geometric window (mode 1) */
 #define PG_CNT_SEG_VETO 4    /* samples with a token ratio below veto_ratio */
 #define PG_CNT_TRUNCATED 5   /* tokens whose weight was capped (mode 2) */
-#define PG_CNT_LOSS_TOKENS 6 /* rows with loss_mask = 1 */
+#define PG_CNT_LOSS_TOKENS 6 /* rows with loss_mask = 1 in samples that were not dropped */
+#define PG_CNT_SEG_DROPPED 7 /* samples with loss rows whose sample_keep flag is 0 */
 
 typedef struct pg_params {
   int32_t dtype;         /* PG_DTYPE_* of H, W and dH */
@@ -140,6 +141,10 @@ int32_t pg_logprob_fwd(const void* H, const void* W, const int32_t* y, const uin
  *   loss_mask[t]      1 on response tokens (context / feedback rows are 0)
  *   adv               fp64 table of advantages (e.g. adv_out of trloo_advantage)
  *   seg_sample        [S] index into adv of each segment; NULL = segment s uses adv[s]
+ *   sample_keep       uint8 table indexed like adv (e.g. keep_out of prs_retain), nullable: a
+ *                     segment whose flag is 0 was filtered out before training (Sec. 5.2) and is
+ *                     treated exactly as if its loss_mask rows were 0 -- no loss, no gradient, not
+ *                     in the normaliser, not examined by the mismatch correction
  *   old_logp          [T] log-prob under the policy that the update starts from; NULL =
  *                     on-policy (ratio 1, gradient of log-prob times advantage)
  *   rollout_logp      [T] log-prob reported by the rollout engine; required unless
@@ -162,7 +167,8 @@ int32_t pg_logprob_fwd(const void* H, const void* W, const int32_t* y, const uin
  */
 int32_t pg_loss_fwd_bwd(const void* H, const void* W, const int32_t* y, const uint8_t* loss_mask,
                         const int32_t* cu_seqlens, int32_t S, const double* adv,
-                        const int32_t* seg_sample, const float* old_logp, const float* rollout_logp,
+                        const int32_t* seg_sample, const uint8_t* sample_keep, const float* old_logp,
+                        const float* rollout_logp,
                         int64_t T, int64_t d, int64_t V, const pg_params* h_params, float* loss_out,
                         void* dH, void* dW, float* logp_out, float* entropy_out, int64_t* counters_out,
                         void* workspace, size_t workspace_bytes, void* stream);
@@ -293,8 +299,8 @@ int32_t pg_head_shard_fwd(const void* H, const void* W_shard, const int32_t* y, 
 int32_t pg_head_partials_merge(const float* a, const float* b, float* out, int64_t T, void* stream);
 int32_t pg_loss_shard_bwd(const void* H, const void* W_shard, const int32_t* y, const uint8_t* loss_mask,
                           const int32_t* cu_seqlens, int32_t S, const double* adv, const int32_t* seg_sample,
-                          const float* old_logp, const float* rollout_logp, const float* partials, int64_t T, int64_t d,
-                          int64_t V_shard, int64_t v_offset, const pg_params* h_params, float* loss_out, void* dH_partial,
+                          const uint8_t* sample_keep, const float* old_logp, const float* rollout_logp,
+                          const float* partials, int64_t T, int64_t d, int64_t V_shard, int64_t v_offset, const pg_params* h_params, float* loss_out, void* dH_partial,
                           int32_t dH_f32, void* dW_shard, float* logp_out, float* entropy_out, int64_t* counters_out,
                           void* workspace, size_t workspace_bytes, void* stream);
 

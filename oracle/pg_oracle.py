@@ -259,6 +259,21 @@ def finish_shard_partials(parts: np.ndarray):
 # tokens.  One segment = one training sample = one (prompt, rollout, turn); |T|
 # is the number of its loss (response) tokens.  No gradient flows through it.
 # --------------------------------------------------------------------------
+def drop_filtered_segments(loss_mask, cu_seqlens, seg_keep):
+    """Sec. 5.2: samples filtered out before training (PRS keep flag 0) take no part in the update --
+    their rows leave the loss mask.  Returns (mask, number of dropped segments that had loss rows)."""
+    mask = np.array(loss_mask).astype(bool)
+    if seg_keep is None:
+        return mask, 0
+    cu = np.asarray(cu_seqlens, dtype=np.int64)
+    dropped = 0
+    for s in range(len(cu) - 1):
+        if not seg_keep[s]:
+            dropped += int(mask[cu[s]:cu[s + 1]].any())
+            mask[cu[s]:cu[s + 1]] = False
+    return mask, dropped
+
+
 def mismatch_weights(old_logp, rollout_logp, loss_mask, cu_seqlens, prm: Params):
     """Returns c[T] (weight per token), active[T], seg_keep[S], counters dict."""
     loss_mask = np.asarray(loss_mask).astype(bool)
@@ -321,13 +336,14 @@ def surrogate(logp, old_logp, A, prm: Params):
 
 
 def pg_loss_fwd_bwd(H, W, y, loss_mask, cu_seqlens, adv_seg, old_logp, rollout_logp,
-                    prm: Params, dW_prev=None, block: int = 256, vocab_slice=None):
+                    prm: Params, dW_prev=None, block: int = 256, vocab_slice=None, seg_keep=None):
     """Loss, dH, dW, per-token log-prob/entropy and counters, all float64.
 
     adv_seg[s] is the advantage of segment s, broadcast to its loss tokens.
     vocab_slice = (v0, v1): one vocab shard's share of the gradients -- the softmax still runs
     over all of W, but only the columns v0 <= v < v1 of dS are contracted: dW has the v1 - v0
     rows of that range and dH is that range's term of the sum over v (dW_prev likewise).
+    seg_keep[s] = 0 drops segment s before anything else (drop_filtered_segments).
     """
     H = np.asarray(H, dtype=np.float64)
     W = np.asarray(W, dtype=np.float64)
@@ -337,7 +353,7 @@ def pg_loss_fwd_bwd(H, W, y, loss_mask, cu_seqlens, adv_seg, old_logp, rollout_l
     tau = _f32(prm.temperature)
     cu = np.asarray(cu_seqlens, dtype=np.int64)
     S = len(cu) - 1
-    loss_mask = np.asarray(loss_mask).astype(bool)
+    loss_mask, n_dropped = drop_filtered_segments(loss_mask, cu, seg_keep)
     old = None if old_logp is None else np.asarray(old_logp, np.float64)
 
     c, active, keep, mm = mismatch_weights(old, rollout_logp, loss_mask, cu, prm)
@@ -372,7 +388,7 @@ def pg_loss_fwd_bwd(H, W, y, loss_mask, cu_seqlens, adv_seg, old_logp, rollout_l
         dH[r_] = dS @ W[v0:v1]
         dW += dS.T @ H[r_]
     counters = np.array([n_active, n_hi, n_lo, mm["geo"], mm["veto"], mm["trunc"],
-                         int(loss_mask.sum()), 0], dtype=np.int64)
+                         int(loss_mask.sum()), n_dropped], dtype=np.int64)
     return dict(loss=total / norm, dH=dH, dW=dW, logp=logp, entropy=ent,
                 counters=counters, active=active, c=c, norm=norm)
 

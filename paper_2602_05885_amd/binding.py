@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(_PKG, "libpg_head.so")
 PG_OK = 0
 CALL_LOGPROB_FWD = 0
 CALL_LOSS_FWD_BWD = 1
-COUNTER_NAMES = ("active", "clip_hi", "clip_lo", "seg_geo", "seg_veto", "truncated", "loss_tokens", "reserved")
+COUNTER_NAMES = ("active", "clip_hi", "clip_lo", "seg_geo", "seg_veto", "truncated", "loss_tokens", "seg_dropped")
 
 EXPORTS = ("pg_last_error", "pg_workspace_bytes", "trloo_advantage", "pg_logprob_fwd", "pg_loss_fwd_bwd",
            "pg_sft_fwd_bwd", "pg_head_shard_fwd", "pg_head_partials_merge", "pg_loss_shard_bwd", "grpo_advantage",
@@ -87,7 +87,7 @@ def lib() -> C.CDLL:
                                      C.c_size_t, C.c_void_p]
         L.pg_loss_fwd_bwd.restype = C.c_int32
         L.pg_loss_fwd_bwd.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
-                                      C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int64,
+                                      C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int64,
                                       C.c_int64, C.POINTER(PgParams), C.c_void_p, C.c_void_p, C.c_void_p,
                                       C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
         L.pg_sft_fwd_bwd.restype = C.c_int32
@@ -101,7 +101,7 @@ def lib() -> C.CDLL:
         L.pg_head_partials_merge.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
         L.pg_loss_shard_bwd.restype = C.c_int32
         L.pg_loss_shard_bwd.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
-                                        C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64,
+                                        C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64,
                                         C.c_int64, C.c_int64, C.c_int64, C.POINTER(PgParams), C.c_void_p, C.c_void_p,
                                         C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                         C.c_size_t, C.c_void_p]
@@ -270,8 +270,11 @@ def pg_logprob_fwd(H, W, y, row_mask, params: Params, workspace: torch.Tensor, w
 
 
 def pg_loss_fwd_bwd(H, W, y, loss_mask, cu_seqlens, adv, seg_sample, old_logp, rollout_logp, params: Params,
-                    workspace: torch.Tensor, dW: Optional[torch.Tensor] = None, out=None, stream=None):
-    """Returns dict(loss [1] f32, dH, dW, logp, entropy, counters [8] i64), all on the device of H."""
+                    workspace: torch.Tensor, dW: Optional[torch.Tensor] = None, out=None, stream=None,
+                    sample_keep: Optional[torch.Tensor] = None):
+    """Returns dict(loss [1] f32, dH, dW, logp, entropy, counters [8] i64), all on the device of H.
+
+    sample_keep: uint8 keep flags indexed like adv (e.g. from prs_retain); None keeps every sample."""
     T, d = H.shape
     V = W.shape[0]
     S = cu_seqlens.numel() - 1
@@ -290,7 +293,8 @@ def pg_loss_fwd_bwd(H, W, y, loss_mask, cu_seqlens, adv, seg_sample, old_logp, r
         dW = torch.empty((V, d), dtype=torch.bfloat16 if params.dW_dtype else torch.float32, device=dev)
     p = params.c_struct()
     _check(lib().pg_loss_fwd_bwd(_ptr(H), _ptr(W), _ptr(y), _ptr(loss_mask), _ptr(cu_seqlens), S, _ptr(adv),
-                                 _ptr(seg_sample), _ptr(old_logp), _ptr(rollout_logp), T, d, V, C.byref(p),
+                                 _ptr(seg_sample), _ptr(sample_keep), _ptr(old_logp), _ptr(rollout_logp), T, d, V,
+                                 C.byref(p),
                                  _ptr(loss), _ptr(dH), _ptr(dW), _ptr(logp), _ptr(ent), _ptr(counters),
                                  _ptr(workspace), workspace.numel(), _stream(stream)))
     return dict(loss=loss, dH=dH, dW=dW, logp=logp, entropy=ent, counters=counters)
@@ -343,7 +347,8 @@ def pg_head_partials_merge(a, b, out=None, stream=None):
 
 def pg_loss_shard_bwd(H, W_shard, y, loss_mask, cu_seqlens, adv, seg_sample, old_logp, rollout_logp, partials,
                       v_offset: int, params: Params, workspace: torch.Tensor, dH_f32: bool = True,
-                      dW: Optional[torch.Tensor] = None, out=None, stream=None):
+                      dW: Optional[torch.Tensor] = None, out=None, stream=None,
+                      sample_keep: Optional[torch.Tensor] = None):
     """One vocab shard's loss + backward from the states merged over all shards.
 
     Returns dict(loss, dH (this shard's partial sum), dW (the shard's rows), logp, entropy, counters)."""
@@ -365,7 +370,8 @@ def pg_loss_shard_bwd(H, W_shard, y, loss_mask, cu_seqlens, adv, seg_sample, old
         dW = torch.empty((Vs, d), dtype=torch.bfloat16 if params.dW_dtype else torch.float32, device=dev)
     p = params.c_struct()
     _check(lib().pg_loss_shard_bwd(_ptr(H), _ptr(W_shard), _ptr(y), _ptr(loss_mask), _ptr(cu_seqlens), S, _ptr(adv),
-                                   _ptr(seg_sample), _ptr(old_logp), _ptr(rollout_logp), _ptr(partials), T, d, Vs,
+                                   _ptr(seg_sample), _ptr(sample_keep), _ptr(old_logp), _ptr(rollout_logp),
+                                   _ptr(partials), T, d, Vs,
                                    int(v_offset), C.byref(p), _ptr(loss), _ptr(dH), 1 if dH_f32 else 0, _ptr(dW),
                                    _ptr(logp), _ptr(ent), _ptr(counters), _ptr(workspace), workspace.numel(),
                                    _stream(stream)))

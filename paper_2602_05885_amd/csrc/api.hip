@@ -275,7 +275,8 @@ struct Shard {
 // cross-entropy call (sft = 1: no segments, no advantages, no mismatch correction).
 int32_t loss_fwd_bwd(int sft, const void* H, const void* W, const int32_t* y, const uint8_t* loss_mask,
                      const int32_t* cu_seqlens, int32_t S, const double* adv, const int32_t* seg_sample,
-                     const float* old_logp, const float* rollout_logp, int64_t T, int64_t d, int64_t V,
+                     const uint8_t* sample_keep, const float* old_logp, const float* rollout_logp, int64_t T, int64_t d,
+                     int64_t V,
                      const pg_params* h_params, float* loss_out, void* dH, void* dW, float* logp_out,
                      float* entropy_out, int64_t* counters_out, void* workspace, size_t workspace_bytes,
                      void* stream, const Shard& shard);
@@ -356,12 +357,14 @@ int32_t pg_logprob_fwd(const void* H, const void* W, const int32_t* y, const uin
 
 int32_t pg_loss_fwd_bwd(const void* H, const void* W, const int32_t* y, const uint8_t* loss_mask,
                         const int32_t* cu_seqlens, int32_t S, const double* adv, const int32_t* seg_sample,
-                        const float* old_logp, const float* rollout_logp, int64_t T, int64_t d, int64_t V,
+                        const uint8_t* sample_keep, const float* old_logp, const float* rollout_logp, int64_t T,
+                        int64_t d, int64_t V,
                         const pg_params* h_params, float* loss_out, void* dH, void* dW, float* logp_out,
                         float* entropy_out, int64_t* counters_out, void* workspace, size_t workspace_bytes,
                         void* stream) {
-  return loss_fwd_bwd(0, H, W, y, loss_mask, cu_seqlens, S, adv, seg_sample, old_logp, rollout_logp, T, d, V, h_params,
-                      loss_out, dH, dW, logp_out, entropy_out, counters_out, workspace, workspace_bytes, stream, Shard{});
+  return loss_fwd_bwd(0, H, W, y, loss_mask, cu_seqlens, S, adv, seg_sample, sample_keep, old_logp, rollout_logp, T, d, V,
+                      h_params, loss_out, dH, dW, logp_out, entropy_out, counters_out, workspace, workspace_bytes, stream,
+                      Shard{});
 }
 
 int32_t pg_head_shard_fwd(const void* H, const void* W_shard, const int32_t* y, const uint8_t* row_mask, int64_t T,
@@ -401,8 +404,8 @@ int32_t pg_head_partials_merge(const float* a, const float* b, float* out, int64
 
 int32_t pg_loss_shard_bwd(const void* H, const void* W_shard, const int32_t* y, const uint8_t* loss_mask,
                           const int32_t* cu_seqlens, int32_t S, const double* adv, const int32_t* seg_sample,
-                          const float* old_logp, const float* rollout_logp, const float* partials, int64_t T, int64_t d,
-                          int64_t V_shard, int64_t v_offset, const pg_params* h_params, float* loss_out, void* dH_partial,
+                          const uint8_t* sample_keep, const float* old_logp, const float* rollout_logp,
+                          const float* partials, int64_t T, int64_t d, int64_t V_shard, int64_t v_offset, const pg_params* h_params, float* loss_out, void* dH_partial,
                           int32_t dH_f32, void* dW_shard, float* logp_out, float* entropy_out, int64_t* counters_out,
                           void* workspace, size_t workspace_bytes, void* stream) {
   if (v_offset < 0 || v_offset > (1ll << 30)) return fail(PG_ERR_INVALID_ARG, "v_offset out of range");
@@ -411,8 +414,8 @@ int32_t pg_loss_shard_bwd(const void* H, const void* W_shard, const int32_t* y, 
   if (misaligned(partials)) return fail(PG_ERR_INVALID_ARG, "partials must be 16-byte aligned");
   Shard sh;
   sh.partials = partials; sh.v_offset = v_offset; sh.dH_f32 = dH_f32; sh.what = "pg_loss_shard_bwd";
-  return loss_fwd_bwd(0, H, W_shard, y, loss_mask, cu_seqlens, S, adv, seg_sample, old_logp, rollout_logp, T, d, V_shard,
-                      h_params, loss_out, dH_partial, dW_shard, logp_out, entropy_out, counters_out, workspace,
+  return loss_fwd_bwd(0, H, W_shard, y, loss_mask, cu_seqlens, S, adv, seg_sample, sample_keep, old_logp, rollout_logp, T,
+                      d, V_shard, h_params, loss_out, dH_partial, dW_shard, logp_out, entropy_out, counters_out, workspace,
                       workspace_bytes, stream, sh);
 }
 
@@ -420,7 +423,7 @@ int32_t pg_sft_fwd_bwd(const void* H, const void* W, const int32_t* y, const uin
                        int64_t V, const pg_params* h_params, float* loss_out, void* dH, void* dW, float* logp_out,
                        float* entropy_out, int64_t* counters_out, void* workspace, size_t workspace_bytes,
                        void* stream) {
-  return loss_fwd_bwd(1, H, W, y, loss_mask, nullptr, 0, nullptr, nullptr, nullptr, nullptr, T, d, V, h_params,
+  return loss_fwd_bwd(1, H, W, y, loss_mask, nullptr, 0, nullptr, nullptr, nullptr, nullptr, nullptr, T, d, V, h_params,
                       loss_out, dH, dW, logp_out, entropy_out, counters_out, workspace, workspace_bytes, stream, Shard{});
 }
 
@@ -517,7 +520,8 @@ namespace {
 
 int32_t loss_fwd_bwd(int sft, const void* H, const void* W, const int32_t* y, const uint8_t* loss_mask,
                      const int32_t* cu_seqlens, int32_t S, const double* adv, const int32_t* seg_sample,
-                     const float* old_logp, const float* rollout_logp, int64_t T, int64_t d, int64_t V,
+                     const uint8_t* sample_keep, const float* old_logp, const float* rollout_logp, int64_t T, int64_t d,
+                     int64_t V,
                      const pg_params* h_params, float* loss_out, void* dH, void* dW, float* logp_out,
                      float* entropy_out, int64_t* counters_out, void* workspace, size_t workspace_bytes,
                      void* stream, const Shard& shard) {
@@ -550,6 +554,7 @@ int32_t loss_fwd_bwd(int sft, const void* H, const void* W, const int32_t* y, co
 
   pg::PrepArgs prep = base_prep(pl, ws);
   prep.mask = loss_mask; prep.cu = cu_seqlens; prep.S = S; prep.adv = adv; prep.seg_sample = seg_sample;
+  prep.sample_keep = sample_keep;
   prep.old_logp = old_logp; prep.rollout_logp = rollout_logp;
   prep.mismatch_mode = sft ? PG_MISMATCH_NONE : p.mismatch_mode; prep.geo_lo = p.geo_lo; prep.geo_hi = p.geo_hi;
   prep.veto_ratio = p.veto_ratio; prep.trunc_c = p.trunc_c; prep.norm_override = p.norm_override;

@@ -88,6 +88,7 @@ struct PrepArgs {
   int S;
   const double* adv;
   const int* seg_sample;
+  const uint8_t* sample_keep; // indexed like adv (nullable = keep all): 0 drops the segment
   const float* old_logp;
   const float* rollout_logp;
   int T, t_cap;

@@ -83,7 +83,8 @@ __global__ void prep_init_kernel(PrepArgs a) {
 }
 
 // One workgroup per segment (= one training sample): Sec. 5.1's geometric-mean ratio and
-// token veto over the sample's loss tokens, decided in fp64, then per-row weights.
+// token veto over the sample's loss tokens, decided in fp64, then per-row weights.  A sample
+// whose keep flag is 0 (Sec. 5.2's rejection sampling) is skipped before any of that.
 __global__ __launch_bounds__(256) void prep_segment_kernel(PrepArgs a) {
   __shared__ double sh_sum[256];
   __shared__ double sh_min[256];
@@ -119,7 +120,11 @@ __global__ __launch_bounds__(256) void prep_segment_kernel(PrepArgs a) {
   if (tid == 0) {
     int keep = 1;
     const int nn = sh_n[0];
-    if (nn > 0) {
+    const bool dropped = a.sample_keep && !a.sample_keep[a.seg_sample ? a.seg_sample[s] : s];
+    if (dropped) {            // filtered out before training (PRS): as if the sample had no loss rows
+      keep = 0;
+      if (nn > 0) atomicAdd(&a.counters[7], 1ull);
+    } else if (nn > 0) {
       atomicAdd(&a.counters[6], (unsigned long long)nn);
       if (mm) {
         const bool vetoed = (a.veto_ratio > 0.f) && (exp(sh_min[0]) < (double)a.veto_ratio);

@@ -60,13 +60,23 @@ __global__ __launch_bounds__(NTHREADS) void tile_kernel(const __bf16* A, const _
 // The engine's per-wavefront register tile (4 x 8 MFMA tiles, 8 wavefronts per workgroup, one
 // workgroup per CU) with every operand already in registers.  clk[0..1] = shader-clock and
 // 100 MHz wall-clock ticks of workgroup 0 over the loop.
-__global__ __launch_bounds__(NTHREADS) void mfma_only_kernel(float* out, int iters, long long* clk) {
+// random_operands = 0: small multiples of 0.01 / 0.02 (few mantissa bits set); 1: hashed values
+// with full-entropy mantissas in (-1, 1), the kind of data the contractions see.
+__device__ __forceinline__ float hashed_unit(unsigned x) {
+  x ^= x >> 16; x *= 0x85ebca6bu; x ^= x >> 13; x *= 0xc2b2ae35u; x ^= x >> 16;
+  return (float)(x & 0xffffff) / 8388608.f - 1.f;
+}
+__global__ __launch_bounds__(NTHREADS) void mfma_only_kernel(float* out, int iters, long long* clk, int random_operands) {
   const int lane = threadIdx.x & 63;
   bf16x8 a[GM], b[GN];
   for (int i = 0; i < GM; ++i)
-    for (int e = 0; e < 8; ++e) a[i][e] = (__bf16)(0.01f * (float)((lane * 7 + e * 3 + i) % 17 - 8));
+    for (int e = 0; e < 8; ++e)
+      a[i][e] = random_operands ? (__bf16)hashed_unit(threadIdx.x * 64 + i * 8 + e)
+                                : (__bf16)(0.01f * (float)((lane * 7 + e * 3 + i) % 17 - 8));
   for (int j = 0; j < GN; ++j)
-    for (int e = 0; e < 8; ++e) b[j][e] = (__bf16)(0.02f * (float)((lane * 5 + e + j) % 13 - 6));
+    for (int e = 0; e < 8; ++e)
+      b[j][e] = random_operands ? (__bf16)(0.05f * hashed_unit(0x9e3779b9u + threadIdx.x * 64 + j * 8 + e))
+                                : (__bf16)(0.02f * (float)((lane * 5 + e + j) % 13 - 6));
   f32x4 acc[GM][GN];
   zero_acc(acc);
   const long long c0 = clock64(), w0 = wall_clock64();
@@ -146,24 +156,25 @@ int main(int argc, char** argv) {
     long long* clk;
     const int n_it = 20000;
     CK(hipMalloc(&out, (size_t)1024 * NTHREADS * 4)); CK(hipMalloc(&clk, 16));
-    for (int pass = 0; pass < 4; ++pass) {
+    for (int pass = 0; pass < 6; ++pass) {
       const int wg_per_cu = 1 + (pass & 1);
+      const int random_operands = pass >= 4;
       const int grid = 256 * wg_per_cu;
-      mfma_only_kernel<<<grid, NTHREADS>>>(out, n_it / 2, clk);   // long enough for the clock to settle
+      mfma_only_kernel<<<grid, NTHREADS>>>(out, n_it / 2, clk, random_operands);   // long enough for the clock to settle
       CK(hipDeviceSynchronize());
       hipEvent_t e0, e1;
       CK(hipEventCreate(&e0)); CK(hipEventCreate(&e1));
       CK(hipEventRecord(e0));
-      mfma_only_kernel<<<grid, NTHREADS>>>(out, n_it, clk);
+      mfma_only_kernel<<<grid, NTHREADS>>>(out, n_it, clk, random_operands);
       CK(hipEventRecord(e1)); CK(hipEventSynchronize(e1));
       float ms;
       CK(hipEventElapsedTime(&ms, e0, e1));
       long long h[2];
       CK(hipMemcpy(h, clk, 16, hipMemcpyDeviceToHost));
       const double fl = (double)grid * (NTHREADS / 64) * n_it * (GM * GN) * 16384.0;
-      printf("[mfma ] registers only, %d workgroup(s) of %d wavefronts per CU: %.3f ms  %.1f TFLOP/s  (%.1f%% of 2500)  "
-             "shader clock %.3f GHz\n", wg_per_cu, NTHREADS / 64, ms, fl / ms / 1e9, fl / ms / 1e9 / 25.0,
-             h[1] ? (double)h[0] / (double)h[1] * 0.1 : 0.0);
+      printf("[mfma ] registers only, %s operands, %d workgroup(s) of %d wavefronts per CU: %.3f ms  %.1f TFLOP/s  "
+             "(%.1f%% of 2500)  shader clock %.3f GHz\n", random_operands ? "random" : "small-integer", wg_per_cu,
+             NTHREADS / 64, ms, fl / ms / 1e9, fl / ms / 1e9 / 25.0, h[1] ? (double)h[0] / (double)h[1] * 0.1 : 0.0);
       fflush(stdout);
     }
     CK(hipFree(out)); CK(hipFree(clk));

@@ -67,13 +67,13 @@ def test_invalid_arguments_return_error_codes():
     rc = lib.pg_logprob_fwd(one, one, one, None, 8, 72, 100, C.byref(p), one, None, None, one, 1 << 30, None)
     assert rc == -2
     pm = B.Params(mismatch_mode=1).c_struct()
-    rc = lib.pg_loss_fwd_bwd(one, one, one, one, one, 1, one, None, one, None, 8, 64, 100, C.byref(pm), one, one, one,
+    rc = lib.pg_loss_fwd_bwd(one, one, one, one, one, 1, one, None, None, one, None, 8, 64, 100, C.byref(pm), one, one, one,
                              None, None, None, one, 1 << 30, None)
     assert rc == -1 and "rollout_logp" in B.pg_last_error()
-    rc = lib.pg_loss_fwd_bwd(one, one, one, one, one, 0, one, None, None, None, 8, 64, 100, C.byref(p), one, one, one,
+    rc = lib.pg_loss_fwd_bwd(one, one, one, one, one, 0, one, None, None, None, None, 8, 64, 100, C.byref(p), one, one, one,
                              None, None, None, one, 1 << 30, None)
     assert rc == -1
-    rc = lib.pg_loss_fwd_bwd(one, one, one, one, one, 1, one, None, None, None, 8, 64, 100, None, one, one, one,
+    rc = lib.pg_loss_fwd_bwd(one, one, one, one, one, 1, one, None, None, None, None, 8, 64, 100, None, one, one, one,
                              None, None, None, one, 1 << 30, None)
     assert rc == -1 and "params" in B.pg_last_error()
 
@@ -132,7 +132,7 @@ def test_shard_entry_points_validate_arguments():
     assert lib.pg_head_partials_merge(one, C.c_void_p(4), one, 4, None) == -1 and "aligned" in B.pg_last_error()
     assert lib.pg_head_partials_merge(one, one, one, -1, None) == -1
     assert lib.pg_head_partials_merge(None, None, None, 0, None) == 0
-    args = lambda partials, voff, f32, ws: (one, one, one, one, one, 1, one, None, None, None, partials, 8, 64, 100, voff,
+    args = lambda partials, voff, f32, ws: (one, one, one, one, one, 1, one, None, None, None, None, partials, 8, 64, 100, voff,
                                             C.byref(p), one, one, f32, one, None, None, None, one, ws, None)
     assert lib.pg_loss_shard_bwd(*args(None, 0, 1, big)) == -1 and "partials" in B.pg_last_error()
     assert lib.pg_loss_shard_bwd(*args(one, -5, 1, big)) == -1

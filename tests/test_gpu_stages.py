@@ -203,3 +203,63 @@ def test_rmsnorm_feeds_the_head(dev):
     assert abs(float(out["loss"][0]) - ref["loss"]) <= TOL_LOSS * abs(ref["loss"])
     assert rel_fro(np64(dX), dX_ref) <= TOL_GRAD
     assert rel_fro(dg.double().cpu().numpy(), dg_ref) <= TOL_GRAD
+
+
+# ------------------------------------------------------------------------------------ the whole recipe
+@pytest.mark.parametrize("mode,kind,seed", [(1, "window", 41), (2, "token", 42)])
+def test_recipe_reward_prs_trloo_loss(dev, monkeypatch, mode, kind, seed):
+    """Rewards with the profiling ratio (Eq. 1, 6-7) -> PRS keep flags (Eq. 8) -> TRLOO (Eq. 5) -> loss with
+    mismatch correction (Sec. 5.1), chained on the device with no host step between the calls: the keep
+    flags and the advantage table go straight into pg_loss_fwd_bwd."""
+    from tests._cases import build_loss_case
+    spec = synth.small_spec(seed=seed, P=4, K=5, Tmax=3)
+    batch, tin, nin = build_loss_case(spec, dev, lambda H, W, y, tau: O.lm_head_logprob(H, W, y, tau)[0], kind,
+                                      on_policy=False)
+    T, d, V, S = batch.T, spec.d, spec.V, batch.S
+    monkeypatch.setenv("PG_HEAD_DS_BUDGET_BYTES", str(((T + 255) // 256 * 256) * 2 * 256 * 4))
+    n = spec.P * spec.K * spec.Tmax
+    rng = np.random.default_rng(seed)
+    correct = (rng.random(n) < 0.7).astype(np.uint8)
+    t_ref = rng.lognormal(0.0, 0.5, n).astype(np.float32)
+    t_ker = (t_ref / np.maximum(rng.lognormal(0.0, 0.8, n), 0.05)).astype(np.float32)
+    t_tot = rng.lognormal(0.0, 0.5, n).astype(np.float32)
+    t_gen = (t_tot * rng.random(n)).astype(np.float32)
+    valid = nin["valid"]
+    to = lambda a: torch.from_numpy(a).to(dev)
+    prm = B.Params(mismatch_mode=mode)
+    ws = B.alloc_workspace(T, d, V, S, prm, B.CALL_LOSS_FWD_BWD, dev)
+    R, pr = B.turn_reward(to(correct), to(t_ref), to(t_ker), to(t_gen), to(t_tot), 3.0)
+    keep, _ = B.prs_retain(pr, tin["valid"].reshape(-1), 2602, 0.3, 0.1, False)
+    adv, _, _ = B.trloo_advantage(R.reshape(spec.P, spec.K, spec.Tmax), tin["valid"], 1.0)
+    out = B.pg_loss_fwd_bwd(tin["H"], tin["W"], tin["y"], tin["loss_mask"], tin["cu"], adv.reshape(-1), tin["seg_sample"],
+                            tin["old"], tin["rollout"], prm, ws, sample_keep=keep)
+    torch.cuda.synchronize()
+
+    R_ref, pr_ref = O.turn_reward(correct, t_ref, t_ker, t_gen, t_tot, 3.0)
+    R32, pr32 = R_ref.astype(np.float32), pr_ref.astype(np.float32)          # what the ABI hands from stage to stage
+    keep_ref, _ = O.prs_retain(pr32, valid.reshape(-1), 2602, 0.3, 0.1, False)
+    assert np.array_equal(keep.cpu().numpy(), keep_ref)
+    _, A, _ = O.trloo_advantage(R32.reshape(spec.P, spec.K, spec.Tmax), valid, 1.0)
+    assert np.abs(adv.cpu().numpy() - A).max() <= TOL_ADV
+    oprm = O.Params(mismatch_mode=mode)
+    seg = nin["seg_sample"]
+    ref = O.pg_loss_fwd_bwd(nin["H"], nin["W"], nin["y"], nin["loss_mask"], nin["cu"], A.reshape(-1)[seg], nin["old"],
+                            nin["rollout"], oprm, seg_keep=keep_ref[seg])
+    cnt = out["counters"].cpu().numpy()
+    assert np.array_equal(cnt, ref["counters"]), (cnt, ref["counters"])
+    assert 0 < cnt[7] < S and 0 < cnt[0] < batch.loss_mask.sum()              # some samples dropped, some kept
+    assert abs(float(out["loss"][0]) - ref["loss"]) <= TOL_LOSS * max(abs(ref["loss"]), 1e-6)
+    assert np.abs(out["logp"].cpu().numpy() - ref["logp"]).max() <= TOL_LOGP
+    dH = np64(out["dH"])
+    assert np.all(dH[~ref["active"]] == 0)
+    assert rel_fro(dH, ref["dH"]) <= TOL_GRAD and rel_fro(np64(out["dW"]), ref["dW"]) <= TOL_GRAD
+    # the same flags as a zeroed loss mask: bitwise the same gradients
+    lm = tin["loss_mask"].clone()
+    cu = batch.cu_seqlens
+    for s in range(S):
+        if not keep_ref[seg[s]]:
+            lm[cu[s]:cu[s + 1]] = 0
+    out2 = B.pg_loss_fwd_bwd(tin["H"], tin["W"], tin["y"], lm, tin["cu"], adv.reshape(-1), tin["seg_sample"],
+                             tin["old"], tin["rollout"], prm, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(out2["dW"], out["dW"]) and torch.equal(out2["dH"], out["dH"]) and torch.equal(out2["loss"], out["loss"])

@@ -204,3 +204,58 @@ def test_rmsnorm_invariants():
     f = lambda Z: (O.rmsnorm_fwd(Z, gamma, 1e-6)[0] * G).sum()
     fd = (f(X + e) - f(X - e)) / 2e-6
     assert abs(fd - O.rmsnorm_bwd(X, gamma, 1e-6, G)[0][2, 5]) < 1e-6
+
+
+# ---------------------------------------------------------------- samples filtered out before training (Sec. 5.2)
+def test_dropped_samples_equal_a_microbatch_packed_without_them():
+    """Dropping a sample by its keep flag must give what a packer gives that never packed it: same loss,
+    same dW, same dH rows for the rows that remain, and the normaliser counts kept loss rows only."""
+    rng = np.random.default_rng(11)
+    T, d, V = 60, 12, 31
+    H = rng.normal(size=(T, d))
+    W = rng.normal(size=(V, d)) * 0.4
+    y = rng.integers(0, V, size=T)
+    cu = np.array([0, 9, 22, 22, 40, 51, 60])               # one empty segment
+    mask = (rng.random(T) < 0.7).astype(np.uint8)
+    mask[40:51] = 0                                          # a segment without loss rows
+    adv = rng.normal(size=6)
+    lp, _, _ = O.lm_head_logprob(H, W, y, 1.0)
+    old = lp + rng.normal(size=T) * 0.1
+    roll = old + rng.normal(size=T) * 0.05
+    keep = np.array([1, 0, 1, 1, 0, 0], np.uint8)            # drops segments 1, 4 (no loss rows) and 5
+    prm = O.Params(mismatch_mode=2)
+    a = O.pg_loss_fwd_bwd(H, W, y, mask, cu, adv, old, roll, prm, seg_keep=keep)
+    rows = np.concatenate([np.arange(cu[s], cu[s + 1]) for s in range(6) if keep[s]])
+    lens = [cu[s + 1] - cu[s] for s in range(6) if keep[s]]
+    cu2 = np.concatenate([[0], np.cumsum(lens)])
+    b = O.pg_loss_fwd_bwd(H[rows], W, y[rows], mask[rows], cu2, adv[keep.astype(bool)], old[rows], roll[rows], prm)
+    assert abs(a["loss"] - b["loss"]) < 1e-15 and a["norm"] == b["norm"] == mask[rows].sum()
+    np.testing.assert_allclose(a["dW"], b["dW"], atol=1e-15)
+    np.testing.assert_allclose(a["dH"][rows], b["dH"], atol=1e-15)
+    gone = np.setdiff1d(np.arange(T), rows)
+    assert not a["dH"][gone].any() and not a["logp"][gone].any()
+    assert a["counters"][7] == 2 and b["counters"][7] == 0       # segment 4 had no loss rows: not counted
+    assert np.array_equal(a["counters"][:7], b["counters"][:7])
+    # keep-all flags change nothing
+    c = O.pg_loss_fwd_bwd(H, W, y, mask, cu, adv, old, roll, prm, seg_keep=np.ones(6, np.uint8))
+    e = O.pg_loss_fwd_bwd(H, W, y, mask, cu, adv, old, roll, prm)
+    assert c["loss"] == e["loss"] and np.array_equal(c["dW"], e["dW"])
+
+
+def test_dropped_sample_is_not_examined_by_mismatch_rejection():
+    """A dropped sample with a vetoed token raises neither the veto nor the window counter."""
+    T = 20
+    H = np.eye(T, 8)
+    W = np.ones((5, 8)) * 0.1
+    y = np.zeros(T, np.int64)
+    cu = np.array([0, 10, 20])
+    mask = np.ones(T, np.uint8)
+    old = np.full(T, -1.0)
+    roll = old.copy()
+    roll[3] = old[3] + 12.0                                  # ratio e^-12 < 1e-4 in segment 0
+    prm = O.Params(mismatch_mode=1)
+    kept = O.pg_loss_fwd_bwd(H, W, y, mask, cu, [1.0, 1.0], old, roll, prm)
+    drop = O.pg_loss_fwd_bwd(H, W, y, mask, cu, [1.0, 1.0], old, roll, prm, seg_keep=[0, 1])
+    assert kept["counters"][4] == 1 and kept["counters"][3] == 1 and kept["counters"][6] == 20
+    assert drop["counters"][4] == 0 and drop["counters"][3] == 0 and drop["counters"][7] == 1
+    assert drop["counters"][6] == 10 and drop["counters"][0] == 10
