@@ -420,9 +420,10 @@ __global__ __launch_bounds__(256) void combine_kernel(CombineArgs a) {
   const float r = a.old_logp ? expf(logp - a.old_logp[row]) : 1.f;
   const float lo = 1.f - a.eps_lo, hi = 1.f + a.eps_hi;
   const float rc = fminf(fmaxf(r, lo), hi);
-  const float l = -fminf(r * A, rc * A);
+  float l = -fminf(r * A, rc * A);
   const bool flows = (A >= 0.f && r <= hi) || (A < 0.f && r >= lo);
-  const float g = flows ? -A * r : 0.f;
+  float g = flows ? -A * r : 0.f;
+  if (r != r) { l = r; g = r; }      // fminf / fmaxf drop a NaN operand: a NaN ratio must reach the loss
   if (A >= 0.f && r > hi) atomicAdd(&a.counters[1], 1ull);
   if (A < 0.f && r < lo) atomicAdd(&a.counters[2], 1ull);
   a.coefc[i] = c * g / ctl.norm * a.inv_tau;

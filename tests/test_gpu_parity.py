@@ -97,6 +97,40 @@ def test_logprob_fwd_optional_outputs_and_bad_token(dev):
     assert abs(float(logp[5]) + float(lse[5])) < 1e-5
 
 
+def test_non_finite_inputs_propagate_and_stay_local(dev):
+    """A NaN or an infinity in the inputs must come out as NaN in what depends on it and nowhere else; no
+    kernel takes a data-dependent branch or address from H or W, so the call returns as always."""
+    T, d, V = 600, 64, 900
+    H, W, y = synth.make_head(T, d, V, "bf16", 17, dev)
+    prm = B.Params(mismatch_mode=0)
+    ws = B.alloc_workspace(T, d, V, 1, prm, B.CALL_LOSS_FWD_BWD, dev)
+    clean = B.pg_logprob_fwd(H, W, y, None, prm, ws)[0].clone()
+    Hn = H.clone()
+    Hn[7, 3] = float("nan")
+    Hn[300, 5] = float("inf")
+    logp, ent, lse = B.pg_logprob_fwd(Hn, W, y, None, prm, ws)
+    torch.cuda.synchronize()
+    bad = torch.zeros(T, dtype=torch.bool, device=dev)
+    bad[7] = bad[300] = True
+    assert torch.isnan(logp[bad]).all() and torch.isnan(lse[bad]).all()
+    assert torch.equal(logp[~bad], clean[~bad])                     # every other row is untouched, bit for bit
+    ones = torch.ones(T, dtype=torch.uint8, device=dev)
+    cu = torch.tensor([0, T], dtype=torch.int32, device=dev)
+    adv = torch.ones(1, dtype=torch.float64, device=dev)
+    out = B.pg_loss_fwd_bwd(Hn, W, y, ones, cu, adv, None, clean, None, prm, ws)     # ratio exp(logp - old)
+    torch.cuda.synchronize()
+    assert torch.isnan(out["loss"]).all() and torch.isnan(out["dH"][7].float()).all()
+    ok = out["dH"][~bad].float()
+    assert torch.isfinite(ok).all()                                 # other rows' gradients do not see it
+    assert int(out["counters"][0]) == T
+    # a masked-out row may hold anything: it is never read
+    mask = ones.clone()
+    mask[7] = mask[300] = 0
+    out2 = B.pg_loss_fwd_bwd(Hn, W, y, mask, cu, adv, None, clean, None, prm, ws)
+    torch.cuda.synchronize()
+    assert torch.isfinite(out2["loss"]).all() and torch.isfinite(out2["dW"]).all() and torch.isfinite(out2["dH"].float()).all()
+
+
 # ------------------------------------------------------------------------------------ loss fwd + bwd
 def _run_loss(dev, spec, prm, mismatch_kind, on_policy, monkeypatch=None, budget_tiles=None, accumulate=False):
     batch, tin, nin = build_loss_case(spec, dev, oracle_logp, mismatch_kind, on_policy)

@@ -284,3 +284,9 @@ def test_dH_rows_matches_full():
     rows = np.nonzero(mask)[0][:5]
     coef = -np.repeat(adv, 4)[rows] / out["norm"]
     np.testing.assert_allclose(O.dH_rows(H[rows], W, y[rows], coef, 0.7), out["dH"][rows], atol=1e-14)
+
+
+def test_surrogate_propagates_nan_to_the_loss():
+    """A NaN log-prob must not be swallowed by the min / clip of the surrogate."""
+    l, g, r, _, _ = O.surrogate(np.array([np.nan, -1.0]), np.array([-1.0, -1.0]), np.array([1.0, 1.0]), O.Params())
+    assert np.isnan(l[0]) and l[1] == -1.0
