@@ -251,7 +251,7 @@ int32_t pg_monitors(const float* logp_train, const float* logp_rollout, const fl
  *   xhat = x rstd,   dx = rstd (gamma g - xhat mean_j(gamma_j g_j xhat_j)),   dgamma = sum_rows g xhat.
  * X, H_out, dH, dX_out are [T,d], gamma is [d], all in `dtype` (PG_DTYPE_*); arithmetic is fp32;
  * rstd_out [T] float32 (nullable); dgamma_out [d] float32 (overwritten).  d must be a multiple of 8
- * (and <= 8192 for the backward); X, gamma, H_out, dH, dX_out must be 16-byte aligned.  The backward
+ * and at most 8192 (PG_ERR_UNSUPPORTED_SHAPE otherwise); X, gamma, H_out, dH, dX_out must be 16-byte aligned.  The backward
  * needs pg_rmsnorm_bwd_workspace_bytes(d) bytes of workspace; its sums have a fixed order (bitwise
  * repeatable).  dX_out may alias dH.
  */

@@ -477,7 +477,8 @@ int32_t pg_rmsnorm_fwd(const void* X, const void* gamma, int64_t T, int64_t d, f
                        float* rstd_out, void* stream) {
   if (T < 0 || d < 1) return fail(PG_ERR_INVALID_ARG, "T must be >= 0 and d >= 1");
   if (dtype != PG_DTYPE_BF16 && dtype != PG_DTYPE_F32) return fail(PG_ERR_INVALID_ARG, "unknown dtype %d", dtype);
-  if (d % 8 != 0 || d > (1 << 24)) return fail(PG_ERR_UNSUPPORTED_SHAPE, "d=%lld is not a multiple of 8", (long long)d);
+  if (d % 8 != 0 || d > pg::NORM_MAX_D)
+    return fail(PG_ERR_UNSUPPORTED_SHAPE, "d=%lld must be a multiple of 8 and at most %d", (long long)d, pg::NORM_MAX_D);
   if (!(eps >= 0.f) || !std::isfinite(eps)) return fail(PG_ERR_INVALID_ARG, "eps must be finite and >= 0");
   if (T == 0) return PG_OK;
   if (!X || !gamma || !H_out) return fail(PG_ERR_INVALID_ARG, "X, gamma and H_out must not be NULL");

@@ -212,7 +212,7 @@ struct MonitorArgs {
 void launch_monitors(const MonitorArgs& a, hipStream_t s);
 
 constexpr int NORM_STRIPS = 1024;    // row strips of the RMSNorm backward (one workgroup and one dgamma partial each)
-constexpr int NORM_MAX_D = 8192;     // the backward keeps a row in registers: 4 x 8 columns per thread of 256
+constexpr int NORM_MAX_D = 8192;     // both kernels keep a row in registers (backward: 4 x 8 columns per thread of 256)
 struct NormArgs {
   const void* X;        // [T, d] bf16 or fp32
   const void* gamma;    // [d]    same dtype

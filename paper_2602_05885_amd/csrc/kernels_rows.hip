@@ -672,8 +672,8 @@ void launch_monitors(const MonitorArgs& a, hipStream_t s) {
 // ------------------------------------------------------------------ RMSNorm in front of the head
 // h = x * rstd * gamma, rstd = 1 / sqrt(mean x^2 + eps).  One wavefront per row, 16-byte (bf16) or
 // 32-byte (fp32) accesses of 8 consecutive elements per lane and step; fp32 arithmetic, the sum of
-// squares reduced in a fixed butterfly order.  Both kernels read their rows twice (the second
-// read comes from L2); they are HBM-bound.
+// squares reduced in a fixed butterfly order.  Both kernels hold the current row in registers and
+// read every element once; they are HBM-bound.
 template <bool F32>
 __device__ __forceinline__ void load8(const void* p, long long elem, float (&v)[8]) {
   if (F32) {
@@ -703,17 +703,27 @@ __device__ __forceinline__ float wave_sum(float v) {
   for (int sh = 32; sh >= 1; sh >>= 1) v += __shfl_xor(v, sh);
   return v;
 }
-template <bool F32>
-__device__ __forceinline__ float row_rstd(const void* X, long long row, int d, float eps, int lane) {
-  float ss = 0.f;
-  for (int c = lane * 8; c < d; c += 64 * 8) {
-    float x[8];
-    load8<F32>(X, row * d + c, x);
+// Forward: a lane keeps its (up to) NORM_FC x 8 elements of the row in registers between the sum
+// of squares and the scaling, so every element of X is read from memory once.  All loads of the
+// row are issued before the first use, so they are in flight together.
+constexpr int NORM_FC = NORM_MAX_D / 512;          // 8-column steps per lane
+
+template <bool F32> struct Raw8;
+template <> struct Raw8<true> { float4 a, b; };
+template <> struct Raw8<false> { bf16x8 v; };
+__device__ __forceinline__ void raw_load(const void* p, long long elem, Raw8<true>& r) {
+  r.a = *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(p) + elem);
+  r.b = *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(p) + elem + 4);
+}
+__device__ __forceinline__ void raw_load(const void* p, long long elem, Raw8<false>& r) {
+  r.v = *reinterpret_cast<const bf16x8*>(reinterpret_cast<const __bf16*>(p) + elem);
+}
+__device__ __forceinline__ void raw_unpack(const Raw8<true>& r, float (&v)[8]) {
+  v[0] = r.a.x; v[1] = r.a.y; v[2] = r.a.z; v[3] = r.a.w; v[4] = r.b.x; v[5] = r.b.y; v[6] = r.b.z; v[7] = r.b.w;
+}
+__device__ __forceinline__ void raw_unpack(const Raw8<false>& r, float (&v)[8]) {
 #pragma unroll
-    for (int e = 0; e < 8; ++e) ss = fmaf(x[e], x[e], ss);
-  }
-  ss = wave_sum(ss);
-  return 1.f / sqrtf(ss / (float)d + eps);
+  for (int e = 0; e < 8; ++e) v[e] = (float)r.v[e];
 }
 
 template <bool F32>
@@ -721,15 +731,37 @@ __global__ __launch_bounds__(256) void rmsnorm_fwd_kernel(NormArgs a) {
   const int lane = threadIdx.x & 63;
   const long long row = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
   if (row >= a.T) return;
-  const float rstd = row_rstd<F32>(a.X, row, a.d, a.eps, lane);
-  if (a.rstd_out && lane == 0) a.rstd_out[row] = rstd;
-  for (int c = lane * 8; c < a.d; c += 64 * 8) {
-    float x[8], g[8], h[8];
-    load8<F32>(a.X, row * a.d + c, x);
-    load8<F32>(a.gamma, c, g);
+  Raw8<F32> raw[NORM_FC];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) h[e] = x[e] * rstd * g[e];
-    store8<F32>(a.H, row * a.d + c, h);
+  for (int q = 0; q < NORM_FC; ++q) {
+    const int c = lane * 8 + q * 512;
+    if (c < a.d) raw_load(a.X, row * a.d + c, raw[q]);
+  }
+  float ss = 0.f;
+#pragma unroll
+  for (int q = 0; q < NORM_FC; ++q) {
+    const int c = lane * 8 + q * 512;
+    if (c < a.d) {
+      float x[8];
+      raw_unpack(raw[q], x);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) ss = fmaf(x[e], x[e], ss);
+    }
+  }
+  ss = wave_sum(ss);
+  const float rstd = 1.f / sqrtf(ss / (float)a.d + a.eps);
+  if (a.rstd_out && lane == 0) a.rstd_out[row] = rstd;
+#pragma unroll
+  for (int q = 0; q < NORM_FC; ++q) {
+    const int c = lane * 8 + q * 512;
+    if (c < a.d) {
+      float x[8], g[8], h[8];
+      raw_unpack(raw[q], x);
+      load8<F32>(a.gamma, c, g);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) h[e] = x[e] * rstd * g[e];
+      store8<F32>(a.H, row * a.d + c, h);
+    }
   }
 }
 void launch_rmsnorm_fwd(const NormArgs& a, hipStream_t s) {
@@ -769,15 +801,30 @@ __global__ __launch_bounds__(256) void rmsnorm_bwd_kernel(NormArgs a) {
     if (c < a.d) load8<F32>(a.gamma, c, g[q]);
   }
   const float inv_d = 1.f / (float)a.d;
+  // The next row's loads are issued before the current row's two workgroup reductions, so a
+  // workgroup always has one row of X and dH in flight while it works on the previous one.
+  Raw8<F32> xr[NORM_NC] = {}, gr_raw[NORM_NC] = {}, xn[NORM_NC] = {}, gn[NORM_NC] = {};
+  auto fetch = [&](long long row, Raw8<F32> (&xa)[NORM_NC], Raw8<F32> (&ga)[NORM_NC]) {
+#pragma unroll
+    for (int q = 0; q < NORM_NC; ++q) {
+      const int c = tid * 8 + q * 2048;
+      if (c < a.d) {
+        raw_load(a.X, row * a.d + c, xa[q]);
+        raw_load(a.dH, row * a.d + c, ga[q]);
+      }
+    }
+  };
+  if (r0 < r1) fetch(r0, xr, gr_raw);
   for (long long row = r0; row < r1; ++row) {
+    if (row + 1 < r1) fetch(row + 1, xn, gn);
     float x[NORM_NC][8], gr[NORM_NC][8];
     float ss = 0.f;
 #pragma unroll
     for (int q = 0; q < NORM_NC; ++q) {
       const int c = tid * 8 + q * 2048;
       if (c < a.d) {
-        load8<F32>(a.X, row * a.d + c, x[q]);
-        load8<F32>(a.dH, row * a.d + c, gr[q]);
+        raw_unpack(xr[q], x[q]);
+        raw_unpack(gr_raw[q], gr[q]);
 #pragma unroll
         for (int e = 0; e < 8; ++e) ss = fmaf(x[q][e], x[q][e], ss);
       }
@@ -807,6 +854,8 @@ __global__ __launch_bounds__(256) void rmsnorm_bwd_kernel(NormArgs a) {
         store8<F32>(a.dX, row * a.d + c, dx);
       }
     }
+#pragma unroll
+    for (int q = 0; q < NORM_NC; ++q) { xr[q] = xn[q]; gr_raw[q] = gn[q]; }
   }
   float* part = a.partial + (size_t)blockIdx.x * a.d;
 #pragma unroll

@@ -107,6 +107,7 @@ def test_rmsnorm_entry_points_validate_arguments():
     one = C.c_void_p(16)
     assert lib.pg_rmsnorm_fwd(one, one, 4, 100, 1e-6, 0, one, None, None) == -2         # d not a multiple of 8
     assert lib.pg_rmsnorm_fwd(one, one, 4, 64, 1e-6, 7, one, None, None) == -1
+    assert lib.pg_rmsnorm_fwd(one, one, 4, 8200, 1e-6, 0, one, None, None) == -2        # beyond the register-resident row
     assert lib.pg_rmsnorm_fwd(None, one, 4, 64, 1e-6, 0, one, None, None) == -1
     assert lib.pg_rmsnorm_fwd(None, None, 0, 64, 1e-6, 0, None, None, None) == 0
     assert int(lib.pg_rmsnorm_bwd_workspace_bytes(5120)) == 1024 * 5120 * 4
