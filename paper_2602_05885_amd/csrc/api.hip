@@ -613,11 +613,13 @@ int32_t loss_fwd_bwd(int sft, const void* H, const void* W, const int32_t* y, co
     h.lda = pl.ld_v; h.ldb = pl.ld_v; h.M = pl.t_cap; h.N = d_i; h.K = kc;
     h.tiles_m = pl.tiles_t; h.tiles_n = (d_i + 255) / 256;
     h.C = at<float>(ws, pl.dHacc); h.ldc = d_i;
-    h.accumulate = c > 0; h.out_bf16 = 0; h.k_from_ctl = 0; h.m_from_ctl = 1; h.ctl = ctl;
+    h.accumulate = c > 0; h.out_bf16 = 0; h.k_from_ctl = 0; h.m_from_ctl = 1; h.split_k = 1; h.ctl = ctl;
     { ProfScope ps(PG_KERNEL_DH, st); pg::launch_gemm_store(h, st); }
   }
 
-  pg::ScatterArgs sc{at<float>(ws, pl.dHacc), at<int>(ws, pl.pos), dH, (int)pl.T, d_i, pl.is_f32 || shard.dH_f32};
+  const int kc0 = (int)(((pl.V < pl.vc ? pl.V : pl.vc) + 255) / 256 * 256);      // contraction length of the first chunk
+  pg::ScatterArgs sc{at<float>(ws, pl.dHacc), at<int>(ws, pl.pos), dH, (int)pl.T, d_i, pl.is_f32 || shard.dH_f32,
+                     1, pl.t_cap, (d_i + 255) / 256, kc0 / 64, ctl};
   pg::launch_scatter_dh(sc, st);
   return check_launches(shard.what ? shard.what : sft ? "pg_sft_fwd_bwd" : "pg_loss_fwd_bwd");
 }

@@ -132,6 +132,23 @@ __device__ __forceinline__ bool map_tile_interleaved(int bid, int tiles_m, int t
   return true;
 }
 
+// Split-K factor of the dH contraction.  Its row extent is the padded number of active tokens,
+// known only on the device; when those rows give fewer tiles than the chip has compute units
+// (a microbatch most of whose samples were rejected), the contraction length is cut into ks
+// parts that run side by side.  Part p accumulates into its own slab of n_pad rows of the
+// [t_cap, d] accumulator (so ks n_pad <= t_cap), and the final scatter adds the slabs in order.
+// Every kernel derives ks from the same device-side values, so the decomposition, and with it
+// the summation order, is fixed for given inputs.
+__host__ __device__ inline int dh_split(int n_pad, int t_cap, int tiles_n, int k_stages) {
+  if (n_pad <= 0) return 1;
+  const int tiles = (n_pad / 256) * tiles_n;
+  int ks = 256 / (tiles > 0 ? tiles : 1);
+  if (ks > t_cap / n_pad) ks = t_cap / n_pad;
+  if (ks > k_stages / 8) ks = k_stages / 8;        // every part keeps at least 8 stages
+  if (ks > 8) ks = 8;
+  return ks < 1 ? 1 : ks;
+}
+
 // ---- operand slabs in LDS ----------------------------------------------------------
 // Row r (one of 256) holds its 64 k-values as eight 16-byte chunks; chunk c is stored at
 // position c ^ ((r >> 1) & 7): a 16-lane group of an operand read (16 consecutive rows, same

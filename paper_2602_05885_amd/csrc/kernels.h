@@ -60,6 +60,7 @@ struct StoreArgs {
   int out_bf16;
   int k_from_ctl;       // contraction length = padded active-token count
   int m_from_ctl;       // row extent        = padded active-token count
+  int split_k;          // with m_from_ctl: cut K into dh_split() parts, part p writes rows p n_pad + m
   const Ctl* ctl;
 };
 
@@ -169,6 +170,10 @@ struct ScatterArgs {
   void* dH;             // [T, d]
   int T, d;
   int out_f32;
+  // split-K slabs of the accumulator (see dh_split): 0 = one slab; else the arguments of dh_split
+  // as the first chunk's contraction saw them
+  int split_k, t_cap, tiles_n, k_stages;
+  const Ctl* ctl;
 };
 void launch_scatter_dh(const ScatterArgs& a, hipStream_t s);
 

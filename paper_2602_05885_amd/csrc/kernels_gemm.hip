@@ -294,16 +294,23 @@ __global__ __launch_bounds__(NTHREADS) void gemm_store_kernel(StoreArgs a) {
   const Ctl ctl = *a.ctl;
   int tm, tn;
   const int m_lim = a.m_from_ctl ? min(a.M, ctl.n_pad) : a.M;
-  if (!map_tile_interleaved(blockIdx.x, min(a.tiles_m, (m_lim + BM - 1) / BM), a.tiles_n, tm, tn)) return;
+  const int tiles_m = min(a.tiles_m, (m_lim + BM - 1) / BM);
   const int K = a.k_from_ctl ? ctl.n_pad : a.K;
+  const int ks = (a.split_k && a.m_from_ctl) ? dh_split(ctl.n_pad, a.M, a.tiles_n, K / BK) : 1;
+  if (!map_tile_interleaved(blockIdx.x, tiles_m * ks, a.tiles_n, tm, tn)) return;
+  const int part = tm / tiles_m;                     // 0 unless the contraction is split
+  tm -= part * tiles_m;
+  const int s0 = (int)((long long)part * (K / BK) / ks), s1 = (int)((long long)(part + 1) * (K / BK) / ks);
+  const uint32_t kb = (uint32_t)s0 * BK * 2u;        // byte offset of this part's first k
 
   const int tid = threadIdx.x;
   TileLoader LA, LB;
-  LA.init(a.B, a.b_bytes, tn * BN, a.ldb, tid);     // engine rows <- n
-  LB.init(a.A, a.a_bytes, tm * BM, a.lda, tid);     // engine columns <- m
+  LA.init(static_cast<const char*>(a.B) + kb, a.b_bytes - kb, tn * BN, a.ldb, tid);     // engine rows <- n
+  LB.init(static_cast<const char*>(a.A) + kb, a.a_bytes - kb, tm * BM, a.lda, tid);     // engine columns <- m
   f32x4 acc[GM][GN];
   zero_acc(acc);
-  mainloop(LA, LB, K / BK, g_smem, acc);
+  mainloop(LA, LB, s1 - s0, g_smem, acc);
+  a.C = static_cast<char*>(a.C) + (size_t)part * ctl.n_pad * a.ldc * (a.out_bf16 ? 2 : 4);
   if (a.out_bf16)
     store_tile<__bf16>(a, tm, tn, m_lim, acc);
   else

@@ -459,9 +459,18 @@ __global__ __launch_bounds__(256) void scatter_dh_kernel(ScatterArgs a) {
   const int t = blockIdx.x;
   const int p = a.pos[t];
   const float* src = a.acc + (size_t)(p < 0 ? 0 : p) * a.d;
+  const int n_pad = a.ctl->n_pad;
+  const int ks = a.split_k ? dh_split(n_pad, a.t_cap, a.tiles_n, a.k_stages) : 1;
+  const size_t slab = (size_t)n_pad * a.d;
   for (int j = threadIdx.x * 4; j < a.d; j += 256 * 4) {
     float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (p >= 0) v = *reinterpret_cast<const float4*>(src + j);
+    if (p >= 0) {
+      v = *reinterpret_cast<const float4*>(src + j);
+      for (int q = 1; q < ks; ++q) {               // split-K slabs, added in a fixed order
+        const float4 w = *reinterpret_cast<const float4*>(src + q * slab + j);
+        v.x += w.x; v.y += w.y; v.z += w.z; v.w += w.w;
+      }
+    }
     if (a.out_f32) {
       *reinterpret_cast<float4*>(reinterpret_cast<float*>(a.dH) + (size_t)t * a.d + j) = v;
     } else {

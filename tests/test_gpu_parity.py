@@ -220,6 +220,45 @@ def test_loss_f32_multichunk_with_truncation(dev, monkeypatch):
     _compare(out, ref, logp_tol=2e-4)
 
 
+@pytest.mark.parametrize("budget_tiles,d", [(None, 128), (4, 128), (None, 512)])
+def test_loss_few_active_rows_split_contraction(dev, monkeypatch, budget_tiles, d):
+    """Most samples rejected by the geometric window: the active rows fill a fraction of the padded row
+    capacity, so the dH contraction is cut along the vocabulary into parts that accumulate side by side
+    (one chunk; several chunks whose last one is too short to be cut; several column tiles)."""
+    spec = synth.small_spec(seed=8080, d=d, V=4200, P=4, K=6, Tmax=3, len_lo=40, len_hi=120)
+    prm = B.Params(mismatch_mode=1)
+    out, ref, batch = _run_loss(dev, spec, prm, "window", on_policy=False, monkeypatch=monkeypatch,
+                                budget_tiles=budget_tiles)
+    n_active = int(ref["counters"][0])
+    t_cap = (batch.T + 255) // 256 * 256
+    n_pad = (n_active + 255) // 256 * 256
+    assert 0 < n_active and 2 * n_pad <= t_cap, (n_active, t_cap)       # room for at least two parts
+    _compare(out, ref)
+    out2, _, _ = _run_loss(dev, spec, prm, "window", on_policy=False, monkeypatch=monkeypatch, budget_tiles=budget_tiles)
+    assert torch.equal(out["dH"], out2["dH"]) and torch.equal(out["dW"], out2["dW"])      # fixed summation order
+
+
+def test_loss_very_few_active_rows_eight_parts(dev):
+    """Four samples of 58 kept by their keep flags: the dH contraction runs in its maximum of eight parts."""
+    spec = synth.small_spec(seed=8081, d=128, V=4200, P=4, K=6, Tmax=3, len_lo=40, len_hi=120)
+    prm = B.Params(mismatch_mode=2)
+    batch, tin, nin = build_loss_case(spec, dev, oracle_logp, "token", on_policy=False)
+    T, d, V, S = batch.T, spec.d, spec.V, batch.S
+    keep = np.zeros(spec.P * spec.K * spec.Tmax, np.uint8)
+    keep[nin["seg_sample"][[3, 17, 30, 44]]] = 1
+    adv, _, _ = B.trloo_advantage(tin["rewards"], tin["valid"], 1.0)
+    ws = B.alloc_workspace(T, d, V, S, prm, B.CALL_LOSS_FWD_BWD, dev)
+    out = B.pg_loss_fwd_bwd(tin["H"], tin["W"], tin["y"], tin["loss_mask"], tin["cu"], adv.reshape(-1), tin["seg_sample"],
+                            tin["old"], tin["rollout"], prm, ws, sample_keep=torch.from_numpy(keep).to(dev))
+    torch.cuda.synchronize()
+    _, A, _ = O.trloo_advantage(nin["rewards"], nin["valid"], 1.0)
+    ref = O.pg_loss_fwd_bwd(nin["H"], nin["W"], nin["y"], nin["loss_mask"], nin["cu"], A.reshape(-1)[nin["seg_sample"]],
+                            nin["old"], nin["rollout"], O.Params(mismatch_mode=2), seg_keep=keep[nin["seg_sample"]])
+    n_pad = (int(ref["counters"][0]) + 255) // 256 * 256
+    assert 0 < n_pad and 8 * n_pad <= (T + 255) // 256 * 256
+    _compare(out, ref)
+
+
 def test_loss_all_masked_and_all_rejected(dev):
     spec = synth.small_spec(d=64, V=600, seed=31)
     batch, tin, nin = build_loss_case(spec, dev, oracle_logp, "window", on_policy=False)
