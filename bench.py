@@ -41,6 +41,14 @@ def kernel_sources_digest() -> str:
     return h.hexdigest()
 
 
+def measured_traffic(kernel: str):
+    """L2<->fabric bytes per launch of the dominant kernel from the stored counter runs, or None when they
+    do not describe the kernel that is about to run (another kernel dominates, or the sources changed)."""
+    if kernel != "gemm_store_kernel" or kernel_sources_digest() != TRAFFIC_GEMM_STORE["sources_sha256"]:
+        return None
+    return TRAFFIC_GEMM_STORE["read_bytes"] + TRAFFIC_GEMM_STORE["write_bytes"]
+
+
 def cpu_baseline(spec, rows: int):
     """Times the fp64 oracle (as it stands) on `rows` active rows at the full d and V."""
     import numpy as np
@@ -309,9 +317,7 @@ def main():
     achieved = b["flop"] / (b["ms"] * 1e-3) / 1e12
     roofline = {"bound": "mfma", "kernel": dom, "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                 "frac": achieved / PEAK_BF16_TFLOPS,
-                "traffic": (TRAFFIC_GEMM_STORE["read_bytes"] + TRAFFIC_GEMM_STORE["write_bytes"]
-                            if dom == "gemm_store_kernel" and kernel_sources_digest() == TRAFFIC_GEMM_STORE["sources_sha256"]
-                            else None),
+                "traffic": measured_traffic(dom),
                 "flops_per_launch": b["flop"] / b["launches"], "avg_launch_ms": b["ms"] / b["launches"],
                 "launches_per_step": b["launches"]}
     executed = 8.0 * d * V * n_active / (ms_step * 1e-3) / 1e12   # logits twice, dH, dW
