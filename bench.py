@@ -164,10 +164,13 @@ def main():
     ap.add_argument("--mismatch-mode", type=int, default=2)
     ap.add_argument("--cpu-rows", type=int, default=2048, help="rows of the oracle's timed sample (0 = skip)")
     ap.add_argument("--scale-rows", type=float, default=1.0, help="shrink the packed microbatch (debugging)")
-    ap.add_argument("--workload", choices=["pg", "sft", "fwd", "shard"], default="pg",
+    ap.add_argument("--workload", choices=["pg", "sft", "fwd", "shard", "bwd"], default="pg",
                     help="pg: trloo_advantage + pg_loss_fwd_bwd (the headline); sft: pg_sft_fwd_bwd at the same shape; "
                          "fwd: pg_logprob_fwd over every row (the old-policy recompute); shard: one vocab shard's "
-                         "share of the step (pg_head_shard_fwd + pg_head_partials_merge + pg_loss_shard_bwd)")
+                         "share of the step (pg_head_shard_fwd + pg_head_partials_merge + pg_loss_shard_bwd); "
+                         "bwd: pg_loss_shard_bwd on the whole head from the softmax states the old-policy "
+                         "recompute left behind (valid while the weights are those of that recompute: the "
+                         "forward contraction is not repeated, 6dV instead of 8dV flops per token)")
     ap.add_argument("--vocab-shards", type=int, default=2, help="number of vocab shards for --workload shard")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="also run three plain device-to-device copies of this size (the known-size reference "
@@ -229,10 +232,16 @@ def main():
         V = Vs
         part = torch.empty((T, 4), dtype=torch.float32, device=dev)
         merged = torch.empty_like(part)
+    if args.workload == "bwd":
+        # the recompute stage, run once outside the timed region, keeps the rows' softmax states
+        wsk = B.alloc_workspace(T, d, V, 0, prm, B.CALL_LOGPROB_FWD, dev)
+        merged = B.pg_head_shard_fwd(H, W, y, loss_mask, 0, prm, wsk)
+        torch.cuda.synchronize()
+        del wsk
     ws = B.alloc_workspace(T, d, V, S, prm, B.CALL_LOSS_FWD_BWD, dev)
     dW = torch.empty((V, d), dtype=torch.float32, device=dev)
     outbuf = (torch.empty(1, dtype=torch.float32, device=dev),
-              torch.empty((T, d), dtype=torch.float32, device=dev) if args.workload == "shard" else torch.empty_like(H),
+              torch.empty((T, d), dtype=torch.float32, device=dev) if args.workload in ("shard", "bwd") else torch.empty_like(H),
               torch.empty(T, dtype=torch.float32, device=dev), torch.empty(T, dtype=torch.float32, device=dev),
               torch.empty(8, dtype=torch.int64, device=dev))
 
@@ -243,6 +252,9 @@ def main():
         if args.workload == "shard":
             B.pg_head_shard_fwd(H, W, y, loss_mask, 0, prm, ws, out=part)
             B.pg_head_partials_merge(part, others, out=merged)
+            return B.pg_loss_shard_bwd(H, W, y, loss_mask, cu, adv.reshape(-1), seg_sample, old_logp, rollout_logp,
+                                       merged, 0, prm, ws, dH_f32=True, dW=dW, out=outbuf)
+        if args.workload == "bwd":
             return B.pg_loss_shard_bwd(H, W, y, loss_mask, cu, adv.reshape(-1), seg_sample, old_logp, rollout_logp,
                                        merged, 0, prm, ws, dH_f32=True, dW=dW, out=outbuf)
         return B.pg_loss_fwd_bwd(H, W, y, loss_mask, cu, adv.reshape(-1), seg_sample, old_logp, rollout_logp, prm, ws,
@@ -320,17 +332,20 @@ def main():
                 "traffic": measured_traffic(dom),
                 "flops_per_launch": b["flop"] / b["launches"], "avg_launch_ms": b["ms"] / b["launches"],
                 "launches_per_step": b["launches"]}
-    executed = 8.0 * d * V * n_active / (ms_step * 1e-3) / 1e12   # logits twice, dH, dW
+    n_contractions = 3.0 if args.workload == "bwd" else 4.0       # logits (twice unless the forward is not repeated), dH, dW
+    executed = 2.0 * n_contractions * d * V * n_active / (ms_step * 1e-3) / 1e12
     useful = 6.0 * d * V * n_active / (ms_step * 1e-3) / 1e12
 
     cpu = cpu_baseline(spec, args.cpu_rows) if args.cpu_rows > 0 and args.workload == "pg" else None
     aux = (aux_stage_times(B, torch, dev, rewards, valid, out, loss_mask, old_logp, rollout_logp, dW, H)
-           if args.workload != "shard" else None)
+           if args.workload not in ("shard", "bwd") else None)
 
     line = {
         "metric": {"pg": "loss fwd+bwd tokens/sec at 14B shape (h5120,V151936); % bf16 MFMA peak",
                    "sft": "SFT cross-entropy fwd+bwd tokens/sec at 14B shape (h5120,V151936); % bf16 MFMA peak",
                    "shard": f"loss fwd+bwd tokens/sec of one of {args.vocab_shards} vocab shards of the head; % bf16 MFMA peak",
+                   "bwd": "loss + backward tokens/sec at 14B shape from the recompute stage's softmax states "
+                          "(forward contraction not repeated); % bf16 MFMA peak",
                    }[args.workload],
         "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_step, "ms_per_step_median": step_ms[len(step_ms) // 2] if step_ms else None,
@@ -343,10 +358,12 @@ def main():
                    "mismatch_mode": args.mismatch_mode, "temperature": spec.temperature,
                    "dW": "fp32 overwrite",
                    "step": {"pg": "trloo_advantage + pg_loss_fwd_bwd", "sft": "pg_sft_fwd_bwd",
-                            "shard": "trloo_advantage + pg_head_shard_fwd + pg_head_partials_merge + pg_loss_shard_bwd"
+                            "shard": "trloo_advantage + pg_head_shard_fwd + pg_head_partials_merge + pg_loss_shard_bwd",
+                            "bwd": "trloo_advantage + pg_loss_shard_bwd (states from pg_head_shard_fwd, outside the timed region)"
                             }[args.workload],
                    **({"vocab_shards": args.vocab_shards, "V_shard": V, "V": V_full} if args.workload == "shard" else {})},
-        "pct_mfma_peak_executed_8dV": 100.0 * executed / PEAK_BF16_TFLOPS,
+        "pct_mfma_peak_executed_8dV": 100.0 * executed / PEAK_BF16_TFLOPS,      # of 6dV for --workload bwd
+        "executed_contractions_per_token": n_contractions,
         "pct_mfma_peak_useful_6dV": 100.0 * useful / PEAK_BF16_TFLOPS,
         "loss": loss, "counters": {n: int(c) for n, c in zip(B.COUNTER_NAMES, counters)},
         "kernels": kern, "roofline": roofline, "cpu_baseline": cpu, "aux_stages_us": aux,      # per call; the *_GBps entries are algorithmic bytes / time
