@@ -20,7 +20,7 @@
  *   prs_retain        profiling-based rejection sampling               (Sec. 5.2, Eq. 8)
  *   pg_monitors       entropy, perplexities and gradient norms         (Sec. 5.1)
  *   pg_rmsnorm_fwd/bwd  the RMS normalisation in front of the head in the Qwen3 policies of Sec. 6.1
- *   pg_head_shard_fwd, pg_head_partials_merge, pg_loss_shard_bwd
+ *   pg_head_shard_fwd, pg_head_partials_merge, pg_head_partials_finish, pg_loss_shard_bwd
  *                     pg_logprob_fwd / pg_loss_fwd_bwd with the head's vocabulary rows split over
  *                     devices: one device's share of the work and the reduction operator of the exchange
  *
@@ -283,6 +283,10 @@ int32_t pg_rmsnorm_bwd(const void* X, const void* gamma, const void* dH, int64_t
  * other.  out may alias a or b.  From the merged state: logsumexp = m + ln s,
  * log-prob = z_y - logsumexp, entropy = ln s - u / s.
  *
+ * pg_head_partials_finish: those three per row from a merged state, logp_out [T] (required),
+ * entropy_out and lse_out [T] (nullable); rows with the empty state give 0.  With it the
+ * forward-only recompute of pg_logprob_fwd runs on a sharded head: shard_fwd, exchange, finish.
+ *
  * pg_loss_shard_bwd: arguments, loss, counters, logp_out and entropy_out as pg_loss_fwd_bwd, except
  * that the forward contraction is not run: the rows' log-prob, entropy and logsumexp are taken
  * from `partials` ([T][4], the state merged over ALL shards; read on active rows only).  Writes
@@ -297,6 +301,8 @@ int32_t pg_head_shard_fwd(const void* H, const void* W_shard, const int32_t* y, 
                           int64_t d, int64_t V_shard, int64_t v_offset, const pg_params* h_params, float* partials_out,
                           void* workspace, size_t workspace_bytes, void* stream);
 int32_t pg_head_partials_merge(const float* a, const float* b, float* out, int64_t T, void* stream);
+int32_t pg_head_partials_finish(const float* partials, int64_t T, float* logp_out, float* entropy_out, float* lse_out,
+                                void* stream);
 int32_t pg_loss_shard_bwd(const void* H, const void* W_shard, const int32_t* y, const uint8_t* loss_mask,
                           const int32_t* cu_seqlens, int32_t S, const double* adv, const int32_t* seg_sample,
                           const uint8_t* sample_keep, const float* old_logp, const float* rollout_logp,

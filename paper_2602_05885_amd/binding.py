@@ -22,7 +22,7 @@ CALL_LOSS_FWD_BWD = 1
 COUNTER_NAMES = ("active", "clip_hi", "clip_lo", "seg_geo", "seg_veto", "truncated", "loss_tokens", "seg_dropped")
 
 EXPORTS = ("pg_last_error", "pg_workspace_bytes", "trloo_advantage", "pg_logprob_fwd", "pg_loss_fwd_bwd",
-           "pg_sft_fwd_bwd", "pg_head_shard_fwd", "pg_head_partials_merge", "pg_loss_shard_bwd", "grpo_advantage",
+           "pg_sft_fwd_bwd", "pg_head_shard_fwd", "pg_head_partials_merge", "pg_head_partials_finish", "pg_loss_shard_bwd", "grpo_advantage",
            "turn_reward", "prs_retain", "pg_monitors_workspace_bytes", "pg_monitors", "pg_rmsnorm_fwd", "pg_rmsnorm_bwd_workspace_bytes", "pg_rmsnorm_bwd",
            "pg_profile_enable", "pg_profile_read")
 MONITOR_NAMES = ("entropy_mean", "ppl_train", "ppl_rollout", "dH_norm", "dW_norm", "n")
@@ -99,6 +99,8 @@ def lib() -> C.CDLL:
                                         C.c_int64, C.POINTER(PgParams), C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
         L.pg_head_partials_merge.restype = C.c_int32
         L.pg_head_partials_merge.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
+        L.pg_head_partials_finish.restype = C.c_int32
+        L.pg_head_partials_finish.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         L.pg_loss_shard_bwd.restype = C.c_int32
         L.pg_loss_shard_bwd.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
                                         C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64,
@@ -343,6 +345,15 @@ def pg_head_partials_merge(a, b, out=None, stream=None):
     out = torch.empty_like(a) if out is None else out
     _check(lib().pg_head_partials_merge(_ptr(a), _ptr(b), _ptr(out), a.shape[0], _stream(stream)))
     return out
+
+
+def pg_head_partials_finish(partials, want_entropy=True, want_lse=True, stream=None):
+    """(logp, entropy | None, lse | None), each [T] f32, from states merged over the whole vocabulary."""
+    T = partials.shape[0]
+    mk = lambda: torch.empty(T, dtype=torch.float32, device=partials.device)
+    logp, ent, lse = mk(), (mk() if want_entropy else None), (mk() if want_lse else None)
+    _check(lib().pg_head_partials_finish(_ptr(partials), T, _ptr(logp), _ptr(ent), _ptr(lse), _stream(stream)))
+    return logp, ent, lse
 
 
 def pg_loss_shard_bwd(H, W_shard, y, loss_mask, cu_seqlens, adv, seg_sample, old_logp, rollout_logp, partials,

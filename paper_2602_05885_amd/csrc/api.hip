@@ -402,6 +402,16 @@ int32_t pg_head_partials_merge(const float* a, const float* b, float* out, int64
   return check_launches("pg_head_partials_merge");
 }
 
+int32_t pg_head_partials_finish(const float* partials, int64_t T, float* logp_out, float* entropy_out, float* lse_out,
+                                void* stream) {
+  if (T < 0) return fail(PG_ERR_INVALID_ARG, "T must be >= 0");
+  if (T == 0) return PG_OK;
+  if (!partials || !logp_out) return fail(PG_ERR_INVALID_ARG, "partials and logp_out must not be NULL");
+  if (misaligned(partials)) return fail(PG_ERR_INVALID_ARG, "partials must be 16-byte aligned");
+  pg::launch_finish_partials(partials, T, logp_out, entropy_out, lse_out, static_cast<hipStream_t>(stream));
+  return check_launches("pg_head_partials_finish");
+}
+
 int32_t pg_loss_shard_bwd(const void* H, const void* W_shard, const int32_t* y, const uint8_t* loss_mask,
                           const int32_t* cu_seqlens, int32_t S, const double* adv, const int32_t* seg_sample,
                           const uint8_t* sample_keep, const float* old_logp, const float* rollout_logp,

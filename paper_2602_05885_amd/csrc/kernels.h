@@ -179,6 +179,8 @@ void launch_scatter_dh(const ScatterArgs& a, hipStream_t s);
 
 // out[t] = merge(a[t], b[t]) of two per-row softmax states (m, s, u, z_y), [T][4] each.
 void launch_merge_partials(const float* a, const float* b, float* out, long long T, hipStream_t s);
+// logsumexp = m + ln s, log-prob = z_y - logsumexp, entropy = ln s - u / s per row; 0 on empty rows.
+void launch_finish_partials(const float* parts, long long T, float* logp, float* ent, float* lse, hipStream_t s);
 
 // ---- stages around the path -------------------------------------------------------------
 struct RewardArgs {

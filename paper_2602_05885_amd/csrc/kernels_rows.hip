@@ -509,6 +509,26 @@ void launch_merge_partials(const float* a, const float* b, float* out, long long
   hipLaunchKernelGGL(merge_partials_kernel, dim3((unsigned)((T + 255) / 256)), dim3(256), 0, s, a, b, out, T);
 }
 
+__global__ void finish_partials_kernel(const float* parts, long long T, float* logp, float* ent, float* lse) {
+  const long long t = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (t >= T) return;
+  const float4 p = *reinterpret_cast<const float4*>(parts + t * 4);
+  float lp = 0.f, en = 0.f, ls = 0.f;
+  if (p.y != 0.f) {
+    const float lns = logf(p.y);
+    ls = p.x + lns;
+    lp = p.w - ls;
+    en = lns - p.z / p.y;
+  }
+  if (logp) logp[t] = lp;
+  if (ent) ent[t] = en;
+  if (lse) lse[t] = ls;
+}
+void launch_finish_partials(const float* parts, long long T, float* logp, float* ent, float* lse, hipStream_t s) {
+  if (T <= 0) return;
+  hipLaunchKernelGGL(finish_partials_kernel, dim3((unsigned)((T + 255) / 256)), dim3(256), 0, s, parts, T, logp, ent, lse);
+}
+
 void launch_scatter_dh(const ScatterArgs& a, hipStream_t s) {
   if (a.T <= 0) return;
   hipLaunchKernelGGL(scatter_dh_kernel, dim3(a.T), dim3(256), 0, s, a);

@@ -28,6 +28,7 @@ int main() {
   p.mismatch_mode = 0;
   EXPECT(pg_head_shard_fwd(one, one, (const int32_t*)one, nullptr, 8, 64, 100, -1, &p, (float*)one, one, big, nullptr), PG_ERR_INVALID_ARG);
   EXPECT(pg_head_partials_merge((const float*)one, nullptr, (float*)one, 4, nullptr), PG_ERR_INVALID_ARG);
+  EXPECT(pg_head_partials_finish(nullptr, 4, (float*)one, nullptr, nullptr, nullptr), PG_ERR_INVALID_ARG);
   EXPECT(pg_loss_shard_bwd(one, one, (const int32_t*)one, (const uint8_t*)one, (const int32_t*)one, 1, (const double*)one, nullptr, nullptr, nullptr, nullptr, nullptr, 8, 64, 100, 0, &p, (float*)one, one, 1, one, nullptr, nullptr, nullptr, one, big, nullptr), PG_ERR_INVALID_ARG);
   EXPECT(turn_reward((const uint8_t*)one, (const float*)one, (const float*)one, (const float*)one, nullptr, 4, 3.f, (float*)one, nullptr, nullptr), PG_ERR_INVALID_ARG);
   EXPECT(prs_retain((const float*)one, nullptr, 4, 0.3f, 0.f, 0, 1, (uint8_t*)one, nullptr, nullptr), PG_ERR_INVALID_ARG);

@@ -133,6 +133,10 @@ def test_shard_entry_points_validate_arguments():
     assert lib.pg_head_partials_merge(one, C.c_void_p(4), one, 4, None) == -1 and "aligned" in B.pg_last_error()
     assert lib.pg_head_partials_merge(one, one, one, -1, None) == -1
     assert lib.pg_head_partials_merge(None, None, None, 0, None) == 0
+    assert lib.pg_head_partials_finish(None, 4, one, None, None, None) == -1
+    assert lib.pg_head_partials_finish(one, 4, None, None, None, None) == -1
+    assert lib.pg_head_partials_finish(C.c_void_p(4), 4, one, None, None, None) == -1
+    assert lib.pg_head_partials_finish(None, 0, None, None, None, None) == 0
     args = lambda partials, voff, f32, ws: (one, one, one, one, one, 1, one, None, None, None, None, partials, 8, 64, 100, voff,
                                             C.byref(p), one, one, f32, one, None, None, None, one, ws, None)
     assert lib.pg_loss_shard_bwd(*args(None, 0, 1, big)) == -1 and "partials" in B.pg_last_error()

@@ -74,6 +74,12 @@ def test_shard_forward_states_and_merge(dev, T, d, V, dtype, tau, cuts, mask_fra
             torch.cuda.synchronize()
             _check_partials(ref_dev.cpu().numpy().astype(np.float64), ref_merged, 1e-5)
     logp, ent, lse = O.finish_shard_partials(merged.cpu().numpy())
+    g_logp, g_ent, g_lse = B.pg_head_partials_finish(merged)                  # the same step on the device
+    torch.cuda.synchronize()
+    for g, r in ((g_logp, logp), (g_ent, ent), (g_lse, lse)):
+        assert np.abs(g.cpu().numpy() - r).max() <= 1e-5 and not g[torch.from_numpy(mask == 0).to(dev)].any()
+    only_logp = B.pg_head_partials_finish(merged, want_entropy=False, want_lse=False)
+    assert only_logp[1] is None and only_logp[2] is None and torch.equal(only_logp[0], g_logp)
     rl, re, rs = O.lm_head_logprob(Hn, Wn, yn, tau, mask)
     assert np.abs(logp - rl).max() <= tol and np.abs(ent - re).max() <= tol and np.abs(lse - rs).max() <= tol
     # and the unsharded call gives the same numbers
