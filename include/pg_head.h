@@ -38,8 +38,9 @@
  *   - H is [T,d] row-major, W is [V,d] row-major (LM-head weight, no bias), y[t] is
  *     the token whose log-prob row t predicts (the caller has already shifted).
  *     dtype 0: H, W, dH are bf16 (fp32 accumulation); dtype 1: H, W, dH are fp32.
- *   - Shapes: d must be a multiple of 64, 1 <= d, 1 <= V, 0 <= T; each operand and
- *     each scratch matrix must stay below 4 GiB; otherwise PG_ERR_UNSUPPORTED_SHAPE.
+ *   - Shapes: d must be a multiple of 64, 1 <= d, 1 <= V <= 2^30, 0 <= T < 2^23, and 256 rows of
+ *     any operand (256 x d, x 3 for fp32 inputs) must stay below 4 GiB; otherwise
+ *     PG_ERR_UNSUPPORTED_SHAPE.  Operands as a whole may be of any size.
  *     H, W, dH, dW and workspace must be 16-byte aligned.
  *   - y[t] outside [0,V) on an active row is not detected: that row's log-prob is
  *     then -logsumexp and its gradient has no one-hot term.  No memory is addressed

@@ -93,8 +93,9 @@ int32_t make_plan(int64_t T, int64_t d, int64_t V, int32_t S, const pg_params* p
   const int64_t t_cap = (T + 255) / 256 * 256;
   const int64_t kd = pl.is_f32 ? 3 * d : d;
   const int64_t tiles_v = (V + 255) / 256;
-  if ((uint64_t)V * kd * 2 >= FOUR_GIB) return fail(PG_ERR_UNSUPPORTED_SHAPE, "head weight operand reaches 4 GiB");
-  if ((uint64_t)t_cap * kd * 2 >= FOUR_GIB) return fail(PG_ERR_UNSUPPORTED_SHAPE, "hidden-state operand reaches 4 GiB");
+  // a tile's 256 operand rows are addressed through one 32-bit buffer range
+  if ((uint64_t)kd * 2 * 256 >= FOUR_GIB) return fail(PG_ERR_UNSUPPORTED_SHAPE, "d=%lld: 256 operand rows reach 4 GiB", (long long)d);
+  if ((uint64_t)(t_cap + 64) * 2 * 256 >= FOUR_GIB) return fail(PG_ERR_UNSUPPORTED_SHAPE, "T=%lld: 256 rows of a [*, T] scratch matrix reach 4 GiB", (long long)T);
   pl.t_cap = (int)t_cap; pl.kd = (int)kd; pl.tiles_v = (int)tiles_v; pl.tiles_t = (int)(t_cap / 256);
 
   size_t off = 0;
@@ -137,9 +138,8 @@ int32_t make_plan(int64_t T, int64_t d, int64_t V, int32_t S, const pg_params* p
     const int64_t nchunks = (tiles_v + chunk_tiles - 1) / chunk_tiles;
     const int64_t vc = chunk_tiles * 256;
     const int64_t ld_v = pad_ld(vc), ld_t = pad_ld(t_cap);
-    if ((uint64_t)t_cap * ld_v * 2 >= FOUR_GIB || (uint64_t)d * ld_v * 2 >= FOUR_GIB ||
-        (uint64_t)d * ld_t * 2 >= FOUR_GIB || (uint64_t)vc * ld_t * 2 >= FOUR_GIB)
-      return fail(PG_ERR_UNSUPPORTED_SHAPE, "a backward scratch matrix reaches 4 GiB");
+    if ((uint64_t)ld_v * 2 * 256 >= FOUR_GIB || (uint64_t)ld_t * 2 * 256 >= FOUR_GIB)
+      return fail(PG_ERR_UNSUPPORTED_SHAPE, "256 rows of a backward scratch matrix reach 4 GiB");
     pl.nchunks = (int)nchunks; pl.chunk_tiles = (int)chunk_tiles; pl.vc = (int)vc;
     pl.ld_v = (int)ld_v; pl.ld_t = (int)ld_t;
     pl.HcT = take((size_t)d * ld_t * 2);
@@ -224,7 +224,7 @@ void run_forward(const Plan& pl, const pg_params& p, void* ws, const void* H, co
 
   pg::FwdArgs f{};
   f.W = Wop; f.Hc = at<__bf16>(ws, pl.Hc);
-  f.w_bytes = (uint32_t)((uint64_t)pl.V * pl.kd * 2); f.h_bytes = (uint32_t)((uint64_t)pl.t_cap * pl.kd * 2);
+  f.w_rows = (int)pl.V; f.h_rows = pl.t_cap;
   f.ldw = pl.kd; f.ldh = pl.kd; f.K = pl.kd; f.V = (int)pl.V;
   f.tiles_v = pl.tiles_v; f.tiles_t = pl.tiles_t; f.t_cap = pl.t_cap;
   f.scale = (float)(LOG2E / (double)p.temperature);
@@ -600,7 +600,7 @@ int32_t loss_fwd_bwd(int sft, const void* H, const void* W, const int32_t* y, co
 
     pg::DlogitsArgs g{};
     g.W = Wop; g.Hc = at<__bf16>(ws, pl.Hc);
-    g.w_bytes = (uint32_t)((uint64_t)pl.V * pl.kd * 2); g.h_bytes = (uint32_t)((uint64_t)pl.t_cap * pl.kd * 2);
+    g.w_rows = (int)pl.V; g.h_rows = pl.t_cap;
     g.ldw = pl.kd; g.ldh = pl.kd; g.K = pl.kd; g.V = (int)pl.V; g.v0 = v0; g.ld_s = pl.ld_v; g.ld_t = pl.ld_t;
     g.tiles_v = tiles_c; g.tiles_t = pl.tiles_t; g.t_cap = pl.t_cap;
     g.scale = (float)(LOG2E / (double)p.temperature);
@@ -610,7 +610,7 @@ int32_t loss_fwd_bwd(int sft, const void* H, const void* W, const int32_t* y, co
 
     pg::StoreArgs w{};   // dW[v0 + m, :] = sum_t dS^T[m, t] H^T[:, t]
     w.A = at<__bf16>(ws, pl.dST); w.B = at<__bf16>(ws, pl.HcT);
-    w.a_bytes = (uint32_t)((uint64_t)pl.vc * pl.ld_t * 2); w.b_bytes = (uint32_t)((uint64_t)pl.d * pl.ld_t * 2);
+    w.a_rows = pl.vc; w.b_rows = d_i;
     w.lda = pl.ld_t; w.ldb = pl.ld_t; w.M = rows_valid; w.N = d_i; w.K = pl.t_cap;
     w.tiles_m = tiles_c; w.tiles_n = (d_i + 255) / 256;
     w.C = static_cast<char*>(dW) + (size_t)v0 * pl.d * dw_elem; w.ldc = d_i;
@@ -619,7 +619,7 @@ int32_t loss_fwd_bwd(int sft, const void* H, const void* W, const int32_t* y, co
 
     pg::StoreArgs h{};   // dHacc[t, :] (+)= sum_v dS[t, v] W^T[:, v]
     h.A = at<__bf16>(ws, pl.dS); h.B = at<__bf16>(ws, pl.WT);
-    h.a_bytes = (uint32_t)((uint64_t)pl.t_cap * pl.ld_v * 2); h.b_bytes = (uint32_t)((uint64_t)pl.d * pl.ld_v * 2);
+    h.a_rows = pl.t_cap; h.b_rows = d_i;
     h.lda = pl.ld_v; h.ldb = pl.ld_v; h.M = pl.t_cap; h.N = d_i; h.K = kc;
     h.tiles_m = pl.tiles_t; h.tiles_n = (d_i + 255) / 256;
     h.C = at<float>(ws, pl.dHacc); h.ldc = d_i;

@@ -156,6 +156,7 @@ __host__ __device__ inline int dh_split(int n_pad, int t_cap, int tiles_n, int k
 // One wavefront load instruction fills 1024 contiguous LDS bytes (8 rows); lane l lands at row
 // l/8, position l%8, so it fetches the logical chunk (l%8) ^ ((row>>1)&7) of that row.
 // Loads beyond the buffer resource's size return 0, which pads ragged tiles.
+static_assert(BM == BN, "one loader serves both operands");
 struct TileLoader {
   const void* base;
   uint32_t bytes;
@@ -168,15 +169,25 @@ struct TileLoader {
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, on ? bytes : 0u, 0x00020000);
   }
 
-  __device__ __forceinline__ void init(const void* base_, uint32_t num_bytes, int row0, int ld_elems, int tid) {
-    base = base_;
-    bytes = num_bytes;
+  // The resource covers only the (up to) 256 rows of this tile, from byte k_byte0 of its first
+  // row to the end of its last existing row, so operands of any size can be addressed (a
+  // resource's range and the lane offsets are 32-bit) and rows beyond rows_total read as 0.
+  __device__ __forceinline__ void init(const void* base_, int rows_total, int row0, int ld_elems, uint32_t k_byte0,
+                                       int tid) {
+    const int rows = min(max(rows_total - row0, 0), BM);
+    const uint64_t b = reinterpret_cast<uint64_t>(base_) + (uint64_t)row0 * (uint64_t)ld_elems * 2u + k_byte0;
+    // the tile index is the same for the whole workgroup: keep the resource in scalar registers
+    // (left to itself the compiler treats it as per-lane and loops over every load)
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)b);
+    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(b >> 32));
+    base = reinterpret_cast<const void*>(((uint64_t)hi << 32) | lo);
+    bytes = __builtin_amdgcn_readfirstlane(rows > 0 ? (uint32_t)rows * (uint32_t)ld_elems * 2u - k_byte0 : 0u);
     const int lane = tid & 63, wave = tid >> 6;
 #pragma unroll
     for (int i = 0; i < CHUNKS; ++i) {
       const int row = (i * NW + wave) * 8 + (lane >> 3);
       const int chunk = (lane & 7) ^ ((row >> 1) & 7);
-      voff[i] = (uint32_t)(row0 + row) * (uint32_t)ld_elems * 2u + (uint32_t)chunk * 16u;
+      voff[i] = (uint32_t)row * (uint32_t)ld_elems * 2u + (uint32_t)chunk * 16u;
     }
   }
 

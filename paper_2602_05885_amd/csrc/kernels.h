@@ -11,7 +11,7 @@ struct Ctl;
 struct FwdArgs {
   const void* W;        // [V, ldw] bf16
   const void* Hc;       // [t_cap, ldh] bf16, compacted rows, zero padded
-  uint32_t w_bytes, h_bytes;
+  int w_rows, h_rows;   // rows that exist in W / Hc (loads beyond them give 0)
   int ldw, ldh;         // elements
   int K;                // contraction length (multiple of 64)
   int V;
@@ -29,7 +29,7 @@ struct FwdArgs {
 struct DlogitsArgs {
   const void* W;
   const void* Hc;
-  uint32_t w_bytes, h_bytes;
+  int w_rows, h_rows;   // rows that exist in W / Hc (loads beyond them give 0)
   int ldw, ldh;
   int K;
   int V;
@@ -50,7 +50,7 @@ struct DlogitsArgs {
 struct StoreArgs {
   const void* A;        // [M, lda] bf16
   const void* B;        // [N, ldb] bf16
-  uint32_t a_bytes, b_bytes;
+  int a_rows, b_rows;   // rows that exist in A / B (loads beyond them give 0)
   int lda, ldb;
   int M, N, K;
   int tiles_m, tiles_n;

@@ -43,8 +43,8 @@ __global__ __launch_bounds__(NTHREADS) void lmhead_fwd_kernel(FwdArgs a) {
   const int wm = wave / WN, wn = wave % WN;
 
   TileLoader LA, LB;
-  LA.init(a.W, a.w_bytes, tm * BM, a.ldw, tid);
-  LB.init(a.Hc, a.h_bytes, tn * BN, a.ldh, tid);
+  LA.init(a.W, a.w_rows, tm * BM, a.ldw, 0u, tid);
+  LB.init(a.Hc, a.h_rows, tn * BN, a.ldh, 0u, tid);
   f32x4 acc[GM][GN];
   zero_acc(acc);
   mainloop(LA, LB, a.K / BK, g_smem, acc);
@@ -133,8 +133,8 @@ __global__ __launch_bounds__(NTHREADS) void lmhead_dlogits_kernel(DlogitsArgs a)
   const int wm = wave / WN, wn = wave % WN;
 
   TileLoader LA, LB;
-  LA.init(a.W, a.w_bytes, a.v0 + tm * BM, a.ldw, tid);
-  LB.init(a.Hc, a.h_bytes, tn * BN, a.ldh, tid);
+  LA.init(a.W, a.w_rows, a.v0 + tm * BM, a.ldw, 0u, tid);
+  LB.init(a.Hc, a.h_rows, tn * BN, a.ldh, 0u, tid);
   f32x4 acc[GM][GN];
   zero_acc(acc);
   mainloop(LA, LB, a.K / BK, g_smem, acc);
@@ -305,8 +305,8 @@ __global__ __launch_bounds__(NTHREADS) void gemm_store_kernel(StoreArgs a) {
 
   const int tid = threadIdx.x;
   TileLoader LA, LB;
-  LA.init(static_cast<const char*>(a.B) + kb, a.b_bytes - kb, tn * BN, a.ldb, tid);     // engine rows <- n
-  LB.init(static_cast<const char*>(a.A) + kb, a.a_bytes - kb, tm * BM, a.lda, tid);     // engine columns <- m
+  LA.init(a.B, a.b_rows, tn * BN, a.ldb, kb, tid);     // engine rows <- n
+  LB.init(a.A, a.a_rows, tm * BM, a.lda, kb, tid);     // engine columns <- m
   f32x4 acc[GM][GN];
   zero_acc(acc);
   mainloop(LA, LB, s1 - s0, g_smem, acc);

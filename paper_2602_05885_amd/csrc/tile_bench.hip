@@ -34,8 +34,8 @@ __global__ __launch_bounds__(NTHREADS) void tile_kernel(const __bf16* A, const _
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WN, wn = wave % WN;
   TileLoader LA, LB;
-  LA.init(A, (uint32_t)((size_t)M * K * 2), tm * BM, K, tid);
-  LB.init(B, (uint32_t)((size_t)N * K * 2), tn * BN, K, tid);
+  LA.init(A, M, tm * BM, K, 0u, tid);
+  LB.init(B, N, tn * BN, K, 0u, tid);
   f32x4 acc[GM][GN];
   zero_acc(acc);
   mainloop(LA, LB, K / BK, g_smem, acc);

@@ -45,7 +45,10 @@ def test_workspace_query_and_shape_errors():
     assert B.pg_workspace_bytes(-1, 64, 1000, 1, P, 1) == 0
     assert B.pg_workspace_bytes(1024, 64, 1000, 1, B.Params(temperature=0.0), 1) == 0
     assert B.pg_workspace_bytes(1024, 64, 1000, 1, B.Params(mismatch_mode=7), 1) == 0
-    assert B.pg_workspace_bytes(1 << 20, 5120, 151936, 1, P, 0) == 0 and "4 GiB" in B.pg_last_error()
+    assert B.pg_workspace_bytes(1 << 20, 5120, 151936, 1, P, 0) > 8 << 30      # operands beyond 4 GiB are fine
+    assert B.pg_workspace_bytes(2048, 5120, 151936, 0, B.Params(dtype=1), 1) > 4 << 30  # fp32 head: 4.7 GB split operand
+    assert B.pg_workspace_bytes(1 << 23, 64, 1000, 1, P, 0) == 0 and "4 GiB" in B.pg_last_error()
+    assert B.pg_workspace_bytes(8, 1 << 23, 1000, 0, P, 1) == 0 and "4 GiB" in B.pg_last_error()
     assert B.pg_workspace_bytes(1024, 64, 1000, 1, P, 5) == 0
     assert B.pg_workspace_bytes(0, 64, 1000, 0, P, 1) > 0          # empty microbatch is legal
 

@@ -157,3 +157,40 @@ def test_config4_forward_only_128k(dev):
     torch.cuda.synchronize()
     G, A, N = O.trloo_advantage(batch.rewards, batch.valid, 1.0)
     assert np.abs(adv.cpu().numpy() - A).max() <= 1e-6 and np.array_equal(gn.cpu().numpy(), N)
+
+
+def test_f32_head_at_full_vocabulary_operand_beyond_4_gib(dev):
+    """fp32 H and W at the 14B head shape: the split weight operand is [151936, 3 x 5120] bf16 = 4.7 GB, beyond
+    what one 32-bit buffer range covers, so every tile's resource must start at its own rows.  Target tokens
+    are placed in the vocabulary rows beyond the 4 GiB mark; log-prob, entropy and logsumexp against the
+    oracle on sampled rows (fp32 inputs: 2e-4), dH rows and dW rows of a small loss call likewise."""
+    T, d, V = 1000, 5120, 151936
+    H, W, y = synth.make_head(T, d, V, "f32", 4242, dev, unit_rms=True, w_std=0.02)
+    first_beyond = (1 << 32) // (3 * d * 2) + 1
+    y[::2] = torch.randint(first_beyond, V, (len(y[::2]),), generator=torch.Generator().manual_seed(1)).to(dev).to(y.dtype)
+    prm = B.Params(dtype=1)
+    ws = B.alloc_workspace(T, d, V, 1, prm, B.CALL_LOSS_FWD_BWD, dev)
+    logp, ent, lse = B.pg_logprob_fwd(H, W, y, None, prm, ws)
+    torch.cuda.synchronize()
+    rows = np.sort(np.random.default_rng(3).choice(T, 24, replace=False))
+    rt = torch.from_numpy(rows).to(dev)
+    Wn, yn = np64(W), y.cpu().numpy().astype(np.int64)
+    assert (yn[rows] >= first_beyond).any()
+    o_logp, o_ent, o_lse = O.lm_head_logprob(np64(H[rt]), Wn, yn[rows], 1.0)
+    assert np.abs(logp.cpu().numpy()[rows] - o_logp).max() <= 2e-4
+    assert np.abs(ent.cpu().numpy()[rows] - o_ent).max() <= 2e-4
+    assert np.abs(lse.cpu().numpy()[rows] - o_lse).max() <= 2e-4
+    lib_logp, _ = library_logp_lse(H, W, y, 1.0)
+    assert float((logp - lib_logp).abs().max()) <= 2e-4
+    # backward through the same operand: SFT loss on all rows, sampled dH rows and dW rows beyond the mark
+    out = B.pg_sft_fwd_bwd(H, W, y, torch.ones(T, dtype=torch.uint8, device=dev), prm, ws)
+    torch.cuda.synchronize()
+    ref_dH = O.dH_rows(np64(H[rt]), Wn, yn[rows], np.full(len(rows), -1.0 / T), 1.0)
+    assert rel_fro(np64(out["dH"][rt]), ref_dH) <= 1e-2
+    vs = np.unique(np.concatenate([yn[::2][:6], [V - 1, first_beyond, 0]]))
+    Hn = np64(H)
+    z = Hn @ Wn[vs].T
+    lse_rows = (torch.logsumexp(H.double() @ W.double().T, dim=1)).cpu().numpy()
+    k = -1.0 / T
+    dS = -np.exp(z - lse_rows[:, None]) * k + (yn[:, None] == vs[None, :]) * k
+    assert rel_fro(np64(out["dW"][torch.from_numpy(vs).to(dev)]), dS.T @ Hn) <= 1e-2
