@@ -28,8 +28,8 @@ PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA peak (published)
 # summarised in profiles/gemm_store_kernel_hbm_traffic.md (mean over a step's 14 launches, each
 # counter scaled by what it reads for a plain 1 GiB copy).  Valid only for the kernel sources the
 # counters were taken with: the digest below is of csrc/gemm_core.h + csrc/kernels_gemm.hip.
-TRAFFIC_GEMM_STORE = {"read_bytes": 5947045.7 * 1024 * 2.000, "write_bytes": 547137.1 * 1024 * 1.000,
-                      "sources_sha256": "e145dc6a346b2aded2e2b468811626a004b203fe25dd513242a6a1862b0fb71a"}
+TRAFFIC_GEMM_STORE = {"read_bytes": 5809541.3 * 1024 * 2.000, "write_bytes": 546686.7 * 1024 * 1.000,
+                      "sources_sha256": "4511f895c12052294df0c3fb8fba4b464cfb0dc2089a31cb5e3bc10dd45b897a"}
 
 
 def kernel_sources_digest() -> str:
