@@ -169,10 +169,9 @@ int32_t pg_logprob_fwd(const void* H, const void* W, const int32_t* y, const uin
 int32_t pg_loss_fwd_bwd(const void* H, const void* W, const int32_t* y, const uint8_t* loss_mask,
                         const int32_t* cu_seqlens, int32_t S, const double* adv,
                         const int32_t* seg_sample, const uint8_t* sample_keep, const float* old_logp,
-                        const float* rollout_logp,
-                        int64_t T, int64_t d, int64_t V, const pg_params* h_params, float* loss_out,
-                        void* dH, void* dW, float* logp_out, float* entropy_out, int64_t* counters_out,
-                        void* workspace, size_t workspace_bytes, void* stream);
+                        const float* rollout_logp, int64_t T, int64_t d, int64_t V, const pg_params* h_params,
+                        float* loss_out, void* dH, void* dW, float* logp_out, float* entropy_out,
+                        int64_t* counters_out, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * Cold-start SFT (Sec. 3.3): token-mean cross-entropy of the head over the rows with

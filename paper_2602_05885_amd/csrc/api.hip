@@ -276,10 +276,9 @@ struct Shard {
 int32_t loss_fwd_bwd(int sft, const void* H, const void* W, const int32_t* y, const uint8_t* loss_mask,
                      const int32_t* cu_seqlens, int32_t S, const double* adv, const int32_t* seg_sample,
                      const uint8_t* sample_keep, const float* old_logp, const float* rollout_logp, int64_t T, int64_t d,
-                     int64_t V,
-                     const pg_params* h_params, float* loss_out, void* dH, void* dW, float* logp_out,
-                     float* entropy_out, int64_t* counters_out, void* workspace, size_t workspace_bytes,
-                     void* stream, const Shard& shard);
+                     int64_t V, const pg_params* h_params, float* loss_out, void* dH, void* dW, float* logp_out,
+                     float* entropy_out, int64_t* counters_out, void* workspace, size_t workspace_bytes, void* stream,
+                     const Shard& shard);
 
 }  // namespace
 
@@ -358,10 +357,9 @@ int32_t pg_logprob_fwd(const void* H, const void* W, const int32_t* y, const uin
 int32_t pg_loss_fwd_bwd(const void* H, const void* W, const int32_t* y, const uint8_t* loss_mask,
                         const int32_t* cu_seqlens, int32_t S, const double* adv, const int32_t* seg_sample,
                         const uint8_t* sample_keep, const float* old_logp, const float* rollout_logp, int64_t T,
-                        int64_t d, int64_t V,
-                        const pg_params* h_params, float* loss_out, void* dH, void* dW, float* logp_out,
-                        float* entropy_out, int64_t* counters_out, void* workspace, size_t workspace_bytes,
-                        void* stream) {
+                        int64_t d, int64_t V, const pg_params* h_params, float* loss_out, void* dH, void* dW,
+                        float* logp_out, float* entropy_out, int64_t* counters_out, void* workspace,
+                        size_t workspace_bytes, void* stream) {
   return loss_fwd_bwd(0, H, W, y, loss_mask, cu_seqlens, S, adv, seg_sample, sample_keep, old_logp, rollout_logp, T, d, V,
                       h_params, loss_out, dH, dW, logp_out, entropy_out, counters_out, workspace, workspace_bytes, stream,
                       Shard{});
@@ -532,10 +530,9 @@ namespace {
 int32_t loss_fwd_bwd(int sft, const void* H, const void* W, const int32_t* y, const uint8_t* loss_mask,
                      const int32_t* cu_seqlens, int32_t S, const double* adv, const int32_t* seg_sample,
                      const uint8_t* sample_keep, const float* old_logp, const float* rollout_logp, int64_t T, int64_t d,
-                     int64_t V,
-                     const pg_params* h_params, float* loss_out, void* dH, void* dW, float* logp_out,
-                     float* entropy_out, int64_t* counters_out, void* workspace, size_t workspace_bytes,
-                     void* stream, const Shard& shard) {
+                     int64_t V, const pg_params* h_params, float* loss_out, void* dH, void* dW, float* logp_out,
+                     float* entropy_out, int64_t* counters_out, void* workspace, size_t workspace_bytes, void* stream,
+                     const Shard& shard) {
   Plan pl;
   int32_t rc = make_plan(T, d, V, S, h_params, PG_CALL_LOSS_FWD_BWD, pl);
   if (rc) return rc;
