@@ -367,6 +367,7 @@ def main():
                             "bwd": "trloo_advantage + pg_loss_shard_bwd (states from pg_head_shard_fwd, outside the timed region)"
                             }[args.workload],
                    **({"vocab_shards": args.vocab_shards, "V_shard": V, "V": V_full} if args.workload == "shard" else {})},
+        "packed_rows_per_s": T * args.steps / dt,          # value counts active (loss, not rejected) rows only
         "pct_mfma_peak_executed_8dV": 100.0 * executed / PEAK_BF16_TFLOPS,      # of 6dV for --workload bwd
         "executed_contractions_per_token": n_contractions,
         "pct_mfma_peak_useful_6dV": 100.0 * useful / PEAK_BF16_TFLOPS,
