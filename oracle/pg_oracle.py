@@ -294,7 +294,7 @@ def mismatch_weights(old_logp, rollout_logp, loss_mask, cu_seqlens, prm: Params)
         if len(idx) == 0:
             continue
         d = delta[idx]
-        vetoed = veto > 0.0 and np.exp(d.min()) < veto          # "drops below 1e-4"
+        vetoed = veto > 0.0 and np.exp(d.min()) < veto          # strictly below the threshold
         if vetoed:
             n_veto += 1
         if prm.mismatch_mode == 1:
