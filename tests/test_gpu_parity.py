@@ -97,6 +97,34 @@ def test_logprob_fwd_optional_outputs_and_bad_token(dev):
     assert abs(float(logp[5]) + float(lse[5])) < 1e-5
 
 
+def test_peaked_distributions_large_logits(dev):
+    """Logits with a standard deviation of about 40 (nearly one-hot softmax, log-probs down to -300, entropies
+    near 0): the online maximum must keep every exponent in range, forward and backward."""
+    T, d, V = 520, 128, 3000
+    H, W, y = synth.make_head(T, d, V, "bf16", 909, dev, unit_rms=True, w_std=3.5)
+    Hn, Wn, yn = np64(H), np64(W), y.cpu().numpy()
+    z = Hn @ Wn.T
+    y[::3] = torch.from_numpy(z.argmax(axis=1)[::3].astype(np.int32)).to(dev)       # a third of the targets are the mode
+    yn = y.cpu().numpy()
+    assert z.std() > 30
+    prm = B.Params(mismatch_mode=0)
+    ws = B.alloc_workspace(T, d, V, 1, prm, B.CALL_LOSS_FWD_BWD, dev)
+    logp, ent, lse = B.pg_logprob_fwd(H, W, y, None, prm, ws)
+    torch.cuda.synchronize()
+    rl, re, rs = O.lm_head_logprob(Hn, Wn, yn, 1.0)
+    assert rl.min() < -100 and re.min() < 1e-3
+    assert np.abs(logp.cpu().numpy() - rl).max() <= TOL_LOGP * max(1.0, np.abs(rl).max() / 100)
+    assert np.abs(ent.cpu().numpy() - re).max() <= TOL_LOGP and np.abs(lse.cpu().numpy() - rs).max() <= TOL_LOGP * 2
+    cu = torch.tensor([0, T], dtype=torch.int32, device=dev)
+    adv = torch.tensor([1.5], dtype=torch.float64, device=dev)
+    out = B.pg_loss_fwd_bwd(H, W, y, torch.ones(T, dtype=torch.uint8, device=dev), cu, adv, None, None, None, prm, ws)
+    torch.cuda.synchronize()
+    ref = O.pg_loss_fwd_bwd(Hn, Wn, yn, np.ones(T, np.uint8), np.array([0, T]), [1.5], None, None, O.Params())
+    assert torch.isfinite(out["dW"]).all() and torch.isfinite(out["dH"].float()).all()
+    assert abs(float(out["loss"][0]) - ref["loss"]) <= TOL_LOSS * abs(ref["loss"])
+    assert rel_fro(np64(out["dH"]), ref["dH"]) <= TOL_GRAD and rel_fro(np64(out["dW"]), ref["dW"]) <= TOL_GRAD
+
+
 def test_non_finite_inputs_propagate_and_stay_local(dev):
     """A NaN or an infinity in the inputs must come out as NaN in what depends on it and nowhere else; no
     kernel takes a data-dependent branch or address from H or W, so the call returns as always."""
