@@ -328,6 +328,43 @@ def test_repeatable_bitwise(dev):
         assert torch.equal(a[k], b[k]), k
 
 
+def test_two_streams_and_two_threads_do_not_interfere(dev):
+    """The library keeps no device state between calls: the same step issued on two streams from two host threads
+    at once, each with its own workspace and outputs, gives on both the bits of a single call."""
+    import threading
+    spec = synth.small_spec(d=128, V=2100, seed=9)
+    prm = B.Params(mismatch_mode=2)
+    batch, tin, _ = build_loss_case(spec, dev, oracle_logp, "token", on_policy=False)
+    T, d, V, S = batch.T, spec.d, spec.V, batch.S
+    adv, _, _ = B.trloo_advantage(tin["rewards"], tin["valid"], 1.0)
+    call = lambda ws, st: B.pg_loss_fwd_bwd(tin["H"], tin["W"], tin["y"], tin["loss_mask"], tin["cu"], adv.reshape(-1),
+                                            tin["seg_sample"], tin["old"], tin["rollout"], prm, ws, stream=st)
+    ref = call(B.alloc_workspace(T, d, V, S, prm, B.CALL_LOSS_FWD_BWD, dev), None)
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream(device=dev), torch.cuda.Stream(device=dev)]        # default priority
+    wss = [B.alloc_workspace(T, d, V, S, prm, B.CALL_LOSS_FWD_BWD, dev) for _ in streams]
+    results, errors = [None, None], []
+
+    def worker(i):
+        try:
+            torch.cuda.set_device(dev)
+            for _ in range(3):
+                results[i] = call(wss[i], streams[i])
+        except Exception as e:          # surfaced below: a thread must not die silently
+            errors.append(e)
+
+    threads = [threading.Thread(target=worker, args=(i,)) for i in range(2)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join(timeout=60)
+    torch.cuda.synchronize()
+    assert not errors and all(not t.is_alive() for t in threads), errors
+    for r in results:
+        for k in ("loss", "dH", "dW", "logp", "entropy", "counters"):
+            assert torch.equal(r[k], ref[k]), k
+
+
 def test_hip_graph_replay_matches_eager(dev):
     """The whole step (advantages + loss forward/backward) captured in a HIP graph: the library enqueues
     only kernels on the caller's stream, so a replay must reproduce the eager result bit for bit, also
