@@ -10,6 +10,11 @@ if ROOT not in sys.path:
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+    mutant = os.environ.get("PG_ORACLE_MUTANT")
+    if mutant:        # set only by test_oracle_pins_catch_mistakes.py for its child sessions
+        from oracle import pg_oracle
+        from tests._oracle_mutants import plant
+        plant(pg_oracle, mutant)
 
 
 @pytest.fixture(scope="session")

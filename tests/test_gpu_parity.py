@@ -224,6 +224,18 @@ def test_loss_small_bf16_modes(dev, monkeypatch, mode, kind, tau):
     _compare(out, ref)
 
 
+def test_loss_unequal_clip_ranges(dev):
+    """eps_lo != eps_hi (ratio clipped to [0.65, 1.05]): both clip counters and the gradients must follow."""
+    spec = synth.small_spec(d=64, V=900, seed=98)
+    prm = B.Params(clip_eps_lo=0.35, clip_eps_hi=0.05, mismatch_mode=0)
+    out, ref, _ = _run_loss(dev, spec, prm, "none", on_policy=False)
+    _compare(out, ref)
+    # the same inputs under the default symmetric range give different counters
+    assert ref["counters"][1] > 0 and ref["counters"][2] > 0
+    out_s, ref_s, _ = _run_loss(dev, spec, B.Params(mismatch_mode=0), "none", on_policy=False)
+    assert ref["counters"][1] != ref_s["counters"][1] and ref["counters"][2] != ref_s["counters"][2]
+
+
 def test_loss_on_policy_no_old_logp(dev):
     spec = synth.small_spec(d=64, V=900, seed=99)
     out, ref, _ = _run_loss(dev, spec, B.Params(), "none", on_policy=True)

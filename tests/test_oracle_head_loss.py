@@ -167,6 +167,14 @@ def test_ppo_truth_table():
     np.testing.assert_allclose(g[:6], [0.0, -1.0, -0.5, 1.5, 1.0, 0.0], atol=1e-12)
     assert list(chi[:6]) == [True, False, False, False, False, False]
     assert list(clo[:6]) == [False, False, False, False, False, True]
+    # unequal ranges: the ratio is clipped to [1 - eps_lo, 1 + eps_hi] = [0.9, 1.3]
+    asym = O.Params(clip_eps_lo=0.1, clip_eps_hi=0.3)
+    ra = np.array([1.25, 1.35, 0.95, 0.85])
+    Aa = np.array([1.0, 1.0, -1.0, -1.0])
+    loss_a, g_a, _, chi_a, clo_a = O.surrogate(np.log(ra), np.zeros(4), Aa, asym)
+    np.testing.assert_allclose(loss_a, [-1.25, -1.3, 0.95, 0.9], atol=1e-7)
+    np.testing.assert_allclose(g_a, [-1.25, 0.0, 0.95, 0.0], atol=1e-12)
+    assert list(chi_a) == [False, True, False, False] and list(clo_a) == [False, False, False, True]
     # on-policy: r = 1, l = -A, g = -A   (App. A estimator)
     loss, g, rr, _, _ = O.surrogate(np.log(r), None, A, prm)
     np.testing.assert_allclose(loss, -A)
