@@ -236,6 +236,26 @@ def test_loss_unequal_clip_ranges(dev):
     assert ref["counters"][1] != ref_s["counters"][1] and ref["counters"][2] != ref_s["counters"][2]
 
 
+def test_loss_non_default_mismatch_parameters(dev):
+    """The window, the veto threshold and the truncation cap come from the parameters, not from the paper's
+    defaults: a wider, off-centre window keeps a sample the default rejects; a veto threshold of 0 switches
+    the veto off; a lower threshold lets the e^-10 token through; a cap of 1.2 truncates more tokens."""
+    spec = synth.small_spec(d=64, V=900, seed=4322, P=3, K=5, Tmax=3)
+    base, ref_base, _ = _run_loss(dev, spec, B.Params(mismatch_mode=1), "window", on_policy=False)
+    prm = B.Params(mismatch_mode=1, geo_lo=0.9965, geo_hi=1.0015, veto_ratio=0.0)
+    out, ref, _ = _run_loss(dev, spec, prm, "window", on_policy=False)
+    _compare(out, ref)
+    assert ref["counters"][4] == 0 and ref_base["counters"][4] == 1                  # veto switched off
+    assert 0 < ref["counters"][3] < ref_base["counters"][3]                          # fewer samples outside the window
+    assert ref["counters"][0] > ref_base["counters"][0]
+    base2, ref_base2, _ = _run_loss(dev, spec, B.Params(mismatch_mode=2), "token", on_policy=False)
+    prm2 = B.Params(mismatch_mode=2, trunc_c=1.2, veto_ratio=1e-6)
+    out2, ref2, _ = _run_loss(dev, spec, prm2, "token", on_policy=False)
+    _compare(out2, ref2)
+    assert ref2["counters"][4] == 0 and ref_base2["counters"][4] == 1                # e^-10 = 4.5e-5 is above 1e-6
+    assert ref2["counters"][5] > ref_base2["counters"][5] > 0                        # more tokens hit the lower cap
+
+
 def test_loss_on_policy_no_old_logp(dev):
     spec = synth.small_spec(d=64, V=900, seed=99)
     out, ref, _ = _run_loss(dev, spec, B.Params(), "none", on_policy=True)
