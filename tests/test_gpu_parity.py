@@ -271,6 +271,11 @@ def test_loss_accumulate_bf16_dW_and_norm_override(dev, monkeypatch):
     prm = B.Params(accumulate_dW=0, dW_dtype=1)
     out, ref, _ = _run_loss(dev, spec, prm, "none", on_policy=False)
     _compare(out, ref)                            # bf16 dW: rounding 2^-9 per element, inside 1e-2
+    prm = B.Params(accumulate_dW=1, dW_dtype=1)   # read-modify-write of a bf16 dW, several chunks
+    out, ref, _ = _run_loss(dev, spec, prm, "none", on_policy=False, monkeypatch=monkeypatch, budget_tiles=2,
+                            accumulate=True)
+    assert out["dW"].dtype == torch.bfloat16
+    _compare(out, ref)
 
 
 def test_loss_f32_multichunk_with_truncation(dev, monkeypatch):
