@@ -2,7 +2,8 @@
 // checksum instead of an epilogue, at the three contraction shapes of the 14B head
 // (logits: M=V, N=tokens, K=d;  dW chunk: M=vc, N=d, K=tokens;  dH chunk: M=tokens, N=d, K=vc).
 // Usage: tile_bench [iters [shape]]   iters timed launches per shape (default 3); shape 0..2 runs
-// that shape only, shape 3 only the register-resident MFMA loop.  It first verifies a small ragged
+// that shape only, shape 3 only the register-resident MFMA loop, shape 4 the logits contraction over all
+// 32768 tokens in one launch (297 rounds of tiles instead of 74).  It first verifies a small ragged
 // product against a naive kernel, then times the MFMA instruction alone (operands and accumulators
 // in registers, no memory traffic: the rate the matrix pipes sustain on this chip, which the
 // published peak is compared with) and then the three shapes.
@@ -182,9 +183,11 @@ int main(int argc, char** argv) {
   struct Shape { const char* name; int M, N, K; } shapes[] = {
       {"logits  (V x tokens x d)", 151936, 8192, 5120},
       {"dW chunk (vc x d x tokens)", 21760, 5120, 32768},
-      {"dH chunk (tokens x d x vc)", 32768, 5120, 21760}};
-  for (int si = 0; si < 3; ++si) {
-    if (only >= 0 && si != only) continue;
+      {"dH chunk (tokens x d x vc)", 32768, 5120, 21760},
+      {"logits, 32768 tokens (297 rounds)", 151936, 32768, 5120}};
+  for (int si = 0; si < 4; ++si) {
+    if (only < 0 && si == 3) continue;    // the long logits launch runs only when asked for (shape 4)
+    if (only >= 0 && si != (only == 4 ? 3 : only)) continue;
     const Shape s = shapes[si];
     __bf16 *A, *B;
     float* out;
