@@ -198,3 +198,52 @@ def test_shard_empty_and_all_masked(dev):
     part0 = B.pg_head_shard_fwd(e, W, y[:0], None, 0, prm, ws)
     assert part0.shape == (0, 4)
     assert B.pg_head_partials_merge(part0, part0).shape == (0, 4)
+
+
+def test_shard_sequence_in_a_hip_graph(dev):
+    """Forward on two shards, merge, finish and the backward of one shard captured in one HIP graph: replays
+    reproduce the eager results bit for bit with a scrambled workspace (kernels only, no state between calls)."""
+    spec = synth.small_spec(seed=4323)
+    prm = B.Params(mismatch_mode=2)
+    batch, tin, _ = build_loss_case(spec, dev, oracle_logp, "token", on_policy=False)
+    T, d, V, S = batch.T, spec.d, spec.V, batch.S
+    cut = 1100
+    Wa, Wb = tin["W"][:cut].contiguous(), tin["W"][cut:].contiguous()
+    ws = B.alloc_workspace(T, d, V, S, prm, B.CALL_LOSS_FWD_BWD, dev)          # large enough for every call below
+    adv, _, _ = B.trloo_advantage(tin["rewards"], tin["valid"], 1.0)
+    pa = torch.empty((T, 4), dtype=torch.float32, device=dev)
+    pb = torch.empty_like(pa)
+    merged = torch.empty_like(pa)
+    dW = torch.empty((V - cut, d), dtype=torch.float32, device=dev)
+    outbuf = (torch.empty(1, dtype=torch.float32, device=dev), torch.empty((T, d), dtype=torch.float32, device=dev),
+              torch.empty(T, dtype=torch.float32, device=dev), torch.empty(T, dtype=torch.float32, device=dev),
+              torch.empty(8, dtype=torch.int64, device=dev))
+
+    def step(stream=None):
+        B.pg_head_shard_fwd(tin["H"], Wa, tin["y"], tin["loss_mask"], 0, prm, ws, out=pa, stream=stream)
+        B.pg_head_shard_fwd(tin["H"], Wb, tin["y"], tin["loss_mask"], cut, prm, ws, out=pb, stream=stream)
+        B.pg_head_partials_merge(pa, pb, out=merged, stream=stream)
+        return B.pg_loss_shard_bwd(tin["H"], Wb, tin["y"], tin["loss_mask"], tin["cu"], adv.reshape(-1), tin["seg_sample"],
+                                   tin["old"], tin["rollout"], merged, cut, prm, ws, dH_f32=True, dW=dW, out=outbuf,
+                                   stream=stream)
+
+    out = step()
+    torch.cuda.synchronize()
+    eager = {k: v.clone() for k, v in out.items()}
+    eager_merged = merged.clone()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            step(side)
+    for rep in range(3):
+        for t in outbuf + (pa, pb, merged, dW):
+            t.zero_()
+        ws.random_(0, 255)
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(merged, eager_merged), rep
+        for k in ("loss", "dH", "dW", "logp", "entropy", "counters"):
+            assert torch.equal(out[k], eager[k]), (rep, k)
+        _ = (tin["H"].float() @ Wa.float().T).sum()
+        torch.cuda.synchronize()
