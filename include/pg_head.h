@@ -294,6 +294,9 @@ int32_t pg_rmsnorm_bwd(const void* X, const void* gamma, const void* dH, int64_t
  *   dH_partial = dS[:, shard] W_shard        [T, d], this shard's term of the sum over shards that
  *                gives dH; fp32 if dH_f32 != 0 (what a sum all-reduce wants), else the dtype of H.
  * loss_out, logp_out, entropy_out and the counters are the same on every shard.
+ * With the whole head as the one shard (v_offset = 0, V_shard = V) this is pg_loss_fwd_bwd without its
+ * forward contraction: a caller whose old-policy recompute (pg_head_shard_fwd + pg_head_partials_finish)
+ * ran on the same H and W can hand its states over and save a quarter of the step's flops.
  * Workspace: pg_workspace_bytes(T, d, V_shard, S, params, PG_CALL_LOSS_FWD_BWD).
  * Errors as for pg_loss_fwd_bwd; partials and partials_out must be 16-byte aligned.
  */
