@@ -32,9 +32,14 @@
  *   - All work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the
  *     default stream).  No call synchronises with the host; scalar results are
  *     written to device memory.
- *   - Arguments are validated on the host before anything is enqueued.  On error
- *     the return value is negative, nothing has been enqueued and nothing is written;
- *     pg_last_error() gives a thread-local message.
+ *   - Arguments are validated on the host before anything is enqueued: for PG_ERR_INVALID_ARG,
+ *     PG_ERR_UNSUPPORTED_SHAPE and PG_ERR_WORKSPACE_TOO_SMALL nothing has been enqueued and
+ *     nothing is written.  PG_ERR_HIP reports a launch that the runtime refused; the kernels
+ *     enqueued before it still run and the outputs are then undefined.  Only an error that
+ *     arises during the call is reported: an error state that an earlier HIP call of the caller
+ *     left behind is neither returned nor cleared.  pg_last_error() gives a thread-local message.
+ *   - The first call on a device sets kernel attributes and must not happen inside a stream
+ *     capture: run one call eagerly, or pg_init(), before capturing.
  *   - H is [T,d] row-major, W is [V,d] row-major (LM-head weight, no bias), y[t] is
  *     the token whose log-prob row t predicts (the caller has already shifted).
  *     dtype 0: H, W, dH are bf16 (fp32 accumulation); dtype 1: H, W, dH are fp32.
@@ -80,7 +85,7 @@ extern "C" {
 #define PG_CNT_SEG_VETO 4    /* samples with a token ratio below veto_ratio */
 #define PG_CNT_TRUNCATED 5   /* tokens whose weight was capped (mode 2) */
 #define PG_CNT_LOSS_TOKENS 6 /* rows with loss_mask = 1 in samples that were not dropped */
-#define PG_CNT_SEG_DROPPED 7 /* samples with loss rows whose sample_keep flag is 0 */
+#define PG_CNT_SEG_DROPPED 7 /* samples with loss rows whose sample_keep flag is 0 (or whose table index is out of range) */
 
 typedef struct pg_params {
   int32_t dtype;         /* PG_DTYPE_* of H, W and dH */
@@ -96,10 +101,22 @@ typedef struct pg_params {
                             > 0: divide by this value (e.g. a global token count) */
   int32_t accumulate_dW; /* 0: dW is overwritten; 1: dW += */
   int32_t dW_dtype;      /* 0: fp32, 1: bf16 */
+  int32_t n_samples;     /* entries in the adv and sample_keep tables of the loss calls; a segment whose
+                            table index (seg_sample[s], or s) lies outside [0, n_samples) is treated as a
+                            dropped sample and counted in PG_CNT_SEG_DROPPED.  0: the length is not given
+                            and the indices are used as they are (an index outside the tables then reads
+                            memory that is not the caller's: undefined) */
 } pg_params;
 
 /* Message for the last error returned on this thread ("" if none). */
 const char* pg_last_error(void);
+
+/*
+ * One-time set-up for the CURRENT device: raises the MFMA kernels' dynamic shared-memory limit.  Every entry point does this
+ * by itself on its first call on a device; call pg_init() beforehand (once per device, outside any
+ * stream capture) if the first real call is to be recorded into a HIP graph.  Allocates nothing.
+ */
+int32_t pg_init(void);
 
 /*
  * Bytes of device workspace the given call needs for these sizes (S is ignored for
@@ -140,7 +157,8 @@ int32_t pg_logprob_fwd(const void* H, const void* W, const int32_t* y, const uin
  * training sample, i.e. one (prompt, rollout, turn).
  *
  *   loss_mask[t]      1 on response tokens (context / feedback rows are 0)
- *   adv               fp64 table of advantages (e.g. adv_out of trloo_advantage)
+ *   adv               fp64 table of advantages (e.g. adv_out of trloo_advantage), h_params->n_samples
+ *                     entries
  *   seg_sample        [S] index into adv of each segment; NULL = segment s uses adv[s]
  *   sample_keep       uint8 table indexed like adv (e.g. keep_out of prs_retain), nullable: a
  *                     segment whose flag is 0 was filtered out before training (Sec. 5.2) and is

@@ -46,11 +46,13 @@ def build(verbose: bool = True) -> str:
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.run(cmd, check=True)
-    # stand-alone tile-engine benchmark (used for the counter profiles)
+    # stand-alone tile-engine benchmark (a measurement tool: its failure must not fail the product build)
     cmd = [cc, *[f for f in FLAGS if f != "-fPIC"], os.path.join(CSRC, "tile_bench.hip"), "-o", os.path.join(PKG, "tile_bench")]
     if verbose:
         print(" ".join(cmd), flush=True)
-    subprocess.run(cmd, check=True, stdout=subprocess.DEVNULL, stderr=subprocess.DEVNULL)
+    r = subprocess.run(cmd, stdout=subprocess.DEVNULL, stderr=subprocess.DEVNULL)
+    if r.returncode != 0 and verbose:
+        print("warning: tile_bench did not build (the library is unaffected)", flush=True)
     return LIB
 
 

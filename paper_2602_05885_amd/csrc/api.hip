@@ -78,6 +78,7 @@ int32_t check_params(const pg_params* p) {
     return fail(PG_ERR_INVALID_ARG, "trunc_c must be > 0");
   if (!(p->veto_ratio >= 0.f)) return fail(PG_ERR_INVALID_ARG, "veto_ratio must be >= 0");
   if (p->dW_dtype != 0 && p->dW_dtype != 1) return fail(PG_ERR_INVALID_ARG, "unknown dW_dtype %d", p->dW_dtype);
+  if (p->n_samples < 0) return fail(PG_ERR_INVALID_ARG, "n_samples must be >= 0");
   return PG_OK;
 }
 
@@ -169,9 +170,28 @@ int32_t ensure_init() {
   return PG_OK;
 }
 
-int32_t check_launches(const char* what) {
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return fail(PG_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+// Launch errors.  hipGetLastError() would also return (and clear) an error that some earlier HIP
+// call of the caller left behind, and blame it on this call; instead the error state is looked at
+// without clearing it, before the first launch and after the last one, and only a state that
+// changed in between is reported.  An error present on entry is left for the caller to find.
+struct LaunchGuard {
+  hipError_t before;
+  LaunchGuard() : before(hipPeekAtLastError()) {}
+  int32_t check(const char* what) const {
+    const hipError_t e = hipPeekAtLastError();
+    if (e != hipSuccess && e != before) return fail(PG_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+    return PG_OK;
+  }
+};
+
+int32_t check_monitor_args(const float* logp_train, const uint8_t* loss_mask, int64_t T, const void* dH, int32_t dH_dtype,
+                           int64_t dH_elems, const void* dW, int32_t dW_dtype, int64_t dW_elems, const double* out) {
+  if (T < 0 || dH_elems < 0 || dW_elems < 0) return fail(PG_ERR_INVALID_ARG, "negative extent");
+  if (!out) return fail(PG_ERR_INVALID_ARG, "out must not be NULL");
+  if (T > 0 && (!logp_train || !loss_mask)) return fail(PG_ERR_INVALID_ARG, "logp_train and loss_mask must not be NULL when T > 0");
+  if ((dH && dH_dtype != 0 && dH_dtype != 1) || (dW && dW_dtype != 0 && dW_dtype != 1))
+    return fail(PG_ERR_INVALID_ARG, "gradient dtype must be 0 (bf16) or 1 (fp32)");
+  if ((dH && misaligned(dH)) || (dW && misaligned(dW))) return fail(PG_ERR_INVALID_ARG, "dH and dW must be 16-byte aligned");
   return PG_OK;
 }
 
@@ -256,9 +276,10 @@ int32_t turn_advantage(const float* rewards, const uint8_t* valid, int32_t P, in
   if (P < 1 || K < 1 || Tmax < 1) return fail(PG_ERR_INVALID_ARG, "P, K, Tmax must be >= 1");
   if ((int64_t)P * K * Tmax > (1ll << 30)) return fail(PG_ERR_UNSUPPORTED_SHAPE, "P*K*Tmax too large");
   if (!std::isfinite(gamma)) return fail(PG_ERR_INVALID_ARG, "gamma must be finite");
+  const LaunchGuard guard;
   pg::TrlooArgs a{rewards, valid, P, K, Tmax, gamma, returns_out, adv_out, group_n_out, group_mean};
   pg::launch_trloo(a, static_cast<hipStream_t>(stream));
-  return check_launches(what);
+  return guard.check(what);
 }
 
 // W as one vocab shard of a larger head: rows [v_offset, v_offset + V) of the vocabulary, the rows'
@@ -285,6 +306,10 @@ int32_t loss_fwd_bwd(int sft, const void* H, const void* W, const int32_t* y, co
 extern "C" {
 
 const char* pg_last_error(void) { return g_err; }
+
+int32_t pg_init(void) {
+  return ensure_init();
+}
 
 int32_t pg_profile_enable(int32_t on, int32_t max_launches) {
   for (hipEvent_t e : g_prof.ev) (void)hipEventDestroy(e);
@@ -344,6 +369,8 @@ int32_t pg_logprob_fwd(const void* H, const void* W, const int32_t* y, const uin
   if ((rc = ensure_init())) return rc;
   hipStream_t st = static_cast<hipStream_t>(stream);
 
+  const LaunchGuard guard;
+
   pg::PrepArgs prep = base_prep(pl, workspace);
   prep.mask = row_mask;
   prep.out0 = logp_out; prep.out1 = entropy_out; prep.out2 = lse_out;
@@ -351,7 +378,7 @@ int32_t pg_logprob_fwd(const void* H, const void* W, const int32_t* y, const uin
   comb.logp_out = logp_out; comb.ent_out = entropy_out; comb.lse_out = lse_out;
   comb.with_loss = 0;
   run_forward(pl, *h_params, workspace, H, W, y, 0, prep, comb, false, st);
-  return check_launches("pg_logprob_fwd");
+  return guard.check("pg_logprob_fwd");
 }
 
 int32_t pg_loss_fwd_bwd(const void* H, const void* W, const int32_t* y, const uint8_t* loss_mask,
@@ -381,6 +408,8 @@ int32_t pg_head_shard_fwd(const void* H, const void* W_shard, const int32_t* y, 
   if ((rc = ensure_init())) return rc;
   hipStream_t st = static_cast<hipStream_t>(stream);
 
+  const LaunchGuard guard;
+
   pg::launch_fill_zero_bytes(partials_out, (size_t)T * 4 * sizeof(float), st);   // rows that are masked out stay empty
   pg::PrepArgs prep = base_prep(pl, workspace);
   prep.mask = row_mask;
@@ -388,7 +417,7 @@ int32_t pg_head_shard_fwd(const void* H, const void* W_shard, const int32_t* y, 
   comb.with_loss = 0;
   comb.partials_out = partials_out;
   run_forward(pl, *h_params, workspace, H, W_shard, y, v_offset, prep, comb, false, st);
-  return check_launches("pg_head_shard_fwd");
+  return guard.check("pg_head_shard_fwd");
 }
 
 int32_t pg_head_partials_merge(const float* a, const float* b, float* out, int64_t T, void* stream) {
@@ -396,8 +425,9 @@ int32_t pg_head_partials_merge(const float* a, const float* b, float* out, int64
   if (T == 0) return PG_OK;
   if (!a || !b || !out) return fail(PG_ERR_INVALID_ARG, "a, b and out must not be NULL");
   if (misaligned(a) || misaligned(b) || misaligned(out)) return fail(PG_ERR_INVALID_ARG, "a, b and out must be 16-byte aligned");
+  const LaunchGuard guard;
   pg::launch_merge_partials(a, b, out, T, static_cast<hipStream_t>(stream));
-  return check_launches("pg_head_partials_merge");
+  return guard.check("pg_head_partials_merge");
 }
 
 int32_t pg_head_partials_finish(const float* partials, int64_t T, float* logp_out, float* entropy_out, float* lse_out,
@@ -406,8 +436,9 @@ int32_t pg_head_partials_finish(const float* partials, int64_t T, float* logp_ou
   if (T == 0) return PG_OK;
   if (!partials || !logp_out) return fail(PG_ERR_INVALID_ARG, "partials and logp_out must not be NULL");
   if (misaligned(partials)) return fail(PG_ERR_INVALID_ARG, "partials must be 16-byte aligned");
+  const LaunchGuard guard;
   pg::launch_finish_partials(partials, T, logp_out, entropy_out, lse_out, static_cast<hipStream_t>(stream));
-  return check_launches("pg_head_partials_finish");
+  return guard.check("pg_head_partials_finish");
 }
 
 int32_t pg_loss_shard_bwd(const void* H, const void* W_shard, const int32_t* y, const uint8_t* loss_mask,
@@ -445,9 +476,10 @@ int32_t turn_reward(const uint8_t* correct, const float* t_reference, const floa
   if ((t_generated == nullptr) != (t_total == nullptr))
     return fail(PG_ERR_INVALID_ARG, "t_generated and t_total must be given together");
   if (!(speedup_cap > 0.f) || !std::isfinite(speedup_cap)) return fail(PG_ERR_INVALID_ARG, "speedup_cap must be finite and > 0");
+  const LaunchGuard guard;
   pg::RewardArgs a{correct, t_reference, t_kernel, t_generated, t_total, (long long)n, speedup_cap, rewards_out, pr_out};
   pg::launch_turn_reward(a, static_cast<hipStream_t>(stream));
-  return check_launches("turn_reward");
+  return guard.check("turn_reward");
 }
 
 int32_t prs_retain(const float* pr, const uint8_t* valid, int64_t n, float tau, float s, int32_t hard, uint64_t seed,
@@ -456,9 +488,10 @@ int32_t prs_retain(const float* pr, const uint8_t* valid, int64_t n, float tau, 
   if (n == 0) return PG_OK;
   if (!pr || !keep_out) return fail(PG_ERR_INVALID_ARG, "pr and keep_out must not be NULL");
   if (!(s > 0.f) || !std::isfinite(s) || !std::isfinite(tau)) return fail(PG_ERR_INVALID_ARG, "tau must be finite and s finite and > 0");
+  const LaunchGuard guard;
   pg::PrsArgs a{pr, valid, (long long)n, tau, s, hard != 0, (unsigned long long)seed, keep_out, p_out};
   pg::launch_prs_retain(a, static_cast<hipStream_t>(stream));
-  return check_launches("prs_retain");
+  return guard.check("prs_retain");
 }
 
 size_t pg_monitors_workspace_bytes(void) { return (size_t)6 * pg::MON_BLOCKS * sizeof(double); }
@@ -466,19 +499,17 @@ size_t pg_monitors_workspace_bytes(void) { return (size_t)6 * pg::MON_BLOCKS * s
 int32_t pg_monitors(const float* logp_train, const float* logp_rollout, const float* entropy, const uint8_t* loss_mask,
                     int64_t T, const void* dH, int32_t dH_dtype, int64_t dH_elems, const void* dW, int32_t dW_dtype,
                     int64_t dW_elems, double* out, void* workspace, size_t workspace_bytes, void* stream) {
-  if (T < 0 || dH_elems < 0 || dW_elems < 0) return fail(PG_ERR_INVALID_ARG, "negative extent");
-  if (!out || !workspace) return fail(PG_ERR_INVALID_ARG, "out and workspace must not be NULL");
-  if (T > 0 && (!logp_train || !loss_mask)) return fail(PG_ERR_INVALID_ARG, "logp_train and loss_mask must not be NULL when T > 0");
-  if ((dH && dH_dtype != 0 && dH_dtype != 1) || (dW && dW_dtype != 0 && dW_dtype != 1))
-    return fail(PG_ERR_INVALID_ARG, "gradient dtype must be 0 (bf16) or 1 (fp32)");
-  if ((dH && misaligned(dH)) || (dW && misaligned(dW)) || (reinterpret_cast<uintptr_t>(workspace) & 7u))
-    return fail(PG_ERR_INVALID_ARG, "dH and dW must be 16-byte aligned, workspace 8-byte aligned");
+  int32_t rc = check_monitor_args(logp_train, loss_mask, T, dH, dH_dtype, dH_elems, dW, dW_dtype, dW_elems, out);
+  if (rc) return rc;
+  if (!workspace) return fail(PG_ERR_INVALID_ARG, "workspace must not be NULL");
+  if (reinterpret_cast<uintptr_t>(workspace) & 7u) return fail(PG_ERR_INVALID_ARG, "workspace must be 8-byte aligned");
   if (workspace_bytes < pg_monitors_workspace_bytes())
     return fail(PG_ERR_WORKSPACE_TOO_SMALL, "workspace has %zu bytes, %zu needed", workspace_bytes, pg_monitors_workspace_bytes());
+  const LaunchGuard guard;
   pg::MonitorArgs a{logp_train, logp_rollout, entropy, loss_mask, (long long)T, dH, dH_dtype, (long long)dH_elems,
                     dW, dW_dtype, (long long)dW_elems, static_cast<double*>(workspace), out};
   pg::launch_monitors(a, static_cast<hipStream_t>(stream));
-  return check_launches("pg_monitors");
+  return guard.check("pg_monitors");
 }
 
 int32_t pg_rmsnorm_fwd(const void* X, const void* gamma, int64_t T, int64_t d, float eps, int32_t dtype, void* H_out,
@@ -491,11 +522,12 @@ int32_t pg_rmsnorm_fwd(const void* X, const void* gamma, int64_t T, int64_t d, f
   if (T == 0) return PG_OK;
   if (!X || !gamma || !H_out) return fail(PG_ERR_INVALID_ARG, "X, gamma and H_out must not be NULL");
   if (misaligned(X) || misaligned(gamma) || misaligned(H_out)) return fail(PG_ERR_INVALID_ARG, "X, gamma and H_out must be 16-byte aligned");
+  const LaunchGuard guard;
   pg::NormArgs a{};
   a.X = X; a.gamma = gamma; a.T = T; a.d = (int)d; a.eps = eps; a.is_f32 = dtype == PG_DTYPE_F32;
   a.H = H_out; a.rstd_out = rstd_out;
   pg::launch_rmsnorm_fwd(a, static_cast<hipStream_t>(stream));
-  return check_launches("pg_rmsnorm_fwd");
+  return guard.check("pg_rmsnorm_fwd");
 }
 
 size_t pg_rmsnorm_bwd_workspace_bytes(int64_t d) {
@@ -516,11 +548,12 @@ int32_t pg_rmsnorm_bwd(const void* X, const void* gamma, const void* dH, int64_t
     return fail(PG_ERR_INVALID_ARG, "X, gamma, dH, dX_out and workspace must be 16-byte aligned");
   if (workspace_bytes < pg_rmsnorm_bwd_workspace_bytes(d))
     return fail(PG_ERR_WORKSPACE_TOO_SMALL, "workspace has %zu bytes, %zu needed", workspace_bytes, pg_rmsnorm_bwd_workspace_bytes(d));
+  const LaunchGuard guard;
   pg::NormArgs a{};
   a.X = X; a.gamma = gamma; a.T = T; a.d = (int)d; a.eps = eps; a.is_f32 = dtype == PG_DTYPE_F32;
   a.dH = dH; a.dX = dX_out; a.partial = static_cast<float*>(workspace); a.dgamma = dgamma_out;
   pg::launch_rmsnorm_bwd(a, static_cast<hipStream_t>(stream));
-  return check_launches("pg_rmsnorm_bwd");
+  return guard.check("pg_rmsnorm_bwd");
 }
 
 }  // extern "C"
@@ -542,10 +575,11 @@ int32_t loss_fwd_bwd(int sft, const void* H, const void* W, const int32_t* y, co
   hipStream_t st = static_cast<hipStream_t>(stream);
   const size_t dw_elem = p.dW_dtype ? 2 : 4;
   if (T == 0) {   // empty microbatch: zero loss, zero gradient
+    const LaunchGuard guard;
     pg::launch_fill_f32(loss_out, 1, 0.f, st);
     if (counters_out) pg::launch_fill_zero_bytes(counters_out, 8 * sizeof(int64_t), st);
     if (!p.accumulate_dW) pg::launch_fill_zero_bytes(dW, (size_t)V * d * dw_elem, st);
-    return check_launches(shard.what ? shard.what : sft ? "pg_sft_fwd_bwd (empty)" : "pg_loss_fwd_bwd (empty)");
+    return guard.check(shard.what ? shard.what : sft ? "pg_sft_fwd_bwd (empty)" : "pg_loss_fwd_bwd (empty)");
   }
   if (!H || !y || !loss_mask || !dH || !workspace)
     return fail(PG_ERR_INVALID_ARG, "H, y, loss_mask, dH and workspace must not be NULL");
@@ -559,10 +593,11 @@ int32_t loss_fwd_bwd(int sft, const void* H, const void* W, const int32_t* y, co
   if (workspace_bytes < pl.total) return fail(PG_ERR_WORKSPACE_TOO_SMALL, "workspace has %zu bytes, %zu needed", workspace_bytes, pl.total);
   if ((rc = ensure_init())) return rc;
   void* ws = workspace;
+  const LaunchGuard guard;
 
   pg::PrepArgs prep = base_prep(pl, ws);
   prep.mask = loss_mask; prep.cu = cu_seqlens; prep.S = S; prep.adv = adv; prep.seg_sample = seg_sample;
-  prep.sample_keep = sample_keep;
+  prep.sample_keep = sample_keep; prep.n_samples = p.n_samples;
   prep.old_logp = old_logp; prep.rollout_logp = rollout_logp;
   prep.mismatch_mode = sft ? PG_MISMATCH_NONE : p.mismatch_mode; prep.geo_lo = p.geo_lo; prep.geo_hi = p.geo_hi;
   prep.veto_ratio = p.veto_ratio; prep.trunc_c = p.trunc_c; prep.norm_override = p.norm_override;
@@ -628,7 +663,7 @@ int32_t loss_fwd_bwd(int sft, const void* H, const void* W, const int32_t* y, co
   pg::ScatterArgs sc{at<float>(ws, pl.dHacc), at<int>(ws, pl.pos), dH, (int)pl.T, d_i, pl.is_f32 || shard.dH_f32,
                      1, pl.t_cap, (d_i + 255) / 256, kc0 / 64, ctl};
   pg::launch_scatter_dh(sc, st);
-  return check_launches(shard.what ? shard.what : sft ? "pg_sft_fwd_bwd" : "pg_loss_fwd_bwd");
+  return guard.check(shard.what ? shard.what : sft ? "pg_sft_fwd_bwd" : "pg_loss_fwd_bwd");
 }
 
 }  // namespace

@@ -90,6 +90,7 @@ struct PrepArgs {
   const double* adv;
   const int* seg_sample;
   const uint8_t* sample_keep; // indexed like adv (nullable = keep all): 0 drops the segment
+  int n_samples;             // entries of adv / sample_keep (0 = unknown: indices are not range-checked)
   const float* old_logp;
   const float* rollout_logp;
   int T, t_cap;

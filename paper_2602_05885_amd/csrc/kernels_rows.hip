@@ -84,7 +84,8 @@ __global__ void prep_init_kernel(PrepArgs a) {
 
 // One workgroup per segment (= one training sample): Sec. 5.1's geometric-mean ratio and
 // token veto over the sample's loss tokens, decided in fp64, then per-row weights.  A sample
-// whose keep flag is 0 (Sec. 5.2's rejection sampling) is skipped before any of that.
+// whose keep flag is 0 (Sec. 5.2's rejection sampling), or whose index lies outside the
+// advantage table, is skipped before any of that.
 __global__ __launch_bounds__(256) void prep_segment_kernel(PrepArgs a) {
   __shared__ double sh_sum[256];
   __shared__ double sh_min[256];
@@ -95,6 +96,9 @@ __global__ __launch_bounds__(256) void prep_segment_kernel(PrepArgs a) {
   lo = max(lo, 0);
   hi = min(hi, a.T);
   const bool mm = a.mismatch_mode != 0;
+  // table entry of this segment; an index outside the tables drops the segment and reads nothing
+  const int idx = a.seg_sample ? a.seg_sample[s] : s;
+  const bool in_table = a.n_samples <= 0 || (idx >= 0 && idx < a.n_samples);
   double sum = 0.0, mn = 1.0e300;
   int n = 0;
   for (int t = lo + tid; t < hi; t += 256) {
@@ -120,7 +124,7 @@ __global__ __launch_bounds__(256) void prep_segment_kernel(PrepArgs a) {
   if (tid == 0) {
     int keep = 1;
     const int nn = sh_n[0];
-    const bool dropped = a.sample_keep && !a.sample_keep[a.seg_sample ? a.seg_sample[s] : s];
+    const bool dropped = !in_table || (a.sample_keep && !a.sample_keep[idx]);
     if (dropped) {            // filtered out before training (PRS): as if the sample had no loss rows
       keep = 0;
       if (nn > 0) atomicAdd(&a.counters[7], 1ull);
@@ -140,7 +144,7 @@ __global__ __launch_bounds__(256) void prep_segment_kernel(PrepArgs a) {
   }
   __syncthreads();
   const int keep = sh_keep;
-  const float A = (float)a.adv[a.seg_sample ? a.seg_sample[s] : s];
+  const float A = in_table ? (float)a.adv[idx] : 0.f;
   unsigned long long ntr = 0;
   for (int t = lo + tid; t < hi; t += 256) {
     const bool act = a.mask[t] && keep;

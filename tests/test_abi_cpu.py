@@ -146,3 +146,64 @@ def test_shard_entry_points_validate_arguments():
     assert lib.pg_loss_shard_bwd(*args(one, -5, 1, big)) == -1
     assert lib.pg_loss_shard_bwd(*args(one, 0, 2, big)) == -1 and "dH_f32" in B.pg_last_error()
     assert lib.pg_loss_shard_bwd(*args(one, 0, 1, 16)) == -3
+
+
+def test_binding_rejects_wrong_dtypes_shapes_and_devices():
+    """The C ABI sees raw pointers: the Python wrappers must refuse tensors whose dtype, shape or device is
+    not what the library will assume, before any pointer is handed over (no GPU needed: every case fails
+    in the wrapper)."""
+    import torch
+    T, d, V, S = 16, 64, 100, 2
+    cpu = torch.device("cpu")
+    H = torch.zeros((T, d), dtype=torch.bfloat16)
+    W = torch.zeros((V, d), dtype=torch.bfloat16)
+    y = torch.zeros(T, dtype=torch.int32)
+    ws = torch.zeros(1024, dtype=torch.uint8)
+    P = B.Params()
+    with pytest.raises(ValueError, match="device pointers"):          # CPU tensors never reach the library
+        B.pg_logprob_fwd(H, W, y, None, P, ws)
+    with pytest.raises(ValueError, match="device pointers"):
+        B.pg_sft_fwd_bwd(H, W, y, torch.ones(T, dtype=torch.uint8), P, ws)
+
+    # the remaining checks are exercised through the helpers with the device check satisfied by a fake
+    # device argument (the tensors live on the CPU here; on the GPU box the same code sees cuda tensors)
+    with pytest.raises(ValueError, match="dtype"):                    # torch's default int64 token ids
+        B._want("y", y.long(), torch.int32, (T,), cpu)
+    with pytest.raises(ValueError, match="dtype"):                    # bf16 H with params.dtype = fp32
+        B._want("H", H, B._HEAD_DTYPES[1], (T, d))
+    with pytest.raises(ValueError, match="shape"):
+        B._want("W", torch.zeros((V, d + 64), dtype=torch.bfloat16), torch.bfloat16, (V, d), cpu)
+    with pytest.raises(ValueError, match="shape"):
+        B._want("y", y[:-1], torch.int32, (T,), cpu)
+    with pytest.raises(ValueError, match="contiguous"):
+        B._want("H", torch.zeros((d, T), dtype=torch.bfloat16).t(), torch.bfloat16, (T, d), cpu)
+    with pytest.raises(ValueError, match="None"):
+        B._want("y", None, torch.int32)
+    B._want("mask", torch.ones(T, dtype=torch.bool), torch.uint8, (T,), cpu)          # bool is one byte per flag
+
+    mask = torch.ones(T, dtype=torch.uint8)
+    cu = torch.tensor([0, 8, 16], dtype=torch.int32)
+    adv = torch.zeros(6, dtype=torch.float64)
+    seg = torch.tensor([0, 5], dtype=torch.int32)
+    lp = torch.zeros(T, dtype=torch.float32)
+    ok = dict(T=T, dev=cpu, loss_mask=mask, cu_seqlens=cu, adv=adv, seg_sample=seg, sample_keep=None, old_logp=lp,
+              rollout_logp=lp)
+    assert B._want_loss_args(**ok) == S
+    for key, bad, pat in (("adv", adv.float(), "dtype"), ("cu_seqlens", cu.long(), "dtype"), ("seg_sample", seg.long(), "dtype"),
+                          ("seg_sample", seg[:1], "shape"), ("old_logp", lp.bfloat16(), "dtype"), ("old_logp", lp[:-1], "shape"),
+                          ("rollout_logp", lp.double(), "dtype"), ("loss_mask", mask.int(), "dtype"),
+                          ("sample_keep", torch.ones(5, dtype=torch.uint8), "shape"), ("adv", adv.reshape(2, 3), "1-d")):
+        with pytest.raises(ValueError, match=pat):
+            B._want_loss_args(**{**ok, key: bad})
+    with pytest.raises(ValueError, match="no seg_sample"):
+        B._want_loss_args(**{**ok, "adv": adv[:1], "seg_sample": None})
+
+    out = (torch.zeros(1), torch.zeros((T, d), dtype=torch.bfloat16), torch.zeros(T), torch.zeros(T),
+           torch.zeros(8, dtype=torch.int64))
+    B._want_loss_out(out, T, d, V, cpu, torch.bfloat16, torch.zeros((V, d)), P)
+    with pytest.raises(ValueError, match="dtype"):                    # fp32 dW buffer with params.dW_dtype = bf16
+        B._want_loss_out(out, T, d, V, cpu, torch.bfloat16, torch.zeros((V, d)), B.Params(dW_dtype=1))
+    with pytest.raises(ValueError, match="dtype"):
+        B._want_loss_out(out[:4] + (torch.zeros(8, dtype=torch.int32),), T, d, V, cpu, torch.bfloat16, None, P)
+    with pytest.raises(ValueError, match="shape"):
+        B._want_loss_out(out, T, d, V, cpu, torch.bfloat16, torch.zeros((V + 1, d)), P)
