@@ -112,7 +112,8 @@ typedef struct pg_params {
 const char* pg_last_error(void);
 
 /*
- * One-time set-up for the CURRENT device: raises the MFMA kernels' dynamic shared-memory limit.  Every entry point does this
+ * One-time set-up for the CURRENT device: raises the MFMA kernels' dynamic shared-memory limit and
+ * resolves the device address of the library's static scratch array.  Every entry point does this
  * by itself on its first call on a device; call pg_init() beforehand (once per device, outside any
  * stream capture) if the first real call is to be recorded into a HIP graph.  Allocates nothing.
  */
@@ -261,6 +262,26 @@ int32_t pg_monitors(const float* logp_train, const float* logp_rollout, const fl
                     const uint8_t* loss_mask, int64_t T, const void* dH, int32_t dH_dtype, int64_t dH_elems,
                     const void* dW, int32_t dW_dtype, int64_t dW_elems, double* out, void* workspace,
                     size_t workspace_bytes, void* stream);
+
+/*
+ * pg_monitors for callers that cannot allocate device memory (code under HIP graph capture, tight
+ * loops, harnesses that forbid hipMalloc): same arguments, results and error behaviour, without the
+ * workspace.  The partial sums (6 x 1024 fp64 = 49 152 bytes, for any input size) live in a static
+ * device array inside the library; each GPU the library runs on holds one copy until the process
+ * ends.  The call allocates and frees nothing.  Limits: T <= PG_MONITORS_STATIC_MAX_ROWS and
+ * dH_elems, dW_elems <= PG_MONITORS_STATIC_MAX_ELEMS, else PG_ERR_UNSUPPORTED_SHAPE (use pg_monitors
+ * with a workspace of the caller's).  All calls on one GPU share that GPU's array: calls that
+ * overlap on one GPU (two streams, two threads) race and give undefined monitors; calls that
+ * follow each other on a stream, or are otherwise ordered, are fine - every call rewrites all
+ * partial sums before it reads them, so nothing is carried from one call to the next.  The array's
+ * address is resolved on the first call on a device (or by pg_init()), which must not happen
+ * inside a stream capture.
+ */
+#define PG_MONITORS_STATIC_MAX_ROWS 2147483648LL      /* 2^31 */
+#define PG_MONITORS_STATIC_MAX_ELEMS 1099511627776LL  /* 2^40 */
+int32_t pg_monitors_static(const float* logp_train, const float* logp_rollout, const float* entropy,
+                           const uint8_t* loss_mask, int64_t T, const void* dH, int32_t dH_dtype, int64_t dH_elems,
+                           const void* dW, int32_t dW_dtype, int64_t dW_elems, double* out, void* stream);
 
 /*
  * The step in front of the head in the policies the paper trains (Qwen3, Sec. 6.1): per row,

@@ -23,7 +23,7 @@ COUNTER_NAMES = ("active", "clip_hi", "clip_lo", "seg_geo", "seg_veto", "truncat
 
 EXPORTS = ("pg_last_error", "pg_init", "pg_workspace_bytes", "trloo_advantage", "pg_logprob_fwd", "pg_loss_fwd_bwd",
            "pg_sft_fwd_bwd", "pg_head_shard_fwd", "pg_head_partials_merge", "pg_head_partials_finish", "pg_loss_shard_bwd", "grpo_advantage",
-           "turn_reward", "prs_retain", "pg_monitors_workspace_bytes", "pg_monitors", "pg_rmsnorm_fwd", "pg_rmsnorm_bwd_workspace_bytes", "pg_rmsnorm_bwd",
+           "turn_reward", "prs_retain", "pg_monitors_workspace_bytes", "pg_monitors", "pg_monitors_static", "pg_rmsnorm_fwd", "pg_rmsnorm_bwd_workspace_bytes", "pg_rmsnorm_bwd",
            "pg_profile_enable", "pg_profile_read")
 MONITOR_NAMES = ("entropy_mean", "ppl_train", "ppl_rollout", "dH_norm", "dW_norm", "n")
 KERNEL_CLASSES = ("fwd", "dlogits", "dw", "dh")
@@ -123,6 +123,9 @@ def lib() -> C.CDLL:
         L.pg_monitors.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_int32,
                                   C.c_int64, C.c_void_p, C.c_int32, C.c_int64, C.c_void_p, C.c_void_p, C.c_size_t,
                                   C.c_void_p]
+        L.pg_monitors_static.restype = C.c_int32
+        L.pg_monitors_static.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_int32,
+                                         C.c_int64, C.c_void_p, C.c_int32, C.c_int64, C.c_void_p, C.c_void_p]
         L.pg_init.restype = C.c_int32
         L.pg_init.argtypes = []
         L.pg_rmsnorm_fwd.restype = C.c_int32
@@ -346,6 +349,19 @@ def _monitor_args(logp_train, logp_rollout, entropy, loss_mask, dH, dW):
 def pg_init() -> None:
     """Per-device set-up (kernel attributes, address of the static scratch) for the current device."""
     _check(lib().pg_init())
+
+
+def pg_monitors_static(logp_train, logp_rollout, entropy, loss_mask, dH=None, dW=None, out=None, stream=None):
+    """pg_monitors without a workspace (the library's static scratch); `out` float64 [8] may be passed in, so
+    that the call itself allocates nothing.  Calls that overlap on one GPU race."""
+    T, dev, dt = _monitor_args(logp_train, logp_rollout, entropy, loss_mask, dH, dW)
+    if out is None:
+        out = torch.empty(8, dtype=torch.float64, device=dev)
+    _want("out", out, torch.float64, (8,), dev)
+    _check(lib().pg_monitors_static(_ptr(logp_train), _ptr(logp_rollout), _ptr(entropy), _ptr(loss_mask), T, _ptr(dH),
+                                    dt(dH), 0 if dH is None else dH.numel(), _ptr(dW), dt(dW),
+                                    0 if dW is None else dW.numel(), _ptr(out), _stream(stream)))
+    return out
 
 
 def pg_logprob_fwd(H, W, y, row_mask, params: Params, workspace: torch.Tensor, want_entropy=True, want_lse=True,

@@ -170,6 +170,31 @@ int32_t ensure_init() {
   return PG_OK;
 }
 
+// ---- scratch of the entry point that allocates nothing (pg_monitors_static) ----
+// The monitors' partial sums ([6][MON_BLOCKS] fp64, 48 KiB) in a file-scope device array: every GPU
+// the library runs on holds its own copy, at its own address, until the process ends.  In host
+// code the array's name is only a handle for hipGetSymbolAddress; kernels get the resolved address.
+constexpr size_t MON_SCRATCH_DOUBLES = (size_t)6 * pg::MON_BLOCKS;
+static __device__ __align__(256) double scratch[MON_SCRATCH_DOUBLES];
+
+// Device address of `scratch` on the current device, resolved once per device.
+int32_t monitors_scratch(double** out) {
+  static double* ptr[64] = {};
+  static std::mutex mu;
+  std::lock_guard<std::mutex> lock(mu);
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return fail(PG_ERR_HIP, "hipGetDevice failed");
+  if (dev < 0 || dev >= 64) return fail(PG_ERR_HIP, "device index %d out of range", dev);
+  if (!ptr[dev]) {
+    double* p = nullptr;
+    hipError_t e = hipGetSymbolAddress(reinterpret_cast<void**>(&p), HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !p) return fail(PG_ERR_HIP, "hipGetSymbolAddress(scratch) failed: %s", hipGetErrorString(e));
+    ptr[dev] = p;
+  }
+  *out = ptr[dev];
+  return PG_OK;
+}
+
 // Launch errors.  hipGetLastError() would also return (and clear) an error that some earlier HIP
 // call of the caller left behind, and blame it on this call; instead the error state is looked at
 // without clearing it, before the first launch and after the last one, and only a state that
@@ -308,7 +333,10 @@ extern "C" {
 const char* pg_last_error(void) { return g_err; }
 
 int32_t pg_init(void) {
-  return ensure_init();
+  int32_t rc = ensure_init();
+  if (rc) return rc;
+  double* unused = nullptr;
+  return monitors_scratch(&unused);
 }
 
 int32_t pg_profile_enable(int32_t on, int32_t max_launches) {
@@ -510,6 +538,28 @@ int32_t pg_monitors(const float* logp_train, const float* logp_rollout, const fl
                     dW, dW_dtype, (long long)dW_elems, static_cast<double*>(workspace), out};
   pg::launch_monitors(a, static_cast<hipStream_t>(stream));
   return guard.check("pg_monitors");
+}
+
+int32_t pg_monitors_static(const float* logp_train, const float* logp_rollout, const float* entropy,
+                           const uint8_t* loss_mask, int64_t T, const void* dH, int32_t dH_dtype, int64_t dH_elems,
+                           const void* dW, int32_t dW_dtype, int64_t dW_elems, double* out, void* stream) {
+  int32_t rc = check_monitor_args(logp_train, loss_mask, T, dH, dH_dtype, dH_elems, dW, dW_dtype, dW_elems, out);
+  if (rc) return rc;
+  if (T > PG_MONITORS_STATIC_MAX_ROWS || dH_elems > PG_MONITORS_STATIC_MAX_ELEMS || dW_elems > PG_MONITORS_STATIC_MAX_ELEMS)
+    return fail(PG_ERR_UNSUPPORTED_SHAPE,
+                "pg_monitors_static takes at most %lld rows and %lld elements per gradient (got T=%lld, dH_elems=%lld, "
+                "dW_elems=%lld); use pg_monitors with a caller-owned workspace beyond that",
+                (long long)PG_MONITORS_STATIC_MAX_ROWS, (long long)PG_MONITORS_STATIC_MAX_ELEMS, (long long)T,
+                (long long)dH_elems, (long long)dW_elems);
+  double* partial = nullptr;
+  if ((rc = monitors_scratch(&partial))) return rc;
+  const LaunchGuard guard;
+  // every one of the 6 x MON_BLOCKS partial sums is rewritten by each call (one workgroup per
+  // column), so nothing of the previous call's contents has to be cleared
+  pg::MonitorArgs a{logp_train, logp_rollout, entropy, loss_mask, (long long)T, dH, dH_dtype, (long long)dH_elems,
+                    dW, dW_dtype, (long long)dW_elems, partial, out};
+  pg::launch_monitors(a, static_cast<hipStream_t>(stream));
+  return guard.check("pg_monitors_static");
 }
 
 int32_t pg_rmsnorm_fwd(const void* X, const void* gamma, int64_t T, int64_t d, float eps, int32_t dtype, void* H_out,

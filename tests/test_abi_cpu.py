@@ -148,6 +148,17 @@ def test_shard_entry_points_validate_arguments():
     assert lib.pg_loss_shard_bwd(*args(one, 0, 1, 16)) == -3
 
 
+def test_static_monitors_and_init_validate_arguments():
+    lib = B.lib()
+    one = C.c_void_p(16)      # never dereferenced: validation fails first
+    assert lib.pg_monitors_static(one, None, None, one, 4, None, 0, 0, None, 0, 0, None, None) == -1
+    assert lib.pg_monitors_static(one, None, None, one, -1, None, 0, 0, None, 0, 0, one, None) == -1
+    assert lib.pg_monitors_static(one, None, None, one, (1 << 31) + 1, None, 0, 0, None, 0, 0, one, None) == -2
+    assert "at most" in B.pg_last_error()
+    assert lib.pg_monitors_static(one, None, None, one, 4, one, 0, (1 << 40) + 1, None, 0, 0, one, None) == -2
+    assert lib.pg_monitors_static(one, None, None, one, 4, C.c_void_p(8), 0, 8, None, 0, 0, one, None) == -1
+
+
 def test_binding_rejects_wrong_dtypes_shapes_and_devices():
     """The C ABI sees raw pointers: the Python wrappers must refuse tensors whose dtype, shape or device is
     not what the library will assume, before any pointer is handed over (no GPU needed: every case fails
