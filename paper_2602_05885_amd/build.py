@@ -46,13 +46,15 @@ def build(verbose: bool = True) -> str:
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.run(cmd, check=True)
-    # stand-alone tile-engine benchmark (a measurement tool: its failure must not fail the product build)
-    cmd = [cc, *[f for f in FLAGS if f != "-fPIC"], os.path.join(CSRC, "tile_bench.hip"), "-o", os.path.join(PKG, "tile_bench")]
-    if verbose:
-        print(" ".join(cmd), flush=True)
-    r = subprocess.run(cmd, stdout=subprocess.DEVNULL, stderr=subprocess.DEVNULL)
-    if r.returncode != 0 and verbose:
-        print("warning: tile_bench did not build (the library is unaffected)", flush=True)
+    # stand-alone measurement tools (their failure must not fail the product build): the tile engine's main
+    # loop alone, and the persistent form of the forward kernel next to the library's
+    for tool in ("tile_bench", "stream_bench"):
+        cmd = [cc, *[f for f in FLAGS if f != "-fPIC"], os.path.join(CSRC, tool + ".hip"), "-o", os.path.join(PKG, tool)]
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        r = subprocess.run(cmd, stdout=subprocess.DEVNULL, stderr=subprocess.DEVNULL)
+        if r.returncode != 0 and verbose:
+            print(f"warning: {tool} did not build (the library is unaffected)", flush=True)
     return LIB
 
 

@@ -60,7 +60,8 @@ struct Plan {
   int vc = 0;          // chunk_tiles * 256
   int ld_v = 0;        // leading dimension of the [*, vc] scratch matrices
   int ld_t = 0;        // leading dimension of the [*, t_cap] scratch matrices
-  size_t ctl, counters, flag, c_tok, a_tok, rows, pos, yc, zy, lse2, coefc, lossterm;
+  int queue_words = 0; // tile-queue counters (8 per persistent launch)
+  size_t ctl, counters, queue, flag, c_tok, a_tok, rows, pos, yc, zy, lse2, coefc, lossterm;
   size_t part_m, part_s, part_u, Hc, HcT, Wc, dS, dST, WT, dHacc;
   size_t total = 0;
 };
@@ -118,6 +119,7 @@ int32_t make_plan(int64_t T, int64_t d, int64_t V, int32_t S, const pg_params* p
   pl.part_u = take((size_t)tiles_v * t_cap * 4);
   pl.Hc = take((size_t)t_cap * kd * 2);
   pl.Wc = pl.is_f32 ? take((size_t)V * kd * 2) : 0;
+  pl.queue_words = pg::QUEUE_SET_WORDS * pg::queue_sets(0);
   if (which == PG_CALL_LOSS_FWD_BWD) {
     int64_t max_tiles = t_cap > 0 ? (int64_t)(ds_budget() / ((uint64_t)t_cap * 2 * 256)) : tiles_v;
     if (max_tiles < 1) max_tiles = 1;
@@ -148,7 +150,9 @@ int32_t make_plan(int64_t T, int64_t d, int64_t V, int32_t S, const pg_params* p
     pl.dST = take((size_t)vc * ld_t * 2);
     pl.WT = take((size_t)d * ld_v * 2);
     pl.dHacc = take((size_t)t_cap * d * 4);
+    pl.queue_words = pg::QUEUE_SET_WORDS * pg::queue_sets((int)nchunks);
   }
+  pl.queue = take((size_t)pl.queue_words * sizeof(unsigned));
   pl.total = off > 0 ? off : ALIGN;
   return PG_OK;
 }
@@ -276,6 +280,7 @@ void run_forward(const Plan& pl, const pg_params& p, void* ws, const void* H, co
   f.yc = at<int>(ws, pl.yc); f.zy = at<float>(ws, pl.zy);
   f.part_m = at<float>(ws, pl.part_m); f.part_s = at<float>(ws, pl.part_s); f.part_u = at<float>(ws, pl.part_u);
   f.ctl = at<pg::Ctl>(ws, pl.ctl);
+  f.queue = at<unsigned>(ws, pl.queue);
   if (!comb.partials_in) { ProfScope ps(PG_KERNEL_FWD, st); pg::launch_lmhead_fwd(f, st); }
 
   comb.tiles_v = comb.partials_in ? 0 : pl.tiles_v; comb.t_cap = pl.t_cap;
@@ -291,6 +296,7 @@ pg::PrepArgs base_prep(const Plan& pl, void* ws) {
   a.flag = at<uint8_t>(ws, pl.flag); a.c_tok = at<float>(ws, pl.c_tok); a.a_tok = at<float>(ws, pl.a_tok);
   a.rows = at<int>(ws, pl.rows); a.pos = at<int>(ws, pl.pos); a.zy = at<float>(ws, pl.zy);
   a.counters = at<unsigned long long>(ws, pl.counters); a.ctl = at<pg::Ctl>(ws, pl.ctl);
+  a.queue = at<unsigned>(ws, pl.queue); a.queue_words = pl.queue_words;
   return a;
 }
 
@@ -688,6 +694,8 @@ int32_t loss_fwd_bwd(int sft, const void* H, const void* W, const int32_t* y, co
     g.scale = (float)(LOG2E / (double)p.temperature);
     g.yc = at<int>(ws, pl.yc); g.lse2 = at<float>(ws, pl.lse2); g.coefc = at<float>(ws, pl.coefc);
     g.dS = at<__bf16>(ws, pl.dS); g.dST = at<__bf16>(ws, pl.dST); g.ctl = ctl;
+    unsigned* const queues = at<unsigned>(ws, pl.queue) + pg::QUEUE_SET_WORDS * (1 + 3 * c);
+    g.queue = queues;
     { ProfScope ps(PG_KERNEL_DLOGITS, st); pg::launch_lmhead_dlogits(g, st); }
 
     pg::StoreArgs w{};   // dW[v0 + m, :] = sum_t dS^T[m, t] H^T[:, t]
@@ -697,6 +705,7 @@ int32_t loss_fwd_bwd(int sft, const void* H, const void* W, const int32_t* y, co
     w.tiles_m = tiles_c; w.tiles_n = (d_i + 255) / 256;
     w.C = static_cast<char*>(dW) + (size_t)v0 * pl.d * dw_elem; w.ldc = d_i;
     w.accumulate = p.accumulate_dW; w.out_bf16 = p.dW_dtype; w.k_from_ctl = 1; w.m_from_ctl = 0; w.ctl = ctl;
+    w.queue = queues + pg::QUEUE_SET_WORDS;
     { ProfScope ps(PG_KERNEL_DW, st); pg::launch_gemm_store(w, st); }
 
     pg::StoreArgs h{};   // dHacc[t, :] (+)= sum_v dS[t, v] W^T[:, v]
@@ -706,6 +715,7 @@ int32_t loss_fwd_bwd(int sft, const void* H, const void* W, const int32_t* y, co
     h.tiles_m = pl.tiles_t; h.tiles_n = (d_i + 255) / 256;
     h.C = at<float>(ws, pl.dHacc); h.ldc = d_i;
     h.accumulate = c > 0; h.out_bf16 = 0; h.k_from_ctl = 0; h.m_from_ctl = 1; h.split_k = 1; h.ctl = ctl;
+    h.queue = queues + 2 * pg::QUEUE_SET_WORDS;
     { ProfScope ps(PG_KERNEL_DH, st); pg::launch_gemm_store(h, st); }
   }
 

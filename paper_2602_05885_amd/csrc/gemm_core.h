@@ -298,6 +298,236 @@ __device__ __forceinline__ void mainloop(const TileLoader& LA, const TileLoader&
   asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
+// ---- the same main loop as a stream of tiles (persistent workgroups) -------------------------------
+// A persistent workgroup walks a sequence of tiles that share the operands' leading dimensions
+// and the contraction length.  The per-lane offsets are then the same for every tile (OperandLanes);
+// what changes from tile to tile is the wave-uniform base address and byte range (TileSrc).  The
+// stage schedule above keeps two stages of loads in flight, and across a tile boundary those are
+// simply the first two stages of the next tile: the load stream never drains, the next tile's
+// stage 0 has landed and most of its stage 1 is in flight when the current tile's last MFMA
+// retires, and the epilogue runs with those loads in flight.  The epilogue must therefore not touch
+// the two stage buffers (the first 2 x STAGE_BYTES of the dynamic LDS).
+struct OperandLanes {
+  uint32_t voff[CHUNKS];
+  __device__ __forceinline__ void init(int ld_elems, int tid) {
+    const int lane = tid & 63, wave = tid >> 6;
+#pragma unroll
+    for (int i = 0; i < CHUNKS; ++i) {
+      const int row = (i * NW + wave) * 8 + (lane >> 3);
+      const int chunk = (lane & 7) ^ ((row >> 1) & 7);
+      voff[i] = (uint32_t)row * (uint32_t)ld_elems * 2u + (uint32_t)chunk * 16u;
+    }
+  }
+};
+
+struct TileSrc {
+  uint32_t lo, hi, bytes;       // wave-uniform (scalar registers)
+  // rows [row0, row0 + 256) of an operand with rows_total rows of ld_elems elements, from byte
+  // k_byte0 of each row on; rows beyond rows_total read as zero; bytes = 0 switches the loads off
+  __device__ __forceinline__ void set(const void* base_, int rows_total, int row0, int ld_elems, uint32_t k_byte0) {
+    const int rows = min(max(rows_total - row0, 0), BM);
+    const uint64_t b = reinterpret_cast<uint64_t>(base_) + (uint64_t)row0 * (uint64_t)ld_elems * 2u + k_byte0;
+    lo = __builtin_amdgcn_readfirstlane((uint32_t)b);
+    hi = __builtin_amdgcn_readfirstlane((uint32_t)(b >> 32));
+    bytes = __builtin_amdgcn_readfirstlane(rows > 0 ? (uint32_t)rows * (uint32_t)ld_elems * 2u - k_byte0 : 0u);
+  }
+  __device__ __forceinline__ void off() { lo = 0; hi = 0; bytes = 0; }
+  __device__ __forceinline__ __amdgpu_buffer_rsrc_t rsrc() const {
+    return __builtin_amdgcn_make_buffer_rsrc(reinterpret_cast<void*>(((uint64_t)hi << 32) | lo), 0, bytes, 0x00020000);
+  }
+};
+
+__device__ __forceinline__ void issue_lds(__amdgpu_buffer_rsrc_t r, const OperandLanes& L, int i, uint32_t k_byte_off,
+                                          char* slab, int wave) {
+  char* dst = slab + (i * NW + wave) * 1024;
+  __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (lds_void*)dst, 16, L.voff[i], k_byte_off, 0, 0);
+}
+
+// Buffer resource and k byte offset of stage g (counted from this tile's stage 0) of the stream:
+// stages 0 .. nk-1 belong to this tile, nk and nk+1 to the next one (nk >= 2).  All of it is
+// wave-uniform and stays in scalar registers; the sources are passed as plain values for that.
+__device__ __forceinline__ void pick_stage(const TileSrc cur, const TileSrc nxt, int g, int nk,
+                                           __amdgpu_buffer_rsrc_t& r, uint32_t& kb) {
+  const bool ahead = g >= nk;
+  kb = (uint32_t)(ahead ? g - nk : g) * (BK * 2);
+  TileSrc t;
+  t.lo = __builtin_amdgcn_readfirstlane(ahead ? +nxt.lo : +cur.lo);
+  t.hi = __builtin_amdgcn_readfirstlane(ahead ? +nxt.hi : +cur.hi);
+  t.bytes = __builtin_amdgcn_readfirstlane(ahead ? +nxt.bytes : +cur.bytes);
+  r = t.rsrc();
+}
+
+// One tile of the stream: acc += A(256 x K) B(256 x K)^T with K = 64 nk.
+//   A0, B0    operand sources of this tile; A1, B1 of the next one (bytes = 0 where the stream
+//             ends).  A tile of a single stage (nk = 1) cannot run ahead by two stages: the caller
+//             then passes switched-off next sources, cold = true for every tile, and waits for
+//             vmcnt(0) and a barrier before the next call.
+//   cold      the stream starts here: nothing of this tile is in flight yet
+//   par0      stage buffer (0 / 1) that holds, or will hold, this tile's stage 0; the next tile's is
+//             (par0 + nk) & 1
+// On return the first two stages of the next tile are in the stage buffers or on their way (this
+// wavefront's newest CHUNKS + BH loads may still be in flight) and nobody reads the buffers until the
+// next call's opening barrier.
+__device__ __forceinline__ void mainloop_stream(const OperandLanes& VA, const OperandLanes& VB, const TileSrc A0,
+                                                const TileSrc B0, const TileSrc A1, const TileSrc B1, int nk,
+                                                bool cold, int par0, char* smem,
+                                                f32x4 (&acc)[GM][GN]) {
+  constexpr int NS = 2 * GN, TAIL = 2, XS = 4, BH = CHUNKS / 2;
+  static_assert(CHUNKS == 4 && BH <= XS && XS + CHUNKS < NS - TAIL, "load schedule");
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave / WN, wn = wave % WN;
+  const int lrow = lane & 15;
+  const int xr = (lane >> 1) & 7;
+  const uint32_t a_off = (uint32_t)(wm * WROWS + lrow) * 128u;
+  const uint32_t b_off = (uint32_t)(wn * WCOLS + lrow) * 128u + SLAB_BYTES;
+  uint32_t koff[2];
+#pragma unroll
+  for (int ks = 0; ks < 2; ++ks) koff[ks] = (uint32_t)(((ks * 4 + (lane >> 4)) ^ xr) << 4);
+
+  bf16x8 a[2][GM], bq[4];
+  auto rdA = [&](const char* st, int ks, int i) -> bf16x8 {
+    return *reinterpret_cast<const bf16x8*>(st + a_off + i * (16 * 128) + koff[ks]);
+  };
+  auto rdB = [&](const char* st, int s) -> bf16x8 {
+    return *reinterpret_cast<const bf16x8*>(st + b_off + (s % GN) * (16 * 128) + koff[s / GN]);
+  };
+
+  if (cold) {   // stage 0 complete, A and the first half of B of stage 1
+    char* s0 = smem + par0 * STAGE_BYTES;
+    char* s1 = smem + (par0 ^ 1) * STAGE_BYTES;
+    __amdgpu_buffer_rsrc_t ra, rb;
+    uint32_t kb;
+    pick_stage(A0, A1, 0, nk, ra, kb);
+    pick_stage(B0, B1, 0, nk, rb, kb);
+#pragma unroll
+    for (int i = 0; i < CHUNKS; ++i) issue_lds(ra, VA, i, 0, s0, wave);
+#pragma unroll
+    for (int i = 0; i < CHUNKS; ++i) issue_lds(rb, VB, i, 0, s0 + SLAB_BYTES, wave);
+    pick_stage(A0, A1, 1, nk, ra, kb);
+    pick_stage(B0, B1, 1, nk, rb, kb);
+#pragma unroll
+    for (int i = 0; i < CHUNKS; ++i) issue_lds(ra, VA, i, kb, s1, wave);
+#pragma unroll
+    for (int i = 0; i < BH; ++i) issue_lds(rb, VB, i, kb, s1 + SLAB_BYTES, wave);
+  }
+  // stage 0 has landed: all but this wavefront's CHUNKS + BH newest loads are complete
+  asm volatile("s_waitcnt vmcnt(6)\n\ts_barrier" ::: "memory");
+  {
+    const char* s0 = smem + par0 * STAGE_BYTES;
+    bq[0] = rdB(s0, 0);
+#pragma unroll
+    for (int i = 0; i < GM; ++i) a[0][i] = rdA(s0, 0, i);
+    bq[1] = rdB(s0, 1);
+  }
+
+  for (int kt = 0; kt < nk; ++kt) {
+    char* cur = smem + ((par0 + kt) & 1) * STAGE_BYTES;
+    char* nxt = smem + ((par0 + kt + 1) & 1) * STAGE_BYTES;
+    __amdgpu_buffer_rsrc_t rb1, ra2, rb2;
+    uint32_t kb1, kb2, kb2b;
+    pick_stage(B0, B1, kt + 1, nk, rb1, kb1);
+    pick_stage(A0, A1, kt + 2, nk, ra2, kb2);
+    pick_stage(B0, B1, kt + 2, nk, rb2, kb2b);
+#pragma unroll
+    for (int s = 0; s < NS - TAIL; ++s) {
+      const int ks = s / GN, j = s % GN;
+      bq[(s + 2) & 3] = rdB(cur, s + 2);
+      if (s < GM) a[1][s] = rdA(cur, 1, s);
+      if (s < BH) issue_lds(rb1, VB, BH + s, kb1, nxt + SLAB_BYTES, wave);
+      if (s > XS && s <= XS + CHUNKS) issue_lds(ra2, VA, s - XS - 1, kb2, cur, wave);
+#pragma unroll
+      for (int i = 0; i < GM; ++i)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[ks][i], bq[s & 3], acc[i][j], 0, 0, 0);
+      if (s == XS) asm volatile("s_waitcnt lgkmcnt(1)\n\ts_barrier" ::: "memory");   // barrier X
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    asm volatile("s_waitcnt vmcnt(4) lgkmcnt(0)\n\ts_barrier" ::: "memory");          // barrier Y
+#pragma unroll
+    for (int m = 0; m < TAIL * GM; ++m) {
+      const int s = NS - TAIL + m / GM, i = m % GM;
+      const int ks = s / GN, j = s % GN;
+      if (m == 0) bq[0] = rdB(nxt, 0);
+      else if (m <= GM) a[0][m - 1] = rdA(nxt, 0, m - 1);
+      else if (m == GM + 1) bq[1] = rdB(nxt, 1);
+      if (m % GM == 0) issue_lds(rb2, VB, m / GM, kb2b, cur + SLAB_BYTES, wave);
+      acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[ks][i], bq[s & 3], acc[i][j], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  }
+}
+
+// ---- tile queue of the persistent kernels ----------------------------------------------------------
+// The eight XCDs of the chip run at different clocks under load (each has its own frequency
+// control: 1.58 to 1.80 GHz were measured side by side in one launch), so an equal share of the
+// tiles per XCD (which is what the hardware dispatcher hands out: workgroup b runs on XCD b mod 8)
+// makes a launch as slow as its slowest XCD.  The MFMA kernels are therefore persistent (one
+// workgroup per compute unit) and take their tiles from a queue: XCD y owns the tiles that the
+// XCD-aware order (map_tile / map_tile_interleaved) gives to the workgroups b = 8 i + y,
+// i = 0 .. n_y - 1; its workgroups take them in that order with one atomic increment of cnt[y], and
+// once its share is used up they take tiles from the XCD that has most left.  Which workgroup
+// computes a tile does not change the tile's result, so results stay bitwise repeatable.
+// cnt[0..7] must be zero at launch.
+struct TileQueue {
+  unsigned* cnt;
+  int total;          // tiles of the launch
+  int interleaved;    // 0: map_tile order, 1: map_tile_interleaved order
+  int home;           // XCD this workgroup runs on
+
+  __device__ __forceinline__ void init(unsigned* cnt_, int total_, int interleaved_) {
+    cnt = cnt_; total = total_; interleaved = interleaved_;
+    unsigned x;
+    asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(x));
+    home = (int)(x & 7u);
+  }
+  // n_y: how many workgroup indices b = 8 i + y map to a tile
+  __device__ __forceinline__ int share(int y) const {
+    if (!interleaved) {
+      const int per = (total + 7) / 8;
+      return min(max(total - y * per, 0), per);
+    }
+    const int full = (total / 256) * 256, rem = total - full, per = (rem + 7) / 8;
+    return full / 8 + min(max(rem - y * per, 0), per);
+  }
+  // the workgroup index that map_tile / map_tile_interleaved would have seen for entry i of XCD y
+  static __device__ __forceinline__ int encode(int y, int i) { return (i << 3) | y; }
+
+  // Issues the claim on the home share; the ticket is resolved later, so that the atomic's latency
+  // hides behind whatever runs in between.  (atomicInc with the largest bound is an add of one; unlike
+  // atomicAdd the compiler does not turn it into a wave-wide reduction that needs the result at once.)
+  __device__ __forceinline__ unsigned ticket() const { return atomicInc(cnt + home, 0xffffffffu); }
+
+  // Workgroup index (see encode) of the claimed tile, or -1 when no tile is left anywhere.  Every failed
+  // attempt means one more XCD's share is used up, so the loop ends after at most nine rounds.
+  // steal = false confines every XCD to its own share (used by the measurement tool only).
+  __device__ __forceinline__ int resolve(unsigned tk, bool steal = true) const {
+    if ((int)min(tk, 0x40000000u) < share(home)) return encode(home, (int)tk);
+    if (!steal) return -1;
+    for (int attempt = 0; attempt < 9; ++attempt) {
+      int best = -1, best_left = 0;
+      for (int y = 0; y < 8; ++y) {
+        const unsigned c = __hip_atomic_load(cnt + y, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const int left = share(y) - (int)min(c, 0x40000000u);
+        if (left > best_left) { best_left = left; best = y; }
+      }
+      if (best < 0) return -1;
+      const unsigned t = atomicInc(cnt + best, 0xffffffffu);
+      if ((int)min(t, 0x40000000u) < share(best)) return encode(best, (int)t);
+    }
+    return -1;
+  }
+};
+
+// Thread 0 claims, everybody learns the claim through one LDS word.  `slot` must lie outside whatever the
+// kernel's epilogue uses; the call contains a workgroup barrier (LDS only: vector memory operations
+// in flight are not waited for).
+__device__ __forceinline__ int queue_broadcast(volatile int* slot, int value_of_thread0) {
+  if (threadIdx.x == 0) *slot = value_of_thread0;
+  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+  const int v = __builtin_amdgcn_readfirstlane(*slot);
+  return v;
+}
+
 // Row (m) index inside a 16x16 MFMA tile of accumulator register r for this lane;
 // the column (n) is lane & 15.
 __device__ __forceinline__ int acc_row(int r, int lane) { return ((lane >> 4) << 2) + r; }

@@ -7,6 +7,11 @@ namespace pg {
 
 struct Ctl;
 
+// Tile-queue counters in the workspace: one set of 8 (one per XCD) for every persistent launch of a
+// call (the forward, then recompute / dW / dH of every vocab chunk), all cleared by the pre-pass.
+constexpr int QUEUE_SET_WORDS = 8;
+inline int queue_sets(int nchunks) { return 1 + 3 * nchunks; }
+
 // ---- MFMA kernels ---------------------------------------------------------------------
 struct FwdArgs {
   const void* W;        // [V, ldw] bf16
@@ -24,6 +29,7 @@ struct FwdArgs {
   float* part_s;
   float* part_u;
   const Ctl* ctl;
+  unsigned* queue;      // [8] tile counters of this launch's queue, zero at launch
 };
 
 struct DlogitsArgs {
@@ -45,6 +51,7 @@ struct DlogitsArgs {
   __bf16* dS;           // [t_cap, ld_s]
   __bf16* dST;          // [vc, ld_t]
   const Ctl* ctl;
+  unsigned* queue;      // [8] tile counters of this launch's queue, zero at launch
 };
 
 struct StoreArgs {
@@ -62,6 +69,7 @@ struct StoreArgs {
   int m_from_ctl;       // row extent        = padded active-token count
   int split_k;          // with m_from_ctl: cut K into dh_split() parts, part p writes rows p n_pad + m
   const Ctl* ctl;
+  unsigned* queue;      // [8] tile counters of this launch's queue, zero at launch
 };
 
 hipError_t init_gemm_kernels();
@@ -104,6 +112,8 @@ struct PrepArgs {
   int* pos;                  // [T]
   float* zy;                 // [t_cap]
   unsigned long long* counters; // [8]
+  unsigned* queue;           // [queue_words] tile-queue counters of the persistent kernels, cleared here
+  int queue_words;
   Ctl* ctl;
   // per-row outputs to clear
   float* out0; float* out1; float* out2;

@@ -7,6 +7,8 @@
 // wavefront hold the other 48 rows of the same columns.  The two logits kernels put the
 // vocabulary on the rows (a token's statistics then reduce inside a lane first); the store
 // kernel puts the output's contiguous dimension there (4 consecutive elements per lane).
+#include <cstdlib>
+
 #include "kernels.h"
 #include "gemm_core.h"
 
@@ -29,92 +31,166 @@ __device__ __forceinline__ void merge_state(float& m, float& s, float& u, float 
 constexpr float NEG_BIG = -0x1p100f;
 
 // ------------------------------------------------------------------------------------
-// Forward: one workgroup = 256 vocab rows x 256 compacted tokens.  The logits live only in
-// the accumulators; what leaves the kernel is one (m, s, u) triple per token and vocab
-// tile, plus the scaled logit of the sampled token.
+// Forward: a tile is 256 vocab rows x 256 compacted tokens.  The logits live only in the
+// accumulators; what leaves the kernel is one (m, s, u) triple per token and vocab tile, plus the
+// scaled logit of the sampled token.
+// Persistent: one workgroup per compute unit takes tiles from the XCD-aware queue (gemm_core.h)
+// until none is left.  The operand loads of the next tile run ahead through the tile boundary
+// (mainloop_stream), so the statistics epilogue of a tile executes while the first two stages of
+// the next one arrive, and a tile costs no launch, no cold prologue and no drain.  A workgroup
+// always knows its next tile (the loads need it) and has the claim for the one after that in
+// flight.  LDS: the two stage buffers, then the cross-wavefront merge array, the sampled-token ids
+// of the tile (double-buffered; loaded one tile ahead so that the epilogue waits on no global load)
+// and the words that hand the claimed tiles to all wavefronts.
 // ------------------------------------------------------------------------------------
-__global__ __launch_bounds__(NTHREADS) void lmhead_fwd_kernel(FwdArgs a) {
-  const Ctl ctl = *a.ctl;
-  int tm, tn;
-  // the live token tiles are known only on the device; the grid covers the host-side maximum
-  if (!map_tile(blockIdx.x, a.tiles_v, min(a.tiles_t, ctl.n_pad / BN), tm, tn)) return;
+constexpr int FWD_RED_OFF = 2 * STAGE_BYTES;                 // [WM][256 tokens][3] floats
+constexpr int FWD_STASH_OFF = FWD_RED_OFF + WM * 256 * 3 * 4; // [2][256] ints
+constexpr int FWD_CLAIM_OFF = FWD_STASH_OFF + 2 * 256 * 4;    // [4] ints
+constexpr int FWD_LDS_BYTES = FWD_CLAIM_OFF + 16;
 
+// PROBE = true (the stand-alone measurement tool only) records wall-clock and shader-clock stamps of
+// tiles PROBE_FIRST .. PROBE_FIRST + PROBE_TILES - 1 of every workgroup in tl[wg][tile][4] (main loop
+// start, main loop end, epilogue end, shader clock at the epilogue's end) and lets the tool switch the
+// stealing between XCDs off; the library instantiates PROBE = false, which compiles to none of it.
+constexpr int PROBE_FIRST = 150, PROBE_TILES = 16;
+
+template <bool PROBE>
+__device__ __forceinline__ void lmhead_fwd_body(const FwdArgs& a, bool steal, unsigned long long* tl) {
+  const Ctl ctl = *a.ctl;
+  const int tiles_t = min(a.tiles_t, ctl.n_pad / BN);          // live token tiles: known only on the device
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WN, wn = wave % WN;
+  TileQueue Q;
+  Q.init(a.queue, a.tiles_v * tiles_t, 0);
+  float* red = reinterpret_cast<float*>(g_smem + FWD_RED_OFF);
+  int* stash = reinterpret_cast<int*>(g_smem + FWD_STASH_OFF);
+  volatile int* claim = reinterpret_cast<volatile int*>(g_smem + FWD_CLAIM_OFF);
 
-  TileLoader LA, LB;
-  LA.init(a.W, a.w_rows, tm * BM, a.ldw, 0u, tid);
-  LB.init(a.Hc, a.h_rows, tn * BN, a.ldh, 0u, tid);
-  f32x4 acc[GM][GN];
-  zero_acc(acc);
-  mainloop(LA, LB, a.K / BK, g_smem, acc);
+  // the first two tiles
+  if (tid == 0) {
+    const unsigned k0 = Q.ticket(), k1 = Q.ticket();
+    claim[0] = Q.resolve(k0, steal);
+    claim[1] = Q.resolve(k1, steal);
+  }
+  __syncthreads();
+  const int b_cur = __builtin_amdgcn_readfirstlane(claim[0]), b_nxt = __builtin_amdgcn_readfirstlane(claim[1]);
+  if (b_cur < 0) return;
+  int tm, tn, tm1 = 0, tn1 = 0;
+  map_tile(b_cur, a.tiles_v, tiles_t, tm, tn);
+  bool more = b_nxt >= 0;
+  if (more) map_tile(b_nxt, a.tiles_v, tiles_t, tm1, tn1);
+  OperandLanes VA, VB;
+  VA.init(a.ldw, tid);
+  VB.init(a.ldh, tid);
+  const bool ahead = a.K / BK >= 2;        // single-stage tiles cannot run two stages ahead
+  TileSrc A0, B0, A1, B1;
+  A0.set(a.W, a.w_rows, tm * BM, a.ldw, 0u);
+  B0.set(a.Hc, a.h_rows, tn * BN, a.ldh, 0u);
+  A1.set(a.W, (more && ahead) ? a.w_rows : 0, tm1 * BM, a.ldw, 0u);
+  B1.set(a.Hc, (more && ahead) ? a.h_rows : 0, tn1 * BN, a.ldh, 0u);
+  const int nk = a.K / BK;
+  if (tid < BN) stash[tid] = a.yc[tn * BN + tid];     // visible to everybody behind the main loop's barriers
+  int par = 0;
 
-  const int v_base = tm * BM + wm * WROWS;            // first vocab row of this wavefront's block
-  const bool ragged = (tm * BM + BM > a.V);
-  float* red = reinterpret_cast<float*>(g_smem);      // [WM][256 tokens][3]
+  for (int n = 0;; ++n) {
+    const int* ys = stash + (n & 1) * BN;
+    f32x4 acc[GM][GN];
+    zero_acc(acc);
+    const bool probe = PROBE && tl && tid == 0 && n >= PROBE_FIRST && n < PROBE_FIRST + PROBE_TILES;
+    unsigned long long* stamp = probe ? tl + ((size_t)blockIdx.x * PROBE_TILES + (n - PROBE_FIRST)) * 4 : nullptr;
+    if (probe) stamp[0] = wall_clock64();
+    mainloop_stream(VA, VB, A0, B0, A1, B1, nk, n == 0 || !ahead, par, g_smem, acc);
+    par = (par + nk) & 1;
+    if (probe) stamp[1] = wall_clock64();
+    if (!ahead) asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
+    // claim the tile after the next one: issued here, behind the main loop's last loads (memory
+    // operations return in order, an atomic in front of them would hold up their completion), and
+    // picked up at the end of the epilogue.  (Left uninitialised on the other threads on purpose: a
+    // merged value would make the compiler wait for the atomic right here.)
+    unsigned ticket;
+    if (tid == 0 && more) ticket = Q.ticket();
+    // the next tile's token ids: fetched now, parked in LDS before this tile's stores are issued, so
+    // that neither this epilogue nor the next one waits on memory
+    int y_next = 0;
+    if (more && tid < BN) y_next = a.yc[tn1 * BN + tid];
 
+    const int v_base = tm * BM + wm * WROWS;            // first vocab row of this wavefront's block
+    const bool ragged = (tm * BM + BM > a.V);
 #pragma unroll
-  for (int j = 0; j < GN; ++j) {
-    const int tok_l = wn * WCOLS + j * 16 + (lane & 15);
-    const int tok = tn * BN + tok_l;
-    // max over the raw accumulators (scale > 0 keeps the order); the scale goes on inside the fma
-    float mr = NEG_BIG;
-#pragma unroll
-    for (int i = 0; i < GM; ++i)
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        if (ragged && (v_base + i * 16 + acc_row(r, lane) >= a.V)) acc[i][j][r] = NEG_BIG;
-        mr = fmaxf(mr, acc[i][j][r]);
-      }
-    float mx = mr * a.scale;
-    const float nmx = -mx;
-    float s = 0.f, u = 0.f;
-#pragma unroll
-    for (int i = 0; i < GM; ++i)
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const float dlt = fmaf(acc[i][j][r], a.scale, nmx);
-        const float e = __builtin_amdgcn_exp2f(dlt);
-        s += e;
-        u = fmaf(e, dlt, u);
-      }
-    // sampled token's logit: at most one lane of the whole grid owns (tok, y[tok])
-    const int ytok = a.yc[tok];
-    const int yrel = ytok - v_base;
-    const bool mine = (yrel >= 0) && (yrel < WROWS) && (ytok < a.V) && (((yrel >> 2) & 3) == (lane >> 4));
-    if (__any(mine)) {
-      float zy = 0.f;
+    for (int j = 0; j < GN; ++j) {
+      const int tok_l = wn * WCOLS + j * 16 + (lane & 15);
+      const int tok = tn * BN + tok_l;
+      float mr = NEG_BIG;
 #pragma unroll
       for (int i = 0; i < GM; ++i)
 #pragma unroll
-        for (int r = 0; r < 4; ++r)
-          if (yrel == i * 16 + acc_row(r, lane)) zy = acc[i][j][r] * a.scale;
-      if (mine) a.zy[tok] = zy;
-    }
-    // the other three 16-lane groups hold the other vocab rows of the same token
+        for (int r = 0; r < 4; ++r) {
+          if (ragged && (v_base + i * 16 + acc_row(r, lane) >= a.V)) acc[i][j][r] = NEG_BIG;
+          mr = fmaxf(mr, acc[i][j][r]);
+        }
+      float mx = mr * a.scale;
+      const float nmx = -mx;
+      float s = 0.f, u = 0.f;
 #pragma unroll
-    for (int sh = 16; sh <= 32; sh <<= 1) {
-      const float m2 = __shfl_xor(mx, sh), s2 = __shfl_xor(s, sh), u2 = __shfl_xor(u, sh);
-      merge_state(mx, s, u, m2, s2, u2);
-    }
-    if (lane < 16) {
-      float* p = red + (wm * 256 + tok_l) * 3;
-      p[0] = mx; p[1] = s; p[2] = u;
-    }
-  }
-  __syncthreads();
-  if (tid < BN) {
-    const float* p0 = red + tid * 3;
-    float m = p0[0], s = p0[1], u = p0[2];
+      for (int i = 0; i < GM; ++i)
 #pragma unroll
-    for (int w = 1; w < WM; ++w) {
-      const float* p1 = red + (w * 256 + tid) * 3;
-      merge_state(m, s, u, p1[0], p1[1], p1[2]);
+        for (int r = 0; r < 4; ++r) {
+          const float dlt = fmaf(acc[i][j][r], a.scale, nmx);
+          const float e = __builtin_amdgcn_exp2f(dlt);
+          s += e;
+          u = fmaf(e, dlt, u);
+        }
+      const int ytok = ys[tok_l];
+      const int yrel = ytok - v_base;
+      const bool mine = (yrel >= 0) && (yrel < WROWS) && (ytok < a.V) && (((yrel >> 2) & 3) == (lane >> 4));
+      if (__any(mine)) {
+        float zy = 0.f;
+#pragma unroll
+        for (int i = 0; i < GM; ++i)
+#pragma unroll
+          for (int r = 0; r < 4; ++r)
+            if (yrel == i * 16 + acc_row(r, lane)) zy = acc[i][j][r] * a.scale;
+        if (mine) a.zy[tok] = zy;
+      }
+#pragma unroll
+      for (int sh = 16; sh <= 32; sh <<= 1) {
+        const float m2 = __shfl_xor(mx, sh), s2 = __shfl_xor(s, sh), u2 = __shfl_xor(u, sh);
+        merge_state(mx, s, u, m2, s2, u2);
+      }
+      if (lane < 16) {
+        float* p = red + (wm * 256 + tok_l) * 3;
+        p[0] = mx; p[1] = s; p[2] = u;
+      }
     }
-    const size_t o = (size_t)tm * a.t_cap + (size_t)tn * BN + tid;
-    a.part_m[o] = m; a.part_s[o] = s; a.part_u[o] = u;
+    if (tid == 0) claim[2] = more ? Q.resolve(ticket, steal) : -1;
+    // LDS-only synchronisation: a full __syncthreads() would also wait for the next tile's loads
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    const int b_nn = __builtin_amdgcn_readfirstlane(claim[2]);
+    if (tid < BN) {
+      stash[((n + 1) & 1) * BN + tid] = y_next;
+      const float* p0 = red + tid * 3;
+      float m = p0[0], s = p0[1], u = p0[2];
+#pragma unroll
+      for (int w = 1; w < WM; ++w) {
+        const float* p1 = red + (w * 256 + tid) * 3;
+        merge_state(m, s, u, p1[0], p1[1], p1[2]);
+      }
+      const size_t o = (size_t)tm * a.t_cap + (size_t)tn * BN + tid;
+      a.part_m[o] = m; a.part_s[o] = s; a.part_u[o] = u;
+    }
+    if (probe) { stamp[2] = wall_clock64(); stamp[3] = clock64(); }
+    if (!more) break;
+    tm = tm1; tn = tn1;
+    A0.set(a.W, a.w_rows, tm * BM, a.ldw, 0u);
+    B0.set(a.Hc, a.h_rows, tn * BN, a.ldh, 0u);
+    more = b_nn >= 0;
+    if (more) map_tile(b_nn, a.tiles_v, tiles_t, tm1, tn1);
+    A1.set(a.W, (more && ahead) ? a.w_rows : 0, tm1 * BM, a.ldw, 0u);
+    B1.set(a.Hc, (more && ahead) ? a.h_rows : 0, tn1 * BN, a.ldh, 0u);
   }
 }
+
+__global__ __launch_bounds__(NTHREADS) void lmhead_fwd_kernel(FwdArgs a) { lmhead_fwd_body<false>(a, true, nullptr); }
 
 // ------------------------------------------------------------------------------------
 // Backward recompute: the same contraction, finished with
@@ -123,14 +199,23 @@ __global__ __launch_bounds__(NTHREADS) void lmhead_fwd_kernel(FwdArgs a) {
 // (dS [t_cap, ld_s] for dH, dS^T [vc, ld_t] for dW).  Both go through an LDS transposition
 // stage so that global stores are 16 B per lane and 512 B per row.
 // ------------------------------------------------------------------------------------
+constexpr int DLOGITS_CLAIM_OFF = GEMM_LDS_BYTES;      // behind the epilogue's staging area
+constexpr int DLOGITS_LDS_BYTES = DLOGITS_CLAIM_OFF + 16;
+
 __global__ __launch_bounds__(NTHREADS) void lmhead_dlogits_kernel(DlogitsArgs a) {
   const Ctl ctl = *a.ctl;
-  int tm, tn;
-  // the live token tiles are known only on the device; the grid covers the host-side maximum
-  if (!map_tile(blockIdx.x, a.tiles_v, min(a.tiles_t, ctl.n_pad / BN), tm, tn)) return;
-
+  const int tiles_t = min(a.tiles_t, ctl.n_pad / BN);   // live token tiles: known only on the device
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WN, wn = wave % WN;
+  TileQueue Q;
+  Q.init(a.queue, a.tiles_v * tiles_t, 0);
+  volatile int* claim = reinterpret_cast<volatile int*>(g_smem + DLOGITS_CLAIM_OFF);
+  int b = queue_broadcast(claim, tid == 0 ? Q.resolve(Q.ticket()) : 0);
+
+  // persistent: one workgroup per compute unit takes tiles from the XCD-aware queue until none is left
+  while (b >= 0) {
+  int tm, tn;
+  map_tile(b, a.tiles_v, tiles_t, tm, tn);
 
   TileLoader LA, LB;
   LA.init(a.W, a.w_rows, a.v0 + tm * BM, a.ldw, 0u, tid);
@@ -138,6 +223,11 @@ __global__ __launch_bounds__(NTHREADS) void lmhead_dlogits_kernel(DlogitsArgs a)
   f32x4 acc[GM][GN];
   zero_acc(acc);
   mainloop(LA, LB, a.K / BK, g_smem, acc);
+  // claim the next tile: issued behind the main loop's loads (memory operations return in order) and
+  // picked up after the exponentials.  (Left uninitialised on the other threads on purpose: a merged
+  // value would make the compiler wait for the atomic right here.)
+  unsigned ticket;
+  if (tid == 0) ticket = Q.ticket();
 
   const int v_base = a.v0 + tm * BM + wm * WROWS;     // global vocab index
   const bool ragged = (a.v0 + tm * BM + BM > a.V);
@@ -194,6 +284,7 @@ __global__ __launch_bounds__(NTHREADS) void lmhead_dlogits_kernel(DlogitsArgs a)
       *reinterpret_cast<uint2*>(st + tok_l * EPI_STRIDE + v_l * 2) = two;
     }
   }
+  if (tid == 0) claim[0] = Q.resolve(ticket);       // before this tile's stores, whose completion it would wait for
   __syncthreads();
   {
     const int chunk = tid & 31, r0 = tid >> 5;
@@ -245,6 +336,10 @@ __global__ __launch_bounds__(NTHREADS) void lmhead_dlogits_kernel(DlogitsArgs a)
       __builtin_nontemporal_store(v, reinterpret_cast<i32x4*>(dst + (size_t)row * a.ld_t));
     }
   }
+  b = __builtin_amdgcn_readfirstlane(claim[0]);
+  // every wavefront is done with the staging area before the next tile's loads land in it
+  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+  }   // while (b >= 0)
 }
 
 // ------------------------------------------------------------------------------------
@@ -290,57 +385,82 @@ __device__ __forceinline__ void store_tile(const StoreArgs& a, int tm, int tn, i
   }
 }
 
+constexpr int STORE_CLAIM_OFF = 2 * STAGE_BYTES;
+constexpr int STORE_LDS_BYTES = STORE_CLAIM_OFF + 16;
+
 __global__ __launch_bounds__(NTHREADS) void gemm_store_kernel(StoreArgs a) {
   const Ctl ctl = *a.ctl;
-  int tm, tn;
   const int m_lim = a.m_from_ctl ? min(a.M, ctl.n_pad) : a.M;
   const int tiles_m = min(a.tiles_m, (m_lim + BM - 1) / BM);
   const int K = a.k_from_ctl ? ctl.n_pad : a.K;
   const int ks = (a.split_k && a.m_from_ctl) ? dh_split(ctl.n_pad, a.M, a.tiles_n, K / BK) : 1;
-  if (!map_tile_interleaved(blockIdx.x, tiles_m * ks, a.tiles_n, tm, tn)) return;
-  const int part = tm / tiles_m;                     // 0 unless the contraction is split
-  tm -= part * tiles_m;
-  const int s0 = (int)((long long)part * (K / BK) / ks), s1 = (int)((long long)(part + 1) * (K / BK) / ks);
-  const uint32_t kb = (uint32_t)s0 * BK * 2u;        // byte offset of this part's first k
-
   const int tid = threadIdx.x;
-  TileLoader LA, LB;
-  LA.init(a.B, a.b_rows, tn * BN, a.ldb, kb, tid);     // engine rows <- n
-  LB.init(a.A, a.a_rows, tm * BM, a.lda, kb, tid);     // engine columns <- m
-  f32x4 acc[GM][GN];
-  zero_acc(acc);
-  mainloop(LA, LB, s1 - s0, g_smem, acc);
-  a.C = static_cast<char*>(a.C) + (size_t)part * ctl.n_pad * a.ldc * (a.out_bf16 ? 2 : 4);
-  if (a.out_bf16)
-    store_tile<__bf16>(a, tm, tn, m_lim, acc);
-  else
-    store_tile<float>(a, tm, tn, m_lim, acc);
+  TileQueue Q;
+  Q.init(a.queue, tiles_m * ks * a.tiles_n, 1);
+  volatile int* claim = reinterpret_cast<volatile int*>(g_smem + STORE_CLAIM_OFF);
+  int b = queue_broadcast(claim, tid == 0 ? Q.resolve(Q.ticket()) : 0);
+  char* const C0 = static_cast<char*>(a.C);
+
+  // persistent: one workgroup per compute unit takes tiles from the XCD-aware queue until none is left
+  while (b >= 0) {
+    int tm, tn;
+    map_tile_interleaved(b, tiles_m * ks, a.tiles_n, tm, tn);
+    const int part = tm / tiles_m;                     // 0 unless the contraction is split
+    tm -= part * tiles_m;
+    const int s0 = (int)((long long)part * (K / BK) / ks), s1 = (int)((long long)(part + 1) * (K / BK) / ks);
+    const uint32_t kb = (uint32_t)s0 * BK * 2u;        // byte offset of this part's first k
+
+    // the claim for the next tile travels under the main loop (a tile here is hundreds of stages long)
+    unsigned ticket;
+    if (tid == 0) ticket = Q.ticket();
+    TileLoader LA, LB;
+    LA.init(a.B, a.b_rows, tn * BN, a.ldb, kb, tid);     // engine rows <- n
+    LB.init(a.A, a.a_rows, tm * BM, a.lda, kb, tid);     // engine columns <- m
+    f32x4 acc[GM][GN];
+    zero_acc(acc);
+    mainloop(LA, LB, s1 - s0, g_smem, acc);
+    const int b_next = queue_broadcast(claim, tid == 0 ? Q.resolve(ticket) : 0);
+    a.C = C0 + (size_t)part * ctl.n_pad * a.ldc * (a.out_bf16 ? 2 : 4);
+    if (a.out_bf16)
+      store_tile<__bf16>(a, tm, tn, m_lim, acc);
+    else
+      store_tile<float>(a, tm, tn, m_lim, acc);
+    b = b_next;
+  }
 }
 
 // ---- host-side launchers -------------------------------------------------------------
-static hipError_t ensure_lds(const void* fn) {
-  return hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, GEMM_LDS_BYTES);
-}
+// Workgroups of a persistent launch: one per compute unit, a multiple of the 8 XCDs.
+static int g_persistent_grid = 256;
 
 hipError_t init_gemm_kernels() {
   hipError_t e;
-  if ((e = ensure_lds(reinterpret_cast<const void*>(lmhead_fwd_kernel))) != hipSuccess) return e;
-  if ((e = ensure_lds(reinterpret_cast<const void*>(lmhead_dlogits_kernel))) != hipSuccess) return e;
-  if ((e = ensure_lds(reinterpret_cast<const void*>(gemm_store_kernel))) != hipSuccess) return e;
+  if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(lmhead_fwd_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                               FWD_LDS_BYTES)) != hipSuccess) return e;
+  if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(lmhead_dlogits_kernel),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, DLOGITS_LDS_BYTES)) != hipSuccess) return e;
+  if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_store_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                               STORE_LDS_BYTES)) != hipSuccess) return e;
+  int dev = 0, cus = 0;
+  if ((e = hipGetDevice(&dev)) != hipSuccess) return e;
+  if ((e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev)) != hipSuccess) return e;
+  g_persistent_grid = cus >= 8 ? (cus / 8) * 8 : 8;
   return hipSuccess;
 }
 
+// The grid covers the host-side maximum of tiles (the live extent is known only on the device) but
+// never more than one workgroup per compute unit.
+static int persistent_grid(int tiles_m, int tiles_n) { return min(grid_for_tiles(tiles_m, tiles_n), g_persistent_grid); }
+
 void launch_lmhead_fwd(const FwdArgs& a, hipStream_t s) {
-  const int grid = grid_for_tiles(a.tiles_v, a.tiles_t);
-  hipLaunchKernelGGL(lmhead_fwd_kernel, dim3(grid), dim3(NTHREADS), GEMM_LDS_BYTES, s, a);
+  hipLaunchKernelGGL(lmhead_fwd_kernel, dim3(persistent_grid(a.tiles_v, a.tiles_t)), dim3(NTHREADS), FWD_LDS_BYTES, s, a);
 }
 void launch_lmhead_dlogits(const DlogitsArgs& a, hipStream_t s) {
-  const int grid = grid_for_tiles(a.tiles_v, a.tiles_t);
-  hipLaunchKernelGGL(lmhead_dlogits_kernel, dim3(grid), dim3(NTHREADS), GEMM_LDS_BYTES, s, a);
+  hipLaunchKernelGGL(lmhead_dlogits_kernel, dim3(persistent_grid(a.tiles_v, a.tiles_t)), dim3(NTHREADS), DLOGITS_LDS_BYTES, s, a);
 }
 void launch_gemm_store(const StoreArgs& a, hipStream_t s) {
-  const int grid = grid_for_tiles(a.tiles_m, a.tiles_n);
-  hipLaunchKernelGGL(gemm_store_kernel, dim3(grid), dim3(NTHREADS), GEMM_LDS_BYTES, s, a);
+  // (a split contraction's parts share the row extent: parts x live rows never exceed tiles_m tiles)
+  hipLaunchKernelGGL(gemm_store_kernel, dim3(persistent_grid(a.tiles_m, a.tiles_n)), dim3(NTHREADS), STORE_LDS_BYTES, s, a);
 }
 
 }  // namespace pg

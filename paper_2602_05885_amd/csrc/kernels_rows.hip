@@ -67,6 +67,7 @@ void launch_trloo(const TrlooArgs& a, hipStream_t s) {
 __global__ void prep_init_kernel(PrepArgs a) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i < 8) a.counters[i] = 0ull;
+  for (int w = i; w < a.queue_words; w += gridDim.x * blockDim.x) a.queue[w] = 0u;
   if (i < a.t_cap) a.zy[i] = 0.f;
   if (i < a.T) {
     if (a.out0) a.out0[i] = 0.f;
