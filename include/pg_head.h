@@ -128,6 +128,13 @@ size_t pg_workspace_bytes(int64_t T, int64_t d, int64_t V, int32_t S, const pg_p
                           int32_t which_call);
 
 /*
+ * Inspection hook (tests, tuning): the number of vocabulary rows per chunk of the backward pass of
+ * pg_loss_fwd_bwd / pg_sft_fwd_bwd for these sizes (chunk c covers rows [c n, (c+1) n) of W and dW;
+ * it follows from the scratch budget, PG_HEAD_DS_BUDGET_BYTES).  0 if the arguments are invalid.
+ */
+int64_t pg_backward_chunk_rows(int64_t T, int64_t d, int64_t V, int32_t S, const pg_params* h_params);
+
+/*
  * Sec. 4.2, Eq. (2) and Eq. (5).
  *   rewards[(p*K+k)*Tmax+t]  per-turn reward R of rollout k of prompt p at turn t (0 where the
  *                            turn was never generated)

@@ -21,7 +21,7 @@ CALL_LOGPROB_FWD = 0
 CALL_LOSS_FWD_BWD = 1
 COUNTER_NAMES = ("active", "clip_hi", "clip_lo", "seg_geo", "seg_veto", "truncated", "loss_tokens", "seg_dropped")
 
-EXPORTS = ("pg_last_error", "pg_init", "pg_workspace_bytes", "trloo_advantage", "pg_logprob_fwd", "pg_loss_fwd_bwd",
+EXPORTS = ("pg_last_error", "pg_init", "pg_workspace_bytes", "pg_backward_chunk_rows", "trloo_advantage", "pg_logprob_fwd", "pg_loss_fwd_bwd",
            "pg_sft_fwd_bwd", "pg_head_shard_fwd", "pg_head_partials_merge", "pg_head_partials_finish", "pg_loss_shard_bwd", "grpo_advantage",
            "turn_reward", "prs_retain", "pg_monitors_workspace_bytes", "pg_monitors", "pg_monitors_static", "pg_rmsnorm_fwd", "pg_rmsnorm_bwd_workspace_bytes", "pg_rmsnorm_bwd",
            "pg_profile_enable", "pg_profile_read")
@@ -80,6 +80,8 @@ def lib() -> C.CDLL:
         L.pg_last_error.argtypes = []
         L.pg_workspace_bytes.restype = C.c_size_t
         L.pg_workspace_bytes.argtypes = [C.c_int64, C.c_int64, C.c_int64, C.c_int32, C.POINTER(PgParams), C.c_int32]
+        L.pg_backward_chunk_rows.restype = C.c_int64
+        L.pg_backward_chunk_rows.argtypes = [C.c_int64, C.c_int64, C.c_int64, C.c_int32, C.POINTER(PgParams)]
         L.trloo_advantage.restype = C.c_int32
         L.trloo_advantage.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_float,
                                       C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
@@ -262,6 +264,12 @@ def pg_profile_read():
 def pg_workspace_bytes(T: int, d: int, V: int, S: int, params: Params, which_call: int) -> int:
     p = params.c_struct()
     return int(lib().pg_workspace_bytes(T, d, V, S, C.byref(p), which_call))
+
+
+def pg_backward_chunk_rows(T: int, d: int, V: int, S: int, params: Params) -> int:
+    """Vocabulary rows per chunk of the backward pass for these sizes (inspection hook)."""
+    p = params.c_struct()
+    return int(lib().pg_backward_chunk_rows(T, d, V, S, C.byref(p)))
 
 
 def alloc_workspace(T: int, d: int, V: int, S: int, params: Params, which_call: int, device="cuda") -> torch.Tensor:

@@ -380,6 +380,12 @@ size_t pg_workspace_bytes(int64_t T, int64_t d, int64_t V, int32_t S, const pg_p
   return pl.total;
 }
 
+int64_t pg_backward_chunk_rows(int64_t T, int64_t d, int64_t V, int32_t S, const pg_params* h_params) {
+  Plan pl;
+  if (make_plan(T, d, V, S, h_params, PG_CALL_LOSS_FWD_BWD, pl) != PG_OK) return 0;
+  return pl.vc;
+}
+
 int32_t trloo_advantage(const float* rewards, const uint8_t* valid, int32_t P, int32_t K, int32_t Tmax, float gamma,
                         double* returns_out, double* adv_out, int32_t* group_n_out, void* stream) {
   return turn_advantage(rewards, valid, P, K, Tmax, gamma, returns_out, adv_out, group_n_out, 0, stream, "trloo_advantage");

@@ -70,3 +70,17 @@ def rel_fro(a, b):
     b = np.asarray(b, np.float64)
     den = np.linalg.norm(b)
     return np.linalg.norm(a - b) / den if den > 0 else np.linalg.norm(a)
+
+
+def block_rel_fro(a, b, rows=256):
+    """Largest relative Frobenius error over consecutive blocks of `rows` rows (a wrong 16 x 16 MFMA tile
+    moves a whole-matrix norm by almost nothing; it cannot hide in a 256-row block).  A block's error is
+    taken relative to its own reference norm, or, where that is below 1e-3 of the mean block norm (rows
+    of inactive tokens, vocabulary rows nobody's distribution touches), relative to the mean block norm."""
+    a = np.asarray(a, np.float64)
+    b = np.asarray(b, np.float64)
+    n = (a.shape[0] + rows - 1) // rows
+    den = np.array([np.linalg.norm(b[i * rows:(i + 1) * rows]) for i in range(n)])
+    err = np.array([np.linalg.norm(a[i * rows:(i + 1) * rows] - b[i * rows:(i + 1) * rows]) for i in range(n)])
+    floor = 1e-3 * (den.mean() if den.size and den.mean() > 0 else 1.0)
+    return float((err / np.maximum(den, floor)).max()) if n else 0.0

@@ -20,7 +20,7 @@ import torch
 from oracle import pg_oracle as O
 from paper_2602_05885_amd import binding as B
 from paper_2602_05885_amd import synth
-from tests._cases import np64, ratio_targets, rel_fro
+from tests._cases import block_rel_fro, np64, ratio_targets, rel_fro
 
 pytestmark = pytest.mark.gpu
 
@@ -170,6 +170,181 @@ def test_full_dW_sampled_rows_and_identities(full_case):
     lhs = float((dW.double() * fc["tin"]["W"].double()).sum())
     rhs = float((dH.double() * fc["tin"]["H"].double()).sum())
     assert abs(lhs - rhs) <= 1e-2 * max(abs(lhs), abs(rhs)), (lhs, rhs)
+
+
+def _library_gradients(H, W, y, act_rows, lse_a, k_a, tau, T, vocab_step=4096):
+    """torch fp32 reference for ALL of dW and dH (library GEMMs, chunked over the vocabulary): for a vocab
+    slice, z = H_a W_s^T / tau, dS = k (onehot - exp(z - lse)), dW_s = dS^T H_a, dH_a += dS W_s."""
+    dev = H.device
+    Ha = H[act_rows].float()
+    ya = y[act_rows].long()
+    V, d = W.shape
+    dW = torch.empty((V, d), dtype=torch.float32, device=dev)
+    dHa = torch.zeros((Ha.shape[0], d), dtype=torch.float32, device=dev)
+    for a in range(0, V, vocab_step):
+        Ws = W[a:a + vocab_step].float()
+        dS = torch.exp((Ha @ Ws.T) / tau - lse_a[:, None]).mul_(-k_a[:, None])
+        hit = (ya >= a) & (ya < a + Ws.shape[0])
+        idx = torch.nonzero(hit)[:, 0]
+        dS[idx, ya[idx] - a] += k_a[idx]
+        dW[a:a + Ws.shape[0]] = dS.T @ Ha
+        dHa += dS @ Ws
+    dH = torch.zeros((T, d), dtype=torch.float32, device=dev)
+    dH[act_rows] = dHa
+    return dW, dH
+
+
+def test_full_all_rows_against_library_gradients(full_case):
+    """Every row of dW and dH at the benchmark's size against a torch fp32 computation (library GEMMs), in
+    blocks of 256 rows - a misplaced or wrong MFMA tile cannot hide in a block - with the library result
+    itself checked against fp64 on sampled rows, among them the first and last vocabulary row of every
+    backward chunk (where one launch's tiles end and the next one's begin)."""
+    fc = full_case
+    tin, spec, batch = fc["tin"], fc["spec"], fc["batch"]
+    dev = tin["H"].device
+    T, d, V, S = tin["H"].shape[0], spec.d, spec.V, batch.S
+    tau = float(np.float32(spec.temperature))
+    act = np.nonzero(fc["active"])[0]
+    act_t = torch.from_numpy(act).to(dev)
+    lp = fc["lib_logp"].double().cpu().numpy()[act]
+    _, g, _, _, _ = O.surrogate(lp, fc["old"].astype(np.float64)[act], fc["A_tok"][act], fc["oprm"])
+    k = fc["c"][act] * g / fc["norm"] / tau                                   # fp64 coefficients
+    k_t = torch.from_numpy(k.astype(np.float32)).to(dev)
+    lib_dW, lib_dH = _library_gradients(tin["H"], tin["W"], tin["y"], act_t, fc["lib_lse"][act_t], k_t, tau, T)
+    torch.cuda.synchronize()
+
+    # chunk boundaries of the launch configuration under test
+    prm = B.Params(mismatch_mode=2, temperature=spec.temperature)
+    vc = B.pg_backward_chunk_rows(T, d, V, S, prm)
+    assert 0 < vc < V and vc % 256 == 0, vc
+    edges = sorted({v for c in range((V + vc - 1) // vc) for v in (c * vc, min(V, (c + 1) * vc) - 1)})
+    print(f"[fullsize] backward chunks of {vc} vocabulary rows; boundary rows {edges}", flush=True)
+    assert len(edges) >= 4
+
+    # the library reference against fp64 on the chunk-boundary rows and a few more
+    rng = np.random.default_rng(11)
+    vs = np.unique(np.concatenate([edges, rng.choice(fc["yn"][act], 6), rng.integers(0, V, 6)]))
+    Ha = np64(tin["H"][act_t])
+    lse = fc["lib_lse"].double().cpu().numpy()[act]
+    z = (Ha @ fc["Wn"][vs].T) / tau
+    dS = -np.exp(z - lse[:, None]) * k[:, None] + (fc["yn"][act][:, None] == vs[None, :]) * k[:, None]
+    ref_rows = dS.T @ Ha
+    vs_t = torch.from_numpy(vs).to(dev)
+    e_lib = rel_fro(np64(lib_dW[vs_t]), ref_rows)
+    e_got = max(rel_fro(np64(fc["out"]["dW"][v:v + 1]), ref_rows[i:i + 1]) for i, v in enumerate(vs))
+    print(f"[fullsize] dW rows vs fp64: library {e_lib:.2e}, kernels (worst single row of {len(vs)}) {e_got:.2e}", flush=True)
+    assert e_lib <= 1e-4, e_lib
+    assert e_got <= 1e-2, e_got
+    rows = fc["rows"]
+    l, g_r, r, _, _ = O.surrogate(fc["o_logp"], fc["old"].astype(np.float64)[rows], fc["A_tok"][rows], fc["oprm"])
+    ref_dH = O.dH_rows(fc["Hr"], fc["Wn"], fc["yn"][rows], fc["c"][rows] * g_r / fc["norm"], spec.temperature)
+    e_lib_h = rel_fro(np64(lib_dH[torch.from_numpy(rows).to(dev)]), ref_dH)
+    assert e_lib_h <= 2e-4, e_lib_h           # the library side uses fp32 log-probs for the coefficients
+
+    # all rows, block by block
+    got_dW, got_dH = fc["out"]["dW"], fc["out"]["dH"].float()
+    def blocks(a, b):
+        n = (a.shape[0] + 255) // 256 * 256
+        pad = lambda t: torch.nn.functional.pad(t, (0, 0, 0, n - t.shape[0])).reshape(n // 256, -1)
+        err = (pad(a) - pad(b)).double().norm(dim=1)
+        den = pad(b).double().norm(dim=1)
+        return (err / torch.clamp(den, min=1e-3 * float(den.mean()))).cpu().numpy(), float((pad(a) - pad(b)).double().norm() / pad(b).double().norm())
+    bw, ew = blocks(got_dW, lib_dW)
+    bh, eh = blocks(got_dH, lib_dH)
+    print(f"[fullsize] all rows vs library fp32: dW {ew:.2e} (worst of {len(bw)} blocks {bw.max():.2e} at block {int(bw.argmax())}), "
+          f"dH {eh:.2e} (worst of {len(bh)} blocks {bh.max():.2e})", flush=True)
+    assert ew <= 1e-2 and eh <= 1e-2
+    assert bw.max() <= 1e-2 and bh.max() <= 1e-2
+    del lib_dW, lib_dH
+
+
+def dh_split_parts(n_pad, t_cap, tiles_n, k_stages):
+    """The device's choice of how many parts the dH contraction is cut into (restated from the header's
+    description: enough parts to fill 256 compute units, at most 8, at least 8 stages each, and the parts'
+    accumulator slabs must fit into the [t_cap, d] accumulator)."""
+    if n_pad <= 0:
+        return 1
+    tiles = (n_pad // 256) * tiles_n
+    ks = 256 // max(tiles, 1)
+    ks = min(ks, t_cap // n_pad, k_stages // 8, 8)
+    return max(ks, 1)
+
+
+def test_full_geometric_rejection_few_rows_split_contraction(full_case):
+    """Sec. 5.1's rule at the benchmark's size with most samples rejected: two samples' log-ratios sit inside
+    [0.999, 1.001] by construction, all others 5e-3 outside, so about 1.3 k of 32768 loss tokens stay active
+    and the dH contraction runs cut into parts along the vocabulary (asserted from the counters)."""
+    fc = full_case
+    tin, spec, batch = fc["tin"], fc["spec"], fc["batch"]
+    dev = tin["H"].device
+    T, d, V, S = tin["H"].shape[0], spec.d, spec.V, batch.S
+    tau = float(np.float32(spec.temperature))
+    seg_loss = np.array([batch.loss_mask[batch.cu_seqlens[s]:batch.cu_seqlens[s + 1]].sum() for s in range(S)])
+    seg_adv = np.array([fc["A_tok"][batch.cu_seqlens[s]] for s in range(S)])
+    cand = [s for s in range(S) if abs(seg_adv[s]) > 0.1 and seg_loss[s] > 128]      # samples that carry a gradient
+    keep_segs = next([a, b] for i, a in enumerate(cand) for b in cand[i + 1:] if 1024 < seg_loss[a] + seg_loss[b] <= 1536)
+    assert seg_adv[keep_segs[0]] != seg_adv[keep_segs[1]]
+    rng = np.random.default_rng(77)
+    delta = np.empty(T)
+    for s in range(S):
+        a, b = batch.cu_seqlens[s], batch.cu_seqlens[s + 1]
+        delta[a:b] = (2e-4 if s in keep_segs else 5e-3) + rng.uniform(-1e-5, 1e-5, b - a)
+    rollout = (fc["old"].astype(np.float64) - delta).astype(np.float32)
+    rollout_t = torch.from_numpy(rollout).to(dev)
+    prm = B.Params(mismatch_mode=1, temperature=spec.temperature)
+    ws = B.alloc_workspace(T, d, V, S, prm, B.CALL_LOSS_FWD_BWD, dev)
+    out = B.pg_loss_fwd_bwd(tin["H"], tin["W"], tin["y"], tin["loss_mask"], tin["cu"], fc["adv"].reshape(-1),
+                            tin["seg_sample"], tin["old"], rollout_t, prm, ws)
+    torch.cuda.synchronize()
+    del ws
+    oprm = O.Params(mismatch_mode=1, temperature=spec.temperature)
+    c, active, keep, mm = O.mismatch_weights(fc["old"], rollout, batch.loss_mask, batch.cu_seqlens, oprm)
+    cnt = out["counters"].cpu().numpy()
+    n_act = int(active.sum())
+    assert cnt[0] == n_act == seg_loss[keep_segs].sum() and cnt[6] == batch.loss_mask.sum()
+    assert cnt[3] == mm["geo"] == S - 2 and cnt[4] == mm["veto"] == 0 and cnt[5] == 0
+    # the launch really is the split one
+    vc = B.pg_backward_chunk_rows(T, d, V, S, prm)
+    t_cap, n_pad = (T + 255) // 256 * 256, (n_act + 255) // 256 * 256
+    parts = dh_split_parts(n_pad, t_cap, (d + 255) // 256, vc // 64)
+    print(f"[fullsize] geometric rejection keeps {n_act} rows (padded {n_pad}): dH contraction in {parts} parts", flush=True)
+    assert parts >= 2
+    # per-row outputs against the oracle on sampled active rows; inactive rows are zero
+    act = np.nonzero(active)[0]
+    rows = np.sort(rng.choice(act, 24, replace=False))
+    Hr = np64(tin["H"][torch.from_numpy(rows).to(dev)])
+    o_logp, o_ent, _ = O.lm_head_logprob(Hr, fc["Wn"], fc["yn"][rows], spec.temperature)
+    got_lp, got_ent = out["logp"].cpu().numpy(), out["entropy"].cpu().numpy()
+    assert np.abs(got_lp[rows] - o_logp).max() <= 2e-3 and np.abs(got_ent[rows] - o_ent).max() <= 2e-3
+    assert np.all(got_lp[~active] == 0) and np.abs(got_lp[act] - fc["lib_logp"].cpu().numpy()[act]).max() <= 2e-3
+    norm = float(max(1, n_act))
+    l, g, r, chi, clo = O.surrogate(fc["lib_logp"].double().cpu().numpy()[act], fc["old"].astype(np.float64)[act],
+                                    fc["A_tok"][act], oprm)
+    ref_loss = float(l.sum() / norm)
+    assert abs(ref_loss) > 1e-3 and abs(float(out["loss"][0]) - ref_loss) <= 1e-3 * abs(ref_loss), (float(out["loss"][0]), ref_loss)
+    assert cnt[1] == chi.sum() and cnt[2] == clo.sum()
+    l_r, g_r, _, _, _ = O.surrogate(o_logp, fc["old"].astype(np.float64)[rows], fc["A_tok"][rows], oprm)
+    ref_dH = O.dH_rows(Hr, fc["Wn"], fc["yn"][rows], g_r / norm, spec.temperature)
+    got_dH = np64(out["dH"][torch.from_numpy(rows).to(dev)])
+    assert rel_fro(got_dH, ref_dH) <= 1e-2, rel_fro(got_dH, ref_dH)
+    assert not out["dH"][torch.from_numpy(np.nonzero(~active)[0]).to(dev)].any()
+    # sampled dW rows in fp64 over all active rows (chunk boundaries included)
+    edges = [0, vc - 1, vc, V - 1]
+    vs = np.unique(np.concatenate([edges, rng.choice(fc["yn"][act], 8), rng.integers(0, V, 8)]))
+    Ha = np64(tin["H"][torch.from_numpy(act).to(dev)])
+    lse = fc["lib_lse"].double().cpu().numpy()[act]
+    k = g / norm / tau
+    z = (Ha @ fc["Wn"][vs].T) / tau
+    dS = -np.exp(z - lse[:, None]) * k[:, None] + (fc["yn"][act][:, None] == vs[None, :]) * k[:, None]
+    got_w = np64(out["dW"][torch.from_numpy(vs).to(dev)])
+    assert rel_fro(got_w, dS.T @ Ha) <= 1e-2, rel_fro(got_w, dS.T @ Ha)
+    # all of dW and dH, block by block, against the library gradients for this active set
+    act_t = torch.from_numpy(act).to(dev)
+    lib_dW, lib_dH = _library_gradients(tin["H"], tin["W"], tin["y"], act_t, fc["lib_lse"][act_t],
+                                        torch.from_numpy(k.astype(np.float32)).to(dev), tau, T)
+    assert block_rel_fro(np64(out["dH"]), np64(lib_dH)) <= 1e-2
+    e = float((out["dW"] - lib_dW).double().norm() / lib_dW.double().norm())
+    assert e <= 1e-2, e
 
 
 def test_full_logprob_fwd_call(full_case):

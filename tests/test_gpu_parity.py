@@ -11,7 +11,7 @@ import torch
 from oracle import pg_oracle as O
 from paper_2602_05885_amd import binding as B
 from paper_2602_05885_amd import synth
-from tests._cases import build_loss_case, np64, rel_fro
+from tests._cases import block_rel_fro, build_loss_case, np64, rel_fro
 
 pytestmark = pytest.mark.gpu
 
@@ -113,8 +113,11 @@ def test_peaked_distributions_large_logits(dev):
     torch.cuda.synchronize()
     rl, re, rs = O.lm_head_logprob(Hn, Wn, yn, 1.0)
     assert rl.min() < -100 and re.min() < 1e-3
-    assert np.abs(logp.cpu().numpy() - rl).max() <= TOL_LOGP * max(1.0, np.abs(rl).max() / 100)
-    assert np.abs(ent.cpu().numpy() - re).max() <= TOL_LOGP and np.abs(lse.cpu().numpy() - rs).max() <= TOL_LOGP * 2
+    e_logp, e_ent, e_lse = (np.abs(logp.cpu().numpy() - rl).max(), np.abs(ent.cpu().numpy() - re).max(),
+                            np.abs(lse.cpu().numpy() - rs).max())
+    print(f"[peaked] max|dlogp| {e_logp:.2e} (|logp| up to {np.abs(rl).max():.0f}) max|dentropy| {e_ent:.2e} "
+          f"max|dlse| {e_lse:.2e}")
+    assert e_logp <= TOL_LOGP and e_ent <= TOL_LOGP and e_lse <= TOL_LOGP
     cu = torch.tensor([0, T], dtype=torch.int32, device=dev)
     adv = torch.tensor([1.5], dtype=torch.float64, device=dev)
     out = B.pg_loss_fwd_bwd(H, W, y, torch.ones(T, dtype=torch.uint8, device=dev), cu, adv, None, None, None, prm, ws)
@@ -186,17 +189,25 @@ def _run_loss(dev, spec, prm, mismatch_kind, on_policy, monkeypatch=None, budget
     return out, ref, batch
 
 
-def _compare(out, ref, logp_tol=TOL_LOGP):
+def _compare(out, ref, logp_tol=TOL_LOGP, grad_tol=TOL_GRAD):
     assert np.array_equal(out["counters"].cpu().numpy(), ref["counters"]), \
         (out["counters"].cpu().numpy(), ref["counters"])
-    assert np.abs(out["logp"].cpu().numpy() - ref["logp"]).max() <= logp_tol
-    assert np.abs(out["entropy"].cpu().numpy() - ref["entropy"]).max() <= logp_tol
+    e_logp = np.abs(out["logp"].cpu().numpy() - ref["logp"]).max()
+    e_ent = np.abs(out["entropy"].cpu().numpy() - ref["entropy"]).max()
     loss = float(out["loss"][0])
-    assert abs(loss - ref["loss"]) <= TOL_LOSS * max(abs(ref["loss"]), 1e-6), (loss, ref["loss"])
-    dH = np64(out["dH"])
+    e_loss = abs(loss - ref["loss"]) / max(abs(ref["loss"]), 1e-6)
+    dH, dW = np64(out["dH"]), np64(out["dW"])
+    e_dH, e_dW = rel_fro(dH, ref["dH"]), rel_fro(dW, ref["dW"])
+    b_dH, b_dW = block_rel_fro(dH, ref["dH"]), block_rel_fro(dW, ref["dW"])
+    # achieved errors (shown with pytest -s, and in the failure report)
+    print(f"[parity] logp {e_logp:.2e} entropy {e_ent:.2e} loss(rel) {e_loss:.2e} dH {e_dH:.2e} (worst 256-row block "
+          f"{b_dH:.2e}) dW {e_dW:.2e} (worst block {b_dW:.2e})")
+    assert e_logp <= logp_tol and e_ent <= logp_tol, (e_logp, e_ent)
+    assert e_loss <= TOL_LOSS, (loss, ref["loss"])
     assert np.all(dH[~ref["active"]] == 0)
-    assert rel_fro(dH, ref["dH"]) <= TOL_GRAD, rel_fro(dH, ref["dH"])
-    assert rel_fro(np64(out["dW"]), ref["dW"]) <= TOL_GRAD, rel_fro(np64(out["dW"]), ref["dW"])
+    assert e_dH <= grad_tol and e_dW <= grad_tol, (e_dH, e_dW)
+    # no 256-row block of either gradient may be off by more than the whole-matrix bound either
+    assert b_dH <= grad_tol and b_dW <= grad_tol, (b_dH, b_dW)
 
 
 def test_loss_config0_tiny_f32(dev):
