@@ -216,7 +216,9 @@ def test_loss_config0_tiny_f32(dev):
     prm = B.Params(dtype=1, mismatch_mode=0)
     out, ref, batch = _run_loss(dev, spec, prm, "none", on_policy=False)
     assert batch.T == 1024 and batch.S == 32
-    _compare(out, ref, logp_tol=2e-4)
+    # fp32 inputs: log-probs carry ~16 mantissa bits (split-bf16 products); the gradients go through the bf16
+    # dS like every other configuration, which puts their relative error at 2.3e-3 (printed by _compare)
+    _compare(out, ref, logp_tol=2e-4, grad_tol=5e-3)
     assert ref["counters"][1] > 0 and ref["counters"][2] > 0       # both clip branches occur
 
 
