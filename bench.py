@@ -23,10 +23,24 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA peak (published)
-# What the MFMA instruction alone sustains on this chip with operands and accumulators in registers and random
-# operands (tile_bench's register-only loop; profiles/tile_bench_mfma_only_and_engine.md): context for the
-# roofline fraction, which divides by the published peak.
-MEASURED_MFMA_ONLY_TFLOPS = 2060.0
+TRAFFIC_SOURCE = "profiles/gemm_store_kernel_hbm_traffic.md"
+
+
+def measured_mfma_only_tflops():
+    """What the MFMA instruction alone sustains on THIS box right now, with operands and accumulators in
+    registers and random operands: tile_bench's register-only loop, run as a child process (context for the
+    roofline fraction, which divides by the published peak).  None when the tool is not built or fails."""
+    import re
+    import subprocess
+    exe = os.path.join(ROOT, "paper_2602_05885_amd", "tile_bench")
+    if not os.path.exists(exe):
+        return None
+    try:
+        out = subprocess.run([exe, "1", "3"], stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True, timeout=60).stdout
+    except Exception:
+        return None
+    rates = [float(m.group(1)) for m in re.finditer(r"random operands, 1 workgroup.*?([0-9.]+) TFLOP/s", out)]
+    return rates[-1] if rates else None
 
 # L2<->fabric bytes per gemm_store_kernel launch from the FETCH_SIZE / WRITE_SIZE counter runs
 # summarised in profiles/gemm_store_kernel_hbm_traffic.md (mean over a step's 14 launches, each
@@ -121,6 +135,39 @@ def aux_stage_times(B, torch, dev, rewards, valid, out, loss_mask, old_logp, rol
     return res
 
 
+def timed(torch, B, fn, steps, warmup):
+    """ms per step (host clock around a synchronised region) and the per-kernel-class event times."""
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    B.pg_profile_enable(True, 64 * max(steps, 1))
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        out = fn()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    prof = B.pg_profile_read()
+    B.pg_profile_enable(False)
+    kern = {k: {"launches_per_step": n / steps, "ms_per_step": ms / steps} for k, (ms, n) in prof.items() if n}
+    return dt / steps * 1e3, kern, out
+
+
+def forward_only_workload(torch, B, synth, dev, config, steps, warmup, scale_rows=1.0):
+    """pg_logprob_fwd over all rows of a configuration: ms per step, rows/s, % of peak on 2dV."""
+    spec = synth.SPECS[config]
+    batch = synth.make_batch(spec, scale_rows)
+    T, d, V = batch.T, spec.d, spec.V
+    H, W, y = synth.make_head(T, d, V, spec.dtype, spec.seed, dev, spec.unit_rms)
+    prm = B.Params(dtype=0 if spec.dtype == "bf16" else 1, temperature=spec.temperature)
+    ws = B.alloc_workspace(T, d, V, 0, prm, B.CALL_LOGPROB_FWD, dev)
+    outbuf = tuple(torch.empty(T, dtype=torch.float32, device=dev) for _ in range(3))
+    ms, kern, _ = timed(torch, B, lambda: B.pg_logprob_fwd(H, W, y, None, prm, ws, out=outbuf), steps, warmup)
+    flops = 2.0 * d * V * T
+    return {"workload": f"configs[{config}] {spec.name}: d={d}, V={V}, {T} rows, forward only, temperature {spec.temperature}",
+            "step": "pg_logprob_fwd", "steps": steps, "ms_per_step": ms, "tokens_per_s": T / (ms * 1e-3),
+            "flops_per_token": "2dV", "pct_mfma_peak": 100.0 * flops / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, "kernels": kern}
+
+
 def bench_forward_only(args, torch, B, synth, dev):
     """pg_logprob_fwd (log-prob, entropy, logsumexp) over all rows of the chosen configuration."""
     spec = synth.SPECS[args.config]
@@ -176,6 +223,9 @@ def main():
                          "recompute left behind (valid while the weights are those of that recompute: the "
                          "forward contraction is not repeated, 6dV instead of 8dV flops per token)")
     ap.add_argument("--vocab-shards", type=int, default=2, help="number of vocab shards for --workload shard")
+    ap.add_argument("--no-others", dest="others", action="store_false",
+                    help="skip the secondary workloads that the default run times after the headline "
+                         "(other_workloads: Sec. 5.1's rejection rule, backward from states, forward-only 128k rows)")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="also run three plain device-to-device copies of this size (the known-size reference "
                          "that hardware-counter byte counts are scaled by)")
@@ -184,6 +234,8 @@ def main():
         print("bench.py: this build runs on one GPU only; --gpus must be 1 "
               "(the path shards by token rows; no multi-GPU figure is produced)", file=sys.stderr)
         sys.exit(2)
+
+    mfma_only = measured_mfma_only_tflops() if args.workload == "pg" else None
 
     import torch
     from paper_2602_05885_amd import binding as B
@@ -333,13 +385,53 @@ def main():
     achieved = b["flop"] / (b["ms"] * 1e-3) / 1e12
     roofline = {"bound": "mfma", "kernel": dom, "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                 "frac": achieved / PEAK_BF16_TFLOPS,
-                "frac_of_measured_mfma_rate": achieved / MEASURED_MFMA_ONLY_TFLOPS,
+                "measured_mfma_only_tflops": mfma_only,          # tile_bench's register-only loop, this run, this box
+                "frac_of_measured_mfma_rate": achieved / mfma_only if mfma_only else None,
                 "traffic": measured_traffic(dom),
+                "traffic_source": TRAFFIC_SOURCE if measured_traffic(dom) is not None else None,
                 "flops_per_launch": b["flop"] / b["launches"], "avg_launch_ms": b["ms"] / b["launches"],
                 "launches_per_step": b["launches"]}
     n_contractions = 3.0 if args.workload == "bwd" else 4.0       # logits (twice unless the forward is not repeated), dH, dW
     executed = 2.0 * n_contractions * d * V * n_active / (ms_step * 1e-3) / 1e12
     useful = 6.0 * d * V * n_active / (ms_step * 1e-3) / 1e12
+
+    # ---- the secondary workloads, timed after the headline in the same process (shorter runs) ----
+    others = None
+    if args.workload == "pg" and args.others and args.steps > 0:
+        others = {}
+        n_steps = max(3, args.steps // 2)
+
+        def loss_entry(name, what, fn, n_contr):
+            ms, kern_o, out_o = timed(torch, B, fn, n_steps, 2)
+            na = int(out_o["counters"][0])
+            fl = 2.0 * n_contr * d * V * na
+            others[name] = {"workload": what, "steps": n_steps, "ms_per_step": ms, "active_tokens": na,
+                            "tokens_per_s": na / (ms * 1e-3), "flops_per_token": f"{int(2 * n_contr)}dV",
+                            "pct_mfma_peak": 100.0 * fl / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, "kernels": kern_o}
+
+        # the paper's own mismatch rule (Sec. 5.1: geometric rejection) on the headline microbatch
+        prm1 = B.Params(dtype=dtype_id, temperature=spec.temperature, mismatch_mode=1)
+        adv_flat = B.trloo_advantage(rewards, valid, 1.0, want_returns=False, want_group_n=False)[0].reshape(-1)
+        rollout1 = rollout_logp if rollout_logp is not None else synth.perturb_logp(old_logp, spec.logp_noise, spec.outlier_frac, spec.seed + 1)
+
+        def step_mode1():
+            B.trloo_advantage(rewards, valid, 1.0, want_returns=False, want_group_n=False)
+            return B.pg_loss_fwd_bwd(H, W, y, loss_mask, cu, adv_flat, seg_sample, old_logp, rollout1, prm1, ws, dW=dW, out=outbuf)
+        loss_entry("geometric_rejection", f"configs[{args.config}], mismatch_mode 1 (Sec. 5.1's rejection rule): "
+                   "trloo_advantage + pg_loss_fwd_bwd; tokens/s and % of peak count the tokens that stay active", step_mode1, 4.0)
+
+        # loss + backward from the recompute stage's softmax states (the forward contraction is not repeated)
+        states = B.pg_head_shard_fwd(H, W, y, loss_mask, 0, prm, ws)
+        dH32 = torch.empty((T, d), dtype=torch.float32, device=dev)
+        out_b = (outbuf[0], dH32, outbuf[2], outbuf[3], outbuf[4])
+
+        def step_bwd():
+            B.trloo_advantage(rewards, valid, 1.0, want_returns=False, want_group_n=False)
+            return B.pg_loss_shard_bwd(H, W, y, loss_mask, cu, adv_flat, seg_sample, old_logp, rollout_logp, states, 0, prm,
+                                       ws, dH_f32=True, dW=dW, out=out_b)
+        loss_entry("backward_from_states", f"configs[{args.config}], trloo_advantage + pg_loss_shard_bwd on the whole head from the "
+                   "softmax states of pg_head_shard_fwd (valid while the weights are those of the recompute)", step_bwd, 3.0)
+        del states, dH32, out_b
 
     cpu = cpu_baseline(spec, args.cpu_rows) if args.cpu_rows > 0 and args.workload == "pg" else None
     aux = (aux_stage_times(B, torch, dev, rewards, valid, out, loss_mask, old_logp, rollout_logp, dW, H)
@@ -374,6 +466,12 @@ def main():
         "loss": loss, "counters": {n: int(c) for n, c in zip(B.COUNTER_NAMES, counters)},
         "kernels": kern, "roofline": roofline, "cpu_baseline": cpu, "aux_stages_us": aux,      # per call; the *_GBps entries are algorithmic bytes / time
     }
+    if others is not None:
+        # the forward-only recompute workload needs the memory of the step's buffers
+        del H, W, y, ws, dW, outbuf, out
+        torch.cuda.empty_cache()
+        others["forward_only_128k"] = forward_only_workload(torch, B, synth, dev, 4, max(3, args.steps // 2), 2, args.scale_rows)
+        line["other_workloads"] = others
     print(json.dumps(line))
 
 
