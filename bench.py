@@ -420,6 +420,19 @@ def main():
         loss_entry("geometric_rejection", f"configs[{args.config}], mismatch_mode 1 (Sec. 5.1's rejection rule): "
                    "trloo_advantage + pg_loss_fwd_bwd; tokens/s and % of peak count the tokens that stay active", step_mode1, 4.0)
 
+        # the same with the W^T cache a trainer can keep while W is unchanged (further microbatches of one step)
+        wt = B.alloc_w_transposed(d, V, dev)
+        prm1c = B.Params(dtype=dtype_id, temperature=spec.temperature, mismatch_mode=1, w_transposed=wt)
+        B.pg_loss_fwd_bwd(H, W, y, loss_mask, cu, adv_flat, seg_sample, old_logp, rollout1, prm1c, ws, dW=dW, out=outbuf)   # fills it
+        prm1c.w_transposed_valid = 1
+
+        def step_mode1_cached():
+            B.trloo_advantage(rewards, valid, 1.0, want_returns=False, want_group_n=False)
+            return B.pg_loss_fwd_bwd(H, W, y, loss_mask, cu, adv_flat, seg_sample, old_logp, rollout1, prm1c, ws, dW=dW, out=outbuf)
+        loss_entry("geometric_rejection_wt_cached", "as geometric_rejection, with pg_params.w_transposed filled by an earlier "
+                   "call on the same W (a microbatch after the first of an optimizer step)", step_mode1_cached, 4.0)
+        del wt
+
         # loss + backward from the recompute stage's softmax states (the forward contraction is not repeated)
         states = B.pg_head_shard_fwd(H, W, y, loss_mask, 0, prm, ws)
         dH32 = torch.empty((T, d), dtype=torch.float32, device=dev)

@@ -106,6 +106,12 @@ typedef struct pg_params {
                             dropped sample and counted in PG_CNT_SEG_DROPPED.  0: the length is not given
                             and the indices are used as they are (an index outside the tables then reads
                             memory that is not the caller's: undefined) */
+  void* w_transposed;    /* optional, loss calls only: DEVICE buffer of pg_w_transposed_bytes(d, V) bytes that
+                            caches the transposed head weight the dH contraction reads.  NULL: the transpose
+                            is rebuilt in the workspace on every call */
+  int32_t w_transposed_valid; /* 0: this call fills w_transposed from W; 1: it already holds the transpose of
+                            this very W (filled by an earlier call, W unchanged since: e.g. the further
+                            microbatches of one optimizer step) and the call skips the transposition */
 } pg_params;
 
 /* Message for the last error returned on this thread ("" if none). */
@@ -126,6 +132,9 @@ int32_t pg_init(void);
  */
 size_t pg_workspace_bytes(int64_t T, int64_t d, int64_t V, int32_t S, const pg_params* h_params,
                           int32_t which_call);
+
+/* Bytes of the optional W^T cache (pg_params.w_transposed) for a [V, d] head; 0 if unsupported. */
+size_t pg_w_transposed_bytes(int64_t d, int64_t V);
 
 /*
  * Inspection hook (tests, tuning): the number of vocabulary rows per chunk of the backward pass of

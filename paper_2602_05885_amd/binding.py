@@ -21,7 +21,7 @@ CALL_LOGPROB_FWD = 0
 CALL_LOSS_FWD_BWD = 1
 COUNTER_NAMES = ("active", "clip_hi", "clip_lo", "seg_geo", "seg_veto", "truncated", "loss_tokens", "seg_dropped")
 
-EXPORTS = ("pg_last_error", "pg_init", "pg_workspace_bytes", "pg_backward_chunk_rows", "trloo_advantage", "pg_logprob_fwd", "pg_loss_fwd_bwd",
+EXPORTS = ("pg_last_error", "pg_init", "pg_workspace_bytes", "pg_backward_chunk_rows", "pg_w_transposed_bytes", "trloo_advantage", "pg_logprob_fwd", "pg_loss_fwd_bwd",
            "pg_sft_fwd_bwd", "pg_head_shard_fwd", "pg_head_partials_merge", "pg_head_partials_finish", "pg_loss_shard_bwd", "grpo_advantage",
            "turn_reward", "prs_retain", "pg_monitors_workspace_bytes", "pg_monitors", "pg_monitors_static", "pg_rmsnorm_fwd", "pg_rmsnorm_bwd_workspace_bytes", "pg_rmsnorm_bwd",
            "pg_profile_enable", "pg_profile_read")
@@ -34,7 +34,7 @@ class PgParams(C.Structure):
                 ("clip_eps_hi", C.c_float), ("mismatch_mode", C.c_int32), ("geo_lo", C.c_float),
                 ("geo_hi", C.c_float), ("veto_ratio", C.c_float), ("trunc_c", C.c_float),
                 ("norm_override", C.c_float), ("accumulate_dW", C.c_int32), ("dW_dtype", C.c_int32),
-                ("n_samples", C.c_int32)]
+                ("n_samples", C.c_int32), ("w_transposed", C.c_void_p), ("w_transposed_valid", C.c_int32)]
 
 
 @dataclass
@@ -53,11 +53,15 @@ class Params:
     accumulate_dW: int = 0
     dW_dtype: int = 0
     n_samples: int = 0       # length of the adv / sample_keep tables; the loss wrappers fill it in
+    w_transposed: Optional[torch.Tensor] = None      # optional W^T cache (alloc_w_transposed), loss calls only
+    w_transposed_valid: int = 0                      # 1: the cache already holds the transpose of this W
 
     def c_struct(self) -> PgParams:
         return PgParams(self.dtype, self.temperature, self.clip_eps_lo, self.clip_eps_hi, self.mismatch_mode,
                         self.geo_lo, self.geo_hi, self.veto_ratio, self.trunc_c, self.norm_override,
-                        self.accumulate_dW, self.dW_dtype, self.n_samples)
+                        self.accumulate_dW, self.dW_dtype, self.n_samples,
+                        None if self.w_transposed is None else C.c_void_p(self.w_transposed.data_ptr()),
+                        self.w_transposed_valid)
 
 
 class PgError(RuntimeError):
@@ -80,6 +84,8 @@ def lib() -> C.CDLL:
         L.pg_last_error.argtypes = []
         L.pg_workspace_bytes.restype = C.c_size_t
         L.pg_workspace_bytes.argtypes = [C.c_int64, C.c_int64, C.c_int64, C.c_int32, C.POINTER(PgParams), C.c_int32]
+        L.pg_w_transposed_bytes.restype = C.c_size_t
+        L.pg_w_transposed_bytes.argtypes = [C.c_int64, C.c_int64]
         L.pg_backward_chunk_rows.restype = C.c_int64
         L.pg_backward_chunk_rows.argtypes = [C.c_int64, C.c_int64, C.c_int64, C.c_int32, C.POINTER(PgParams)]
         L.trloo_advantage.restype = C.c_int32
@@ -226,6 +232,15 @@ def _want_workspace(ws, dev):
     _want("workspace", ws, torch.uint8, None, dev)
 
 
+def _want_wt_cache(params: "Params", d, V, dev):
+    if params.w_transposed is None:
+        return
+    _want("params.w_transposed", params.w_transposed, torch.uint8, None, dev)
+    need = int(lib().pg_w_transposed_bytes(d, V))
+    if need == 0 or params.w_transposed.numel() < need:
+        raise ValueError(f"params.w_transposed has {params.w_transposed.numel()} bytes, {need} needed for d={d}, V={V}")
+
+
 def _ptr(t: Optional[torch.Tensor]):
     if t is None:
         return None
@@ -270,6 +285,14 @@ def pg_backward_chunk_rows(T: int, d: int, V: int, S: int, params: Params) -> in
     """Vocabulary rows per chunk of the backward pass for these sizes (inspection hook)."""
     p = params.c_struct()
     return int(lib().pg_backward_chunk_rows(T, d, V, S, C.byref(p)))
+
+
+def alloc_w_transposed(d: int, V: int, device="cuda") -> torch.Tensor:
+    """Buffer for Params.w_transposed (the W^T cache of the loss calls)."""
+    n = int(lib().pg_w_transposed_bytes(d, V))
+    if n == 0:
+        raise PgError(-2, f"no W^T cache for d={d}, V={V}")
+    return torch.empty(n, dtype=torch.uint8, device=device)
 
 
 def alloc_workspace(T: int, d: int, V: int, S: int, params: Params, which_call: int, device="cuda") -> torch.Tensor:
@@ -403,6 +426,7 @@ def pg_loss_fwd_bwd(H, W, y, loss_mask, cu_seqlens, adv, seg_sample, old_logp, r
     S = _want_loss_args(T, dev, loss_mask, cu_seqlens, adv, seg_sample, sample_keep, old_logp, rollout_logp)
     _want_loss_out(out, T, d, V, dev, H.dtype, dW, params)
     _want_workspace(workspace, dev)
+    _want_wt_cache(params, d, V, dev)
     if out is None:
         loss = torch.empty(1, dtype=torch.float32, device=dev)
         dH = torch.empty_like(H)
@@ -432,6 +456,7 @@ def pg_sft_fwd_bwd(H, W, y, loss_mask, params: Params, workspace: torch.Tensor, 
     _want("loss_mask", loss_mask, torch.uint8, (T,), dev)
     _want_loss_out(out, T, d, V, dev, H.dtype, dW, params)
     _want_workspace(workspace, dev)
+    _want_wt_cache(params, d, V, dev)
     if out is None:
         loss = torch.empty(1, dtype=torch.float32, device=dev)
         dH = torch.empty_like(H)
@@ -501,6 +526,7 @@ def pg_loss_shard_bwd(H, W_shard, y, loss_mask, cu_seqlens, adv, seg_sample, old
     _want("partials", partials, torch.float32, (T, 4), dev)
     _want_loss_out(out, T, d, Vs, dev, torch.float32 if dH_f32 else H.dtype, dW, params)
     _want_workspace(workspace, dev)
+    _want_wt_cache(params, d, Vs, dev)
     if out is None:
         loss = torch.empty(1, dtype=torch.float32, device=dev)
         dH = torch.empty((T, d), dtype=torch.float32 if dH_f32 else H.dtype, device=dev)

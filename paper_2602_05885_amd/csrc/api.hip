@@ -48,6 +48,9 @@ inline int64_t pad_ld(int64_t n) { return ((n / 64) % 2 == 0) ? n + 64 : n; }
 
 inline size_t align_up(size_t x) { return (x + ALIGN - 1) / ALIGN * ALIGN; }
 
+// Leading dimension of the caller-owned W^T cache [d, ld]: the vocabulary rounded up to whole tiles.
+inline int64_t wt_cache_ld(int64_t V) { return pad_ld((V + 255) / 256 * 256); }
+
 struct Plan {
   int64_t T = 0, d = 0, V = 0;
   int is_f32 = 0;
@@ -80,6 +83,8 @@ int32_t check_params(const pg_params* p) {
   if (!(p->veto_ratio >= 0.f)) return fail(PG_ERR_INVALID_ARG, "veto_ratio must be >= 0");
   if (p->dW_dtype != 0 && p->dW_dtype != 1) return fail(PG_ERR_INVALID_ARG, "unknown dW_dtype %d", p->dW_dtype);
   if (p->n_samples < 0) return fail(PG_ERR_INVALID_ARG, "n_samples must be >= 0");
+  if (p->w_transposed_valid != 0 && p->w_transposed_valid != 1) return fail(PG_ERR_INVALID_ARG, "w_transposed_valid must be 0 or 1");
+  if (p->w_transposed && (reinterpret_cast<uintptr_t>(p->w_transposed) & 15u)) return fail(PG_ERR_INVALID_ARG, "w_transposed must be 16-byte aligned");
   return PG_OK;
 }
 
@@ -378,6 +383,13 @@ size_t pg_workspace_bytes(int64_t T, int64_t d, int64_t V, int32_t S, const pg_p
   Plan pl;
   if (make_plan(T, d, V, S, h_params, which_call, pl) != PG_OK) return 0;
   return pl.total;
+}
+
+size_t pg_w_transposed_bytes(int64_t d, int64_t V) {
+  if (d < 1 || V < 1 || d % 64 != 0 || V > (1ll << 30)) return 0;
+  const int64_t ld = wt_cache_ld(V);
+  if ((uint64_t)ld * 2 * 256 >= FOUR_GIB) return 0;
+  return align_up((size_t)d * (size_t)ld * 2);
 }
 
 int64_t pg_backward_chunk_rows(int64_t T, int64_t d, int64_t V, int32_t S, const pg_params* h_params) {
@@ -690,7 +702,14 @@ int32_t loss_fwd_bwd(int sft, const void* H, const void* W, const int32_t* y, co
     const int tiles_c = (rows_valid + 255) / 256;
     const int kc = tiles_c * 256;
 
-    pg::launch_transpose_w(W, pl.is_f32, pl.V, d_i, v0, kc, pl.ld_v, at<__bf16>(ws, pl.WT), st);
+    // W^T of this chunk: in the workspace, or a column range of the caller's cache (filled here unless valid)
+    __bf16* wt = at<__bf16>(ws, pl.WT);
+    int ld_wt = pl.ld_v;
+    if (p.w_transposed) {
+      wt = static_cast<__bf16*>(p.w_transposed) + v0;
+      ld_wt = (int)wt_cache_ld(pl.V);
+    }
+    if (!p.w_transposed || !p.w_transposed_valid) pg::launch_transpose_w(W, pl.is_f32, pl.V, d_i, v0, kc, ld_wt, wt, st);
 
     pg::DlogitsArgs g{};
     g.W = Wop; g.Hc = at<__bf16>(ws, pl.Hc);
@@ -715,9 +734,9 @@ int32_t loss_fwd_bwd(int sft, const void* H, const void* W, const int32_t* y, co
     { ProfScope ps(PG_KERNEL_DW, st); pg::launch_gemm_store(w, st); }
 
     pg::StoreArgs h{};   // dHacc[t, :] (+)= sum_v dS[t, v] W^T[:, v]
-    h.A = at<__bf16>(ws, pl.dS); h.B = at<__bf16>(ws, pl.WT);
+    h.A = at<__bf16>(ws, pl.dS); h.B = wt;
     h.a_rows = pl.t_cap; h.b_rows = d_i;
-    h.lda = pl.ld_v; h.ldb = pl.ld_v; h.M = pl.t_cap; h.N = d_i; h.K = kc;
+    h.lda = pl.ld_v; h.ldb = ld_wt; h.M = pl.t_cap; h.N = d_i; h.K = kc;
     h.tiles_m = pl.tiles_t; h.tiles_n = (d_i + 255) / 256;
     h.C = at<float>(ws, pl.dHacc); h.ldc = d_i;
     h.accumulate = c > 0; h.out_bf16 = 0; h.k_from_ctl = 0; h.m_from_ctl = 1; h.split_k = 1; h.ctl = ctl;

@@ -29,8 +29,8 @@ def test_params_struct_layout_matches_header():
     src = open(os.path.join(ROOT, "include", "pg_head.h")).read()
     body = re.search(r"typedef struct pg_params \{(.*?)\} pg_params;", src, flags=re.S).group(1)
     body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
-    fields = re.findall(r"(int32_t|float)\s+(\w+)\s*;", body)
-    ctype = {"int32_t": C.c_int32, "float": C.c_float}
+    fields = re.findall(r"(int32_t|float|void\*)\s+(\w+)\s*;", body)
+    ctype = {"int32_t": C.c_int32, "float": C.c_float, "void*": C.c_void_p}
     assert [(n, ctype[t]) for t, n in fields] == list(B.PgParams._fields_)
 
 
@@ -51,6 +51,22 @@ def test_workspace_query_and_shape_errors():
     assert B.pg_workspace_bytes(8, 1 << 23, 1000, 0, P, 1) == 0 and "4 GiB" in B.pg_last_error()
     assert B.pg_workspace_bytes(1024, 64, 1000, 1, P, 5) == 0
     assert B.pg_workspace_bytes(0, 64, 1000, 0, P, 1) > 0          # empty microbatch is legal
+
+
+def test_w_transposed_cache_size_and_validation():
+    lib = B.lib()
+    n = int(lib.pg_w_transposed_bytes(5120, 151936))
+    assert 5120 * 151936 * 2 <= n <= 5120 * (151936 + 512) * 2 + 256
+    assert int(lib.pg_w_transposed_bytes(100, 1000)) == 0 and int(lib.pg_w_transposed_bytes(64, 0)) == 0
+    one = C.c_void_p(16)
+    p = B.Params().c_struct()
+    p.w_transposed = 8                       # misaligned cache pointer
+    rc = lib.pg_loss_fwd_bwd(one, one, one, one, one, 1, one, None, None, None, None, 8, 64, 100, C.byref(p), one, one, one,
+                             None, None, None, one, 1 << 30, None)
+    assert rc == -1 and "w_transposed" in B.pg_last_error()
+    p = B.Params().c_struct()
+    p.w_transposed_valid = 3
+    assert lib.pg_workspace_bytes(8, 64, 100, 1, C.byref(p), 1) == 0
 
 
 def test_invalid_arguments_return_error_codes():
