@@ -76,6 +76,7 @@ extern "C" {
 
 #define PG_CALL_LOGPROB_FWD 0
 #define PG_CALL_LOSS_FWD_BWD 1
+#define PG_CALL_LOSS_FWD_BWD_NORMED 2
 
 /* indices into counters_out[8] */
 #define PG_CNT_ACTIVE 0      /* loss tokens of kept samples */
@@ -316,6 +317,28 @@ size_t pg_rmsnorm_bwd_workspace_bytes(int64_t d);
 int32_t pg_rmsnorm_bwd(const void* X, const void* gamma, const void* dH, int64_t T, int64_t d, float eps,
                        int32_t dtype, void* dX_out, float* dgamma_out, void* workspace, size_t workspace_bytes,
                        void* stream);
+
+/*
+ * pg_loss_fwd_bwd with that normalisation fused around the head: the hidden states that enter the head
+ * are h_t = x_t rstd_t gamma (computed in fp32, rounded once to the storage dtype, exactly what
+ * pg_rmsnorm_fwd writes) and the call returns dX and dgamma instead of dH, i.e. what pg_rmsnorm_bwd
+ * gives for dH of pg_loss_fwd_bwd - except that dH reaches the normalisation's backward in fp32, not
+ * rounded to the storage dtype in between.  The forward is applied while the active rows are
+ * compacted (rows that are not active are never read) and the backward while the gradient rows are
+ * scattered, so the two extra passes over [T, d] of the separate calls disappear.
+ *   X [T,d], gamma [d]   in the dtype of h_params->dtype;  norm_eps >= 0
+ *   dX [T,d]             same dtype; rows that are not active are written as 0
+ *   dgamma_out [d]       float32, overwritten: sum over the active rows of dH_t xhat_t
+ * All other arguments, outputs and errors as pg_loss_fwd_bwd.  d must not exceed 8192.
+ * Workspace: pg_workspace_bytes(..., PG_CALL_LOSS_FWD_BWD_NORMED).
+ */
+int32_t pg_loss_fwd_bwd_normed(const void* X, const void* gamma, float norm_eps, const void* W, const int32_t* y,
+                               const uint8_t* loss_mask, const int32_t* cu_seqlens, int32_t S, const double* adv,
+                               const int32_t* seg_sample, const uint8_t* sample_keep, const float* old_logp,
+                               const float* rollout_logp, int64_t T, int64_t d, int64_t V, const pg_params* h_params,
+                               float* loss_out, void* dX, float* dgamma_out, void* dW, float* logp_out,
+                               float* entropy_out, int64_t* counters_out, void* workspace, size_t workspace_bytes,
+                               void* stream);
 
 /*
  * Vocab-sharded head: the quantities of pg_logprob_fwd and pg_loss_fwd_bwd (pi_train of Sec. 5.1,

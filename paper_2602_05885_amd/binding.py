@@ -19,9 +19,10 @@ LIB_PATH = os.path.join(_PKG, "libpg_head.so")
 PG_OK = 0
 CALL_LOGPROB_FWD = 0
 CALL_LOSS_FWD_BWD = 1
+CALL_LOSS_FWD_BWD_NORMED = 2
 COUNTER_NAMES = ("active", "clip_hi", "clip_lo", "seg_geo", "seg_veto", "truncated", "loss_tokens", "seg_dropped")
 
-EXPORTS = ("pg_last_error", "pg_init", "pg_workspace_bytes", "pg_backward_chunk_rows", "pg_w_transposed_bytes", "trloo_advantage", "pg_logprob_fwd", "pg_loss_fwd_bwd",
+EXPORTS = ("pg_last_error", "pg_init", "pg_workspace_bytes", "pg_backward_chunk_rows", "pg_w_transposed_bytes", "trloo_advantage", "pg_logprob_fwd", "pg_loss_fwd_bwd", "pg_loss_fwd_bwd_normed",
            "pg_sft_fwd_bwd", "pg_head_shard_fwd", "pg_head_partials_merge", "pg_head_partials_finish", "pg_loss_shard_bwd", "grpo_advantage",
            "turn_reward", "prs_retain", "pg_monitors_workspace_bytes", "pg_monitors", "pg_monitors_static", "pg_rmsnorm_fwd", "pg_rmsnorm_bwd_workspace_bytes", "pg_rmsnorm_bwd",
            "pg_profile_enable", "pg_profile_read")
@@ -100,6 +101,11 @@ def lib() -> C.CDLL:
                                       C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int64,
                                       C.c_int64, C.POINTER(PgParams), C.c_void_p, C.c_void_p, C.c_void_p,
                                       C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.pg_loss_fwd_bwd_normed.restype = C.c_int32
+        L.pg_loss_fwd_bwd_normed.argtypes = [C.c_void_p, C.c_void_p, C.c_float, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                             C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64,
+                                             C.c_int64, C.c_int64, C.POINTER(PgParams), C.c_void_p, C.c_void_p, C.c_void_p,
+                                             C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
         L.pg_sft_fwd_bwd.restype = C.c_int32
         L.pg_sft_fwd_bwd.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_int64,
                                      C.POINTER(PgParams), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
@@ -447,6 +453,39 @@ def pg_loss_fwd_bwd(H, W, y, loss_mask, cu_seqlens, adv, seg_sample, old_logp, r
                                  _ptr(loss), _ptr(dH), _ptr(dW), _ptr(logp), _ptr(ent), _ptr(counters),
                                  _ptr(workspace), workspace.numel(), _stream(stream)))
     return dict(loss=loss, dH=dH, dW=dW, logp=logp, entropy=ent, counters=counters)
+
+
+def pg_loss_fwd_bwd_normed(X, gamma, eps: float, W, y, loss_mask, cu_seqlens, adv, seg_sample, old_logp, rollout_logp,
+                           params: Params, workspace: torch.Tensor, dW: Optional[torch.Tensor] = None, out=None, stream=None,
+                           sample_keep: Optional[torch.Tensor] = None):
+    """pg_loss_fwd_bwd with the RMS normalisation h = x rstd gamma fused in front of the head and its backward
+    behind dH.  Returns dict(loss, dX, dgamma f32 [d], dW, logp, entropy, counters)."""
+    T, d, V, dev = _want_head(X, W, y, params)
+    _want("gamma", gamma, X.dtype, (d,), dev)
+    S = _want_loss_args(T, dev, loss_mask, cu_seqlens, adv, seg_sample, sample_keep, old_logp, rollout_logp)
+    _want_loss_out(out, T, d, V, dev, X.dtype, dW, params)
+    _want_workspace(workspace, dev)
+    _want_wt_cache(params, d, V, dev)
+    if out is None:
+        loss = torch.empty(1, dtype=torch.float32, device=dev)
+        dX = torch.empty_like(X)
+        logp = torch.empty(T, dtype=torch.float32, device=dev)
+        ent = torch.empty(T, dtype=torch.float32, device=dev)
+        counters = torch.empty(8, dtype=torch.int64, device=dev)
+    else:
+        loss, dX, logp, ent, counters = out
+    if dW is None:
+        if params.accumulate_dW:
+            raise ValueError("accumulate_dW needs an existing dW")
+        dW = torch.empty((V, d), dtype=torch.bfloat16 if params.dW_dtype else torch.float32, device=dev)
+    dgamma = torch.empty(d, dtype=torch.float32, device=dev)
+    p = params.c_struct()
+    p.n_samples = adv.numel()
+    _check(lib().pg_loss_fwd_bwd_normed(_ptr(X), _ptr(gamma), eps, _ptr(W), _ptr(y), _ptr(loss_mask), _ptr(cu_seqlens), S,
+                                        _ptr(adv), _ptr(seg_sample), _ptr(sample_keep), _ptr(old_logp), _ptr(rollout_logp),
+                                        T, d, V, C.byref(p), _ptr(loss), _ptr(dX), _ptr(dgamma), _ptr(dW), _ptr(logp),
+                                        _ptr(ent), _ptr(counters), _ptr(workspace), workspace.numel(), _stream(stream)))
+    return dict(loss=loss, dX=dX, dgamma=dgamma, dW=dW, logp=logp, entropy=ent, counters=counters)
 
 
 def pg_sft_fwd_bwd(H, W, y, loss_mask, params: Params, workspace: torch.Tensor, dW: Optional[torch.Tensor] = None,

@@ -65,7 +65,7 @@ struct Plan {
   int ld_t = 0;        // leading dimension of the [*, t_cap] scratch matrices
   int queue_words = 0; // tile-queue counters (8 per persistent launch)
   size_t ctl, counters, queue, flag, c_tok, a_tok, rows, pos, yc, zy, lse2, coefc, lossterm;
-  size_t part_m, part_s, part_u, Hc, HcT, Wc, dS, dST, WT, dHacc;
+  size_t part_m, part_s, part_u, Hc, HcT, Wc, dS, dST, WT, dHacc, rstd_c = 0, norm_partial = 0;
   size_t total = 0;
 };
 
@@ -91,7 +91,8 @@ int32_t check_params(const pg_params* p) {
 int32_t make_plan(int64_t T, int64_t d, int64_t V, int32_t S, const pg_params* p, int which, Plan& pl) {
   int32_t rc = check_params(p);
   if (rc) return rc;
-  if (which != PG_CALL_LOGPROB_FWD && which != PG_CALL_LOSS_FWD_BWD) return fail(PG_ERR_INVALID_ARG, "unknown call id %d", which);
+  if (which != PG_CALL_LOGPROB_FWD && which != PG_CALL_LOSS_FWD_BWD && which != PG_CALL_LOSS_FWD_BWD_NORMED)
+    return fail(PG_ERR_INVALID_ARG, "unknown call id %d", which);
   if (T < 0 || d < 1 || V < 1 || S < 0) return fail(PG_ERR_INVALID_ARG, "negative or zero extent (T=%lld d=%lld V=%lld S=%d)", (long long)T, (long long)d, (long long)V, S);
   if (d % 64 != 0) return fail(PG_ERR_UNSUPPORTED_SHAPE, "d=%lld is not a multiple of 64", (long long)d);
   if (T > (1ll << 30) || V > (1ll << 30)) return fail(PG_ERR_UNSUPPORTED_SHAPE, "T or V too large");
@@ -125,7 +126,12 @@ int32_t make_plan(int64_t T, int64_t d, int64_t V, int32_t S, const pg_params* p
   pl.Hc = take((size_t)t_cap * kd * 2);
   pl.Wc = pl.is_f32 ? take((size_t)V * kd * 2) : 0;
   pl.queue_words = pg::QUEUE_SET_WORDS * pg::queue_sets(0);
-  if (which == PG_CALL_LOSS_FWD_BWD) {
+  if (which == PG_CALL_LOSS_FWD_BWD_NORMED) {
+    if (d > pg::NORM_MAX_D) return fail(PG_ERR_UNSUPPORTED_SHAPE, "d=%lld: the fused normalisation takes d <= %d", (long long)d, pg::NORM_MAX_D);
+    pl.rstd_c = take((size_t)t_cap * 4);
+    pl.norm_partial = take((size_t)pg::NORM_STRIPS * d * 4);
+  }
+  if (which != PG_CALL_LOGPROB_FWD) {
     int64_t max_tiles = t_cap > 0 ? (int64_t)(ds_budget() / ((uint64_t)t_cap * 2 * 256)) : tiles_v;
     if (max_tiles < 1) max_tiles = 1;
     if (max_tiles > tiles_v) max_tiles = tiles_v;
@@ -261,7 +267,8 @@ T* at(void* ws, size_t off) { return reinterpret_cast<T*>(static_cast<char*>(ws)
 // y_offset: first vocab row of W within the whole vocabulary (0 unless W is a vocab shard).  With
 // comb.partials_in set, the contraction is skipped and the rows' states come from there.
 void run_forward(const Plan& pl, const pg_params& p, void* ws, const void* H, const void* W, const int32_t* y,
-                 int64_t y_offset, const pg::PrepArgs& prep, pg::CombineArgs comb, bool need_HT, hipStream_t st) {
+                 int64_t y_offset, const pg::PrepArgs& prep, pg::CombineArgs comb, bool need_HT, hipStream_t st,
+                 const pg::NormFuse* norm = nullptr) {
   pg::launch_prepass(prep, st);
   const void* Wop = W;
   if (pl.is_f32) {
@@ -274,7 +281,8 @@ void run_forward(const Plan& pl, const pg_params& p, void* ws, const void* H, co
   g.HcT = need_HT ? at<__bf16>(ws, pl.HcT) : nullptr;
   g.yc = at<int>(ws, pl.yc); g.ctl = at<pg::Ctl>(ws, pl.ctl); g.ld_t = pl.ld_t;
   g.y_offset = (int)y_offset; g.V = (int)pl.V;
-  pg::launch_gather(g, st);
+  if (norm) pg::launch_norm_gather(g, *norm, st);
+  else pg::launch_gather(g, st);
 
   pg::FwdArgs f{};
   f.W = Wop; f.Hc = at<__bf16>(ws, pl.Hc);
@@ -321,6 +329,13 @@ int32_t turn_advantage(const float* rewards, const uint8_t* valid, int32_t P, in
 // W as one vocab shard of a larger head: rows [v_offset, v_offset + V) of the vocabulary, the rows'
 // softmax states merged over all shards (nullptr: W is the whole head and the forward
 // contraction runs here), and whether dH (a partial sum over this shard) is written as fp32.
+// The normalisation fused around the head (pg_loss_fwd_bwd_normed): H of the call is X.
+struct NormIn {
+  const void* gamma;
+  float eps;
+  float* dgamma;
+};
+
 struct Shard {
   const float* partials = nullptr;
   int64_t v_offset = 0;
@@ -335,7 +350,7 @@ int32_t loss_fwd_bwd(int sft, const void* H, const void* W, const int32_t* y, co
                      const uint8_t* sample_keep, const float* old_logp, const float* rollout_logp, int64_t T, int64_t d,
                      int64_t V, const pg_params* h_params, float* loss_out, void* dH, void* dW, float* logp_out,
                      float* entropy_out, int64_t* counters_out, void* workspace, size_t workspace_bytes, void* stream,
-                     const Shard& shard);
+                     const Shard& shard, const NormIn* norm = nullptr);
 
 }  // namespace
 
@@ -442,6 +457,19 @@ int32_t pg_loss_fwd_bwd(const void* H, const void* W, const int32_t* y, const ui
   return loss_fwd_bwd(0, H, W, y, loss_mask, cu_seqlens, S, adv, seg_sample, sample_keep, old_logp, rollout_logp, T, d, V,
                       h_params, loss_out, dH, dW, logp_out, entropy_out, counters_out, workspace, workspace_bytes, stream,
                       Shard{});
+}
+
+int32_t pg_loss_fwd_bwd_normed(const void* X, const void* gamma, float norm_eps, const void* W, const int32_t* y,
+                               const uint8_t* loss_mask, const int32_t* cu_seqlens, int32_t S, const double* adv,
+                               const int32_t* seg_sample, const uint8_t* sample_keep, const float* old_logp,
+                               const float* rollout_logp, int64_t T, int64_t d, int64_t V, const pg_params* h_params,
+                               float* loss_out, void* dX, float* dgamma_out, void* dW, float* logp_out,
+                               float* entropy_out, int64_t* counters_out, void* workspace, size_t workspace_bytes,
+                               void* stream) {
+  const NormIn norm{gamma, norm_eps, dgamma_out};
+  return loss_fwd_bwd(0, X, W, y, loss_mask, cu_seqlens, S, adv, seg_sample, sample_keep, old_logp, rollout_logp, T, d, V,
+                      h_params, loss_out, dX, dW, logp_out, entropy_out, counters_out, workspace, workspace_bytes, stream,
+                      Shard{}, &norm);
 }
 
 int32_t pg_head_shard_fwd(const void* H, const void* W_shard, const int32_t* y, const uint8_t* row_mask, int64_t T,
@@ -639,17 +667,23 @@ int32_t loss_fwd_bwd(int sft, const void* H, const void* W, const int32_t* y, co
                      const uint8_t* sample_keep, const float* old_logp, const float* rollout_logp, int64_t T, int64_t d,
                      int64_t V, const pg_params* h_params, float* loss_out, void* dH, void* dW, float* logp_out,
                      float* entropy_out, int64_t* counters_out, void* workspace, size_t workspace_bytes, void* stream,
-                     const Shard& shard) {
+                     const Shard& shard, const NormIn* norm) {
   Plan pl;
-  int32_t rc = make_plan(T, d, V, S, h_params, PG_CALL_LOSS_FWD_BWD, pl);
+  int32_t rc = make_plan(T, d, V, S, h_params, norm ? PG_CALL_LOSS_FWD_BWD_NORMED : PG_CALL_LOSS_FWD_BWD, pl);
   if (rc) return rc;
   const pg_params& p = *h_params;
   if (!W || !loss_out || !dW) return fail(PG_ERR_INVALID_ARG, "W, loss_out and dW must not be NULL");
   if (misaligned(W) || misaligned(dW)) return fail(PG_ERR_INVALID_ARG, "W and dW must be 16-byte aligned");
   hipStream_t st = static_cast<hipStream_t>(stream);
   const size_t dw_elem = p.dW_dtype ? 2 : 4;
+  if (norm) {
+    if (!norm->gamma || !norm->dgamma) return fail(PG_ERR_INVALID_ARG, "gamma and dgamma_out must not be NULL");
+    if (misaligned(norm->gamma)) return fail(PG_ERR_INVALID_ARG, "gamma must be 16-byte aligned");
+    if (!(norm->eps >= 0.f) || !std::isfinite(norm->eps)) return fail(PG_ERR_INVALID_ARG, "norm_eps must be finite and >= 0");
+  }
   if (T == 0) {   // empty microbatch: zero loss, zero gradient
     const LaunchGuard guard;
+    if (norm) pg::launch_fill_f32(norm->dgamma, (size_t)d, 0.f, st);
     pg::launch_fill_f32(loss_out, 1, 0.f, st);
     if (counters_out) pg::launch_fill_zero_bytes(counters_out, 8 * sizeof(int64_t), st);
     if (!p.accumulate_dW) pg::launch_fill_zero_bytes(dW, (size_t)V * d * dw_elem, st);
@@ -685,7 +719,12 @@ int32_t loss_fwd_bwd(int sft, const void* H, const void* W, const int32_t* y, co
   comb.coefc = at<float>(ws, pl.coefc); comb.lossterm = at<float>(ws, pl.lossterm);
   comb.counters = at<unsigned long long>(ws, pl.counters);
   comb.partials_in = shard.partials;
-  run_forward(pl, p, ws, H, W, y, shard.v_offset, prep, comb, true, st);
+  pg::NormFuse nf{};
+  if (norm) {
+    nf.X = H; nf.gamma = norm->gamma; nf.eps = norm->eps; nf.dgamma = norm->dgamma;
+    nf.rstd_c = at<float>(ws, pl.rstd_c); nf.partial = at<float>(ws, pl.norm_partial);
+  }
+  run_forward(pl, p, ws, H, W, y, shard.v_offset, prep, comb, true, st, norm ? &nf : nullptr);
 
   pg::FinishArgs fin{at<float>(ws, pl.lossterm), at<unsigned long long>(ws, pl.counters), loss_out,
                      reinterpret_cast<long long*>(counters_out), at<pg::Ctl>(ws, pl.ctl)};
@@ -747,8 +786,9 @@ int32_t loss_fwd_bwd(int sft, const void* H, const void* W, const int32_t* y, co
   const int kc0 = (int)(((pl.V < pl.vc ? pl.V : pl.vc) + 255) / 256 * 256);      // contraction length of the first chunk
   pg::ScatterArgs sc{at<float>(ws, pl.dHacc), at<int>(ws, pl.pos), dH, (int)pl.T, d_i, pl.is_f32 || shard.dH_f32,
                      1, pl.t_cap, (d_i + 255) / 256, kc0 / 64, ctl};
-  pg::launch_scatter_dh(sc, st);
-  return guard.check(shard.what ? shard.what : sft ? "pg_sft_fwd_bwd" : "pg_loss_fwd_bwd");
+  if (norm) pg::launch_scatter_dx_norm(sc, nf, st);
+  else pg::launch_scatter_dh(sc, st);
+  return guard.check(shard.what ? shard.what : sft ? "pg_sft_fwd_bwd" : norm ? "pg_loss_fwd_bwd_normed" : "pg_loss_fwd_bwd");
 }
 
 }  // namespace

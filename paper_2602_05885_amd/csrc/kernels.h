@@ -188,6 +188,21 @@ struct ScatterArgs {
 };
 void launch_scatter_dh(const ScatterArgs& a, hipStream_t s);
 
+// RMS normalisation fused around the head (h = x rstd gamma in front of it, its backward behind dH):
+// the forward is applied while the active rows are compacted, the backward while dH is scattered.
+struct NormFuse {
+  const void* X;        // [T, d] bf16 or fp32: the rows in front of the normalisation
+  const void* gamma;    // [d] same dtype
+  float eps;
+  float* rstd_c;        // [t_cap] workspace: 1 / rms of every compacted row
+  float* partial;       // [NORM_STRIPS, d] workspace: dgamma partial sums
+  float* dgamma;        // [d] output
+};
+// Hc[i, :] = normalised row rows[i] of X (zeros on padding), yc[i] as launch_gather; then Hc -> HcT.
+void launch_norm_gather(const GatherArgs& g, const NormFuse& n, hipStream_t s);
+// dX[t, :] = RMSNorm backward of the accumulated dH row of t (zeros for rows that are not active); dgamma.
+void launch_scatter_dx_norm(const ScatterArgs& a, const NormFuse& n, hipStream_t s);
+
 // out[t] = merge(a[t], b[t]) of two per-row softmax states (m, s, u, z_y), [T][4] each.
 void launch_merge_partials(const float* a, const float* b, float* out, long long T, hipStream_t s);
 // logsumexp = m + ln s, log-prob = z_y - logsumexp, entropy = ln s - u / s per row; 0 on empty rows.

@@ -931,4 +931,200 @@ void launch_rmsnorm_bwd(const NormArgs& a, hipStream_t s) {
   hipLaunchKernelGGL(rmsnorm_dgamma_kernel, dim3((a.d + 31) / 32), dim3(256), 0, s, a);
 }
 
+
+// ------------------------------------------------------------------ RMSNorm fused around the head
+// Forward, fused into the row compaction: one wavefront per compacted row reads the row of X once,
+// keeps it in registers between the sum of squares and the scaling (as rmsnorm_fwd_kernel), rounds
+// h = x rstd gamma to bf16 (fp32 inputs: splits it into bf16 hi + lo parts, [hi | hi | lo] along k) and
+// writes it as the head's compacted operand row; rows that are not active are never read.
+template <bool F32>
+__global__ __launch_bounds__(256) void norm_gather_kernel(GatherArgs a, NormFuse n) {
+  const Ctl ctl = *a.ctl;
+  const int lane = threadIdx.x & 63;
+  const int i = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (i >= ctl.n_pad) return;
+  const bool live = i < ctl.n_active;
+  const int t = live ? a.rows[i] : 0;
+  if (lane == 0) {
+    int yl = -1;
+    if (live) {
+      yl = a.y[t] - a.y_offset;
+      if (yl < 0 || yl >= a.V) yl = -1;
+    }
+    a.yc[i] = yl;
+  }
+  Raw8<F32> raw[NORM_FC];
+  if (live) {
+#pragma unroll
+    for (int q = 0; q < NORM_FC; ++q) {
+      const int c = lane * 8 + q * 512;
+      if (c < a.d) raw_load(n.X, (long long)t * a.d + c, raw[q]);
+    }
+  }
+  float ss = 0.f;
+  if (live) {
+#pragma unroll
+    for (int q = 0; q < NORM_FC; ++q) {
+      const int c = lane * 8 + q * 512;
+      if (c < a.d) {
+        float x[8];
+        raw_unpack(raw[q], x);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) ss = fmaf(x[e], x[e], ss);
+      }
+    }
+  }
+  ss = wave_sum(ss);
+  const float rstd = live ? 1.f / sqrtf(ss / (float)a.d + n.eps) : 0.f;
+  if (lane == 0) n.rstd_c[i] = rstd;
+  const int ldh = F32 ? 3 * a.d : a.d;
+#pragma unroll
+  for (int q = 0; q < NORM_FC; ++q) {
+    const int c = lane * 8 + q * 512;
+    if (c < a.d) {
+      float h[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+      if (live) {
+        float x[8], g[8];
+        raw_unpack(raw[q], x);
+        load8<F32>(n.gamma, c, g);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) h[e] = x[e] * rstd * g[e];
+      }
+      __bf16* o = a.Hc + (size_t)i * ldh + c;
+      if (F32) {
+        bf16x8 hi, lo;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) { __bf16 x, y; split_bf16(h[e], x, y); hi[e] = x; lo[e] = y; }
+        *reinterpret_cast<bf16x8*>(o) = hi;
+        *reinterpret_cast<bf16x8*>(o + a.d) = hi;
+        *reinterpret_cast<bf16x8*>(o + 2 * a.d) = lo;
+      } else {
+        bf16x8 v;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] = (__bf16)h[e];
+        *reinterpret_cast<bf16x8*>(o) = v;
+      }
+    }
+  }
+}
+
+// HcT[j, i] = Hc[i, j] for the first d columns (the bf16 operand, or the hi parts of a split fp32 one).
+__global__ __launch_bounds__(256) void transpose_hc_kernel(const __bf16* Hc, int ldh, __bf16* HcT, int ld_t, const Ctl* ctlp) {
+  __shared__ __attribute__((aligned(16))) uint16_t tile[64 * TT_LD];
+  const int i0 = blockIdx.x * 64, j0 = blockIdx.y * 64;
+  if (i0 >= ctlp->n_pad) return;
+  const int tid = threadIdx.x, chunk = tid & 7;
+#pragma unroll
+  for (int p = 0; p < 2; ++p) {
+    const int r = (tid >> 3) + 32 * p;
+    tt_put(tile, r, chunk, *reinterpret_cast<const i32x4*>(Hc + (size_t)(i0 + r) * ldh + j0 + chunk * 8));
+  }
+  __syncthreads();
+#pragma unroll
+  for (int p = 0; p < 2; ++p) {
+    const int jj = (tid >> 3) + 32 * p;
+    *reinterpret_cast<i32x4*>(HcT + (size_t)(j0 + jj) * ld_t + i0 + chunk * 8) = tt_get(tile, jj, chunk);
+  }
+}
+
+void launch_norm_gather(const GatherArgs& g, const NormFuse& n, hipStream_t s) {
+  if (g.is_f32) hipLaunchKernelGGL(norm_gather_kernel<true>, dim3(g.t_cap / 4), dim3(256), 0, s, g, n);
+  else hipLaunchKernelGGL(norm_gather_kernel<false>, dim3(g.t_cap / 4), dim3(256), 0, s, g, n);
+  if (g.HcT)
+    hipLaunchKernelGGL(transpose_hc_kernel, dim3(g.t_cap / 64, g.d / 64), dim3(256), 0, s, g.Hc, g.is_f32 ? 3 * g.d : g.d,
+                       g.HcT, g.ld_t, g.ctl);
+}
+
+// Backward, fused into the scatter of dH: workgroup b owns a contiguous strip of the T original rows
+// (as rmsnorm_bwd_kernel) and a thread the same (up to) 4 x 8 columns of every row.  For an active row
+// the accumulated fp32 gradient g of its compacted position (split-K slabs added in order) and the
+// row of X are read once, rstd comes from the forward,
+//   dx = rstd (gamma g - xhat mean_j(gamma_j g_j xhat_j)),  xhat = x rstd,
+// and g xhat is added to the thread's dgamma partial sums; rows that are not active are written as
+// zeros and nothing of theirs is read.  The strips' partials are folded by rmsnorm_dgamma_kernel.
+template <bool F32>
+__global__ __launch_bounds__(256) void scatter_dx_norm_kernel(ScatterArgs a, NormFuse n) {
+  __shared__ float red[4];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const long long T = a.T;
+  const long long R = (T + NORM_STRIPS - 1) / NORM_STRIPS;
+  const long long r0 = (long long)blockIdx.x * R, r1 = r0 + R < T ? r0 + R : T;
+  const int n_pad = a.ctl->n_pad;
+  const int ks = a.split_k ? dh_split(n_pad, a.t_cap, a.tiles_n, a.k_stages) : 1;
+  const size_t slab = (size_t)n_pad * a.d;
+  float dg[NORM_NC][8], gam[NORM_NC][8];
+#pragma unroll
+  for (int q = 0; q < NORM_NC; ++q) {
+    const int c = tid * 8 + q * 2048;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { dg[q][e] = 0.f; gam[q][e] = 0.f; }
+    if (c < a.d) load8<F32>(n.gamma, c, gam[q]);
+  }
+  const float inv_d = 1.f / (float)a.d;
+  for (long long row = r0; row < r1; ++row) {
+    const int p = a.pos[row];                       // uniform over the workgroup
+    if (p < 0) {
+#pragma unroll
+      for (int q = 0; q < NORM_NC; ++q) {
+        const int c = tid * 8 + q * 2048;
+        const float z[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        if (c < a.d) store8<F32>(a.dH, row * a.d + c, z);
+      }
+      continue;
+    }
+    const float rstd = n.rstd_c[p];
+    float x[NORM_NC][8], g[NORM_NC][8];
+    float dot = 0.f;
+#pragma unroll
+    for (int q = 0; q < NORM_NC; ++q) {
+      const int c = tid * 8 + q * 2048;
+      if (c < a.d) {
+        load8<F32>(n.X, row * a.d + c, x[q]);
+        load8<true>(a.acc, (long long)p * a.d + c, g[q]);
+        for (int s2 = 1; s2 < ks; ++s2) {           // split-K slabs, added in a fixed order
+          float w[8];
+          load8<true>(a.acc, (long long)(s2 * slab) + (long long)p * a.d + c, w);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) g[q][e] += w[e];
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) dot = fmaf(gam[q][e] * g[q][e], x[q][e] * rstd, dot);
+      }
+    }
+    __syncthreads();                                // red[] of the previous row has been read by everybody
+    dot = block_sum4(dot, red, lane, wave) * inv_d;
+#pragma unroll
+    for (int q = 0; q < NORM_NC; ++q) {
+      const int c = tid * 8 + q * 2048;
+      if (c < a.d) {
+        float dx[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const float xh = x[q][e] * rstd;
+          dx[e] = rstd * (gam[q][e] * g[q][e] - xh * dot);
+          dg[q][e] = fmaf(g[q][e], xh, dg[q][e]);
+        }
+        store8<F32>(a.dH, row * a.d + c, dx);
+      }
+    }
+  }
+  float* part = n.partial + (size_t)blockIdx.x * a.d;
+#pragma unroll
+  for (int q = 0; q < NORM_NC; ++q) {
+    const int c = tid * 8 + q * 2048;
+    if (c < a.d) {
+      *reinterpret_cast<float4*>(part + c) = make_float4(dg[q][0], dg[q][1], dg[q][2], dg[q][3]);
+      *reinterpret_cast<float4*>(part + c + 4) = make_float4(dg[q][4], dg[q][5], dg[q][6], dg[q][7]);
+    }
+  }
+}
+
+void launch_scatter_dx_norm(const ScatterArgs& a, const NormFuse& n, hipStream_t s) {
+  if (a.out_f32) hipLaunchKernelGGL(scatter_dx_norm_kernel<true>, dim3(NORM_STRIPS), dim3(256), 0, s, a, n);
+  else hipLaunchKernelGGL(scatter_dx_norm_kernel<false>, dim3(NORM_STRIPS), dim3(256), 0, s, a, n);
+  NormArgs f{};
+  f.d = a.d; f.partial = n.partial; f.dgamma = n.dgamma;
+  hipLaunchKernelGGL(rmsnorm_dgamma_kernel, dim3((a.d + 31) / 32), dim3(256), 0, s, f);
+}
+
 }  // namespace pg

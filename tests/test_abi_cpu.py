@@ -136,6 +136,24 @@ def test_rmsnorm_entry_points_validate_arguments():
     assert lib.pg_rmsnorm_bwd(one, one, one, 4, 64, -1.0, 0, one, one, one, 1 << 30, None) == -1
 
 
+def test_fused_norm_entry_point_validates_arguments():
+    lib = B.lib()
+    one = C.c_void_p(16)
+    p = B.Params().c_struct()
+    big = 1 << 30
+    call = lambda gamma, eps, dg, d, ws: lib.pg_loss_fwd_bwd_normed(one, gamma, eps, one, one, one, one, 1, one, None, None, None,
+                                                                    None, 8, d, 100, C.byref(p), one, one, dg, one, None, None,
+                                                                    None, one, ws, None)
+    assert call(None, 1e-6, one, 64, big) == -1 and "gamma" in B.pg_last_error()
+    assert call(one, 1e-6, None, 64, big) == -1
+    assert call(one, -1.0, one, 64, big) == -1 and "norm_eps" in B.pg_last_error()
+    assert call(one, 1e-6, one, 16384, big) == -2
+    assert call(one, 1e-6, one, 64, 16) == -3
+    n1 = B.pg_workspace_bytes(1024, 64, 1000, 4, B.Params(), B.CALL_LOSS_FWD_BWD)
+    n2 = B.pg_workspace_bytes(1024, 64, 1000, 4, B.Params(), B.CALL_LOSS_FWD_BWD_NORMED)
+    assert n2 > n1 > 0
+
+
 def test_shard_entry_points_validate_arguments():
     lib = B.lib()
     one = C.c_void_p(16)      # never dereferenced: validation fails first

@@ -214,6 +214,66 @@ def test_rmsnorm_feeds_the_head(dev):
     assert rel_fro(dg.double().cpu().numpy(), dg_ref) <= TOL_GRAD
 
 
+@pytest.mark.parametrize("dtype,mode,kind,seed", [("bf16", 2, "token", 71), ("bf16", 1, "window", 72), ("f32", 0, "none", 73)])
+def test_loss_with_fused_rmsnorm(dev, monkeypatch, dtype, mode, kind, seed):
+    """pg_loss_fwd_bwd_normed (normalisation applied while the rows are compacted, its backward while dH is
+    scattered) against the oracle's chain rmsnorm_fwd -> pg_loss_fwd_bwd -> rmsnorm_bwd, several vocab chunks,
+    masked and rejected rows; and against the separate calls of the library (same kernels around the head)."""
+    from tests._cases import segment_offsets, ratio_targets, block_rel_fro
+    spec = synth.small_spec(seed=seed, d=192, V=2300, dtype=dtype, P=3, K=4, Tmax=3)
+    batch = synth.make_batch(spec)
+    T, d, V, S = batch.T, spec.d, spec.V, batch.S
+    monkeypatch.setenv("PG_HEAD_DS_BUDGET_BYTES", str(((T + 255) // 256 * 256) * 2 * 256 * 3))
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    rng = np.random.default_rng(seed)
+    eps = 1e-5
+    X = torch.from_numpy((rng.normal(size=(T, d)) * rng.uniform(0.3, 3.0, size=(T, 1))).astype(np.float32)).to(dev).to(tdt)
+    gamma = torch.from_numpy(rng.normal(1.0, 0.2, size=d).astype(np.float32)).to(dev).to(tdt)
+    _, W, y = synth.make_head(T, d, V, dtype, spec.seed, dev, unit_rms=True, w_std=0.02 if dtype == "bf16" else 0.1)
+    # oracle chain; the head sees h rounded to the storage dtype
+    H_ref, _ = O.rmsnorm_fwd(np64(X), np64(gamma), eps)
+    H_bits = torch.from_numpy(H_ref).to(tdt).double().numpy()
+    Wn, yn = np64(W), y.cpu().numpy().astype(np.int64)
+    base = O.lm_head_logprob(H_bits, Wn, yn, 1.0)[0]
+    old = (base - np.log(ratio_targets(T, seed))).astype(np.float32)
+    rollout = (old.astype(np.float64) - segment_offsets(batch, seed, kind)).astype(np.float32)
+    _, A, _ = O.trloo_advantage(batch.rewards, batch.valid, 1.0)
+    ref = O.pg_loss_fwd_bwd(H_bits, Wn, yn, batch.loss_mask, batch.cu_seqlens, A.reshape(-1)[batch.seg_sample],
+                            old, rollout if mode else None, O.Params(mismatch_mode=mode))
+    dX_ref, dg_ref = O.rmsnorm_bwd(np64(X), np64(gamma), eps, ref["dH"])
+    # library, fused
+    to = lambda a: torch.from_numpy(a).to(dev)
+    prm = B.Params(dtype=0 if dtype == "bf16" else 1, mismatch_mode=mode)
+    adv, _, _ = B.trloo_advantage(to(batch.rewards), to(batch.valid), 1.0)
+    args = (to(batch.loss_mask), to(batch.cu_seqlens), adv.reshape(-1), to(batch.seg_sample), to(old),
+            to(rollout) if mode else None)
+    ws = B.alloc_workspace(T, d, V, S, prm, B.CALL_LOSS_FWD_BWD_NORMED, dev)
+    out = B.pg_loss_fwd_bwd_normed(X, gamma, eps, W, y, *args, prm, ws)
+    out2 = B.pg_loss_fwd_bwd_normed(X, gamma, eps, W, y, *args, prm, ws)
+    torch.cuda.synchronize()
+    tol_lp = TOL_LOGP if dtype == "bf16" else 2e-4
+    assert np.array_equal(out["counters"].cpu().numpy(), ref["counters"])
+    assert 0 < ref["counters"][0] < T
+    assert np.abs(out["logp"].cpu().numpy() - ref["logp"]).max() <= tol_lp
+    assert np.abs(out["entropy"].cpu().numpy() - ref["entropy"]).max() <= tol_lp
+    assert abs(float(out["loss"][0]) - ref["loss"]) <= TOL_LOSS * abs(ref["loss"])
+    e_dx, e_dg, e_dw = rel_fro(np64(out["dX"]), dX_ref), rel_fro(out["dgamma"].double().cpu().numpy(), dg_ref), rel_fro(np64(out["dW"]), ref["dW"])
+    print(f"[fused norm {dtype} mode {mode}] dX {e_dx:.2e} (worst block {block_rel_fro(np64(out['dX']), dX_ref):.2e}) dgamma {e_dg:.2e} dW {e_dw:.2e}")
+    assert e_dx <= TOL_GRAD and e_dg <= TOL_GRAD and e_dw <= TOL_GRAD
+    assert block_rel_fro(np64(out["dX"]), dX_ref) <= TOL_GRAD
+    assert np.all(np64(out["dX"])[~ref["active"]] == 0)
+    for k in ("loss", "dX", "dgamma", "dW", "logp"):
+        assert torch.equal(out[k], out2[k]), k                                      # fixed reduction orders
+    # the separate calls (normalise every row, head, backward of the normalisation) agree with the fused one
+    H, _ = B.pg_rmsnorm_fwd(X, gamma, eps, want_rstd=False)
+    ws1 = B.alloc_workspace(T, d, V, S, prm, B.CALL_LOSS_FWD_BWD, dev)
+    sep = B.pg_loss_fwd_bwd(H, W, y, *args, prm, ws1)
+    dX_sep, dg_sep = B.pg_rmsnorm_bwd(X, gamma, sep["dH"], eps)
+    torch.cuda.synchronize()
+    assert torch.equal(sep["logp"], out["logp"]) and torch.equal(sep["dW"], out["dW"]) and torch.equal(sep["loss"], out["loss"])
+    assert rel_fro(np64(dX_sep), np64(out["dX"])) <= 5e-3 and rel_fro(dg_sep.double().cpu().numpy(), out["dgamma"].double().cpu().numpy()) <= 5e-3
+
+
 # ------------------------------------------------------------------------------------ the whole recipe
 @pytest.mark.parametrize("mode,kind,seed", [(1, "window", 41), (2, "token", 42)])
 def test_recipe_reward_prs_trloo_loss(dev, monkeypatch, mode, kind, seed):
