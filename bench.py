@@ -365,21 +365,24 @@ def main():
     ms_step = dt / args.steps * 1e3
     tokens_per_s = n_active * args.steps / dt
 
-    # ---- roofline of the dominant kernel (gemm_store_kernel: the dW and dH contractions) ----
-    flop_token = 2.0 * d * V                                  # one contraction, per active token
+    # ---- roofline of the dominant kernel ----
+    # Algorithmic flops of each launch class per step: every class is one contraction over the whole
+    # vocabulary, 2 d V flops per active token.
+    rows_of = {"fwd": V, "dlogits": V, "dw": V, "dh": V}
     kernel_of = {"fwd": "lmhead_fwd_kernel", "dlogits": "lmhead_dlogits_kernel", "dw": "gemm_store_kernel",
                  "dh": "gemm_store_kernel"}
     kern = {}
     for k, (ms, n) in prof.items():
         if n:
+            fl = 2.0 * d * rows_of[k] * n_active                      # per step
             kern[k] = {"kernel": kernel_of[k], "launches_per_step": n / args.steps, "ms_per_step": ms / args.steps,
-                       "avg_launch_ms": ms / n, "tflops": flop_token * n_active * args.steps / (ms * 1e-3) / 1e12}
+                       "avg_launch_ms": ms / n, "flop_per_step": fl, "tflops": fl * args.steps / (ms * 1e-3) / 1e12}
     by_kernel = {}
     for k, v in kern.items():
         b = by_kernel.setdefault(v["kernel"], {"ms": 0.0, "launches": 0.0, "flop": 0.0})
         b["ms"] += v["ms_per_step"]
         b["launches"] += v["launches_per_step"]
-        b["flop"] += flop_token * n_active
+        b["flop"] += v["flop_per_step"]
     dom = max(by_kernel, key=lambda k: by_kernel[k]["ms"])
     b = by_kernel[dom]
     achieved = b["flop"] / (b["ms"] * 1e-3) / 1e12

@@ -199,23 +199,39 @@ __global__ __launch_bounds__(NTHREADS) void lmhead_fwd_kernel(FwdArgs a) { lmhea
 // (dS [t_cap, ld_s] for dH, dS^T [vc, ld_t] for dW).  Both go through an LDS transposition
 // stage so that global stores are 16 B per lane and 512 B per row.
 // ------------------------------------------------------------------------------------
-constexpr int DLOGITS_CLAIM_OFF = GEMM_LDS_BYTES;      // behind the epilogue's staging area
-constexpr int DLOGITS_LDS_BYTES = DLOGITS_CLAIM_OFF + 16;
+// Where the persistent kernels keep the word that hands a claimed tile to all wavefronts: behind the
+// recompute epilogue's staging area (the largest LDS user).
+constexpr int CLAIM_OFF = GEMM_LDS_BYTES;
+constexpr int PERSISTENT_LDS_BYTES = CLAIM_OFF + 16;
 
-__global__ __launch_bounds__(NTHREADS) void lmhead_dlogits_kernel(DlogitsArgs a) {
-  const Ctl ctl = *a.ctl;
-  const int tiles_t = min(a.tiles_t, ctl.n_pad / BN);   // live token tiles: known only on the device
+// Takes tiles from the queue until it has none for this workgroup: with steal = false the XCD's own
+// share only, with steal = true the own share first and then whatever is left on other XCDs.
+// tile(b, after_loop, before_stores) computes the tile with workgroup index b (TileQueue::encode) and
+// calls the two hooks once each, on every thread: after_loop behind its main loop's last load (the
+// claim for the next tile is issued there: memory operations return in order, an atomic in front of
+// the loads would hold up their completion), before_stores at a point that at least one workgroup
+// barrier separates from the end of the tile and that lies before the tile's own global stores
+// (the claim is picked up there; later it would wait for those stores to complete).
+template <class TileFn>
+__device__ __forceinline__ void drain_queue(const TileQueue& Q, bool steal, volatile int* claim, TileFn&& tile) {
+  const int tid = threadIdx.x;
+  int b = queue_broadcast(claim, tid == 0 ? Q.resolve(Q.ticket(), steal) : 0);
+  while (b >= 0) {
+    // (ticket is left uninitialised on the other threads on purpose: a merged value would make the
+    // compiler wait for the atomic where it is issued)
+    unsigned ticket;
+    tile(b, [&]() { if (tid == 0) ticket = Q.ticket(); }, [&]() { if (tid == 0) claim[0] = Q.resolve(ticket, steal); });
+    b = __builtin_amdgcn_readfirstlane(claim[0]);
+    // every wavefront is done with the tile's LDS before the next tile's loads land in it
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+  }
+}
+
+template <class AfterLoop, class BeforeStores>
+__device__ __forceinline__ void dlogits_tile(const DlogitsArgs& a, int tm, int tn, AfterLoop&& after_loop,
+                                             BeforeStores&& before_stores) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WN, wn = wave % WN;
-  TileQueue Q;
-  Q.init(a.queue, a.tiles_v * tiles_t, 0);
-  volatile int* claim = reinterpret_cast<volatile int*>(g_smem + DLOGITS_CLAIM_OFF);
-  int b = queue_broadcast(claim, tid == 0 ? Q.resolve(Q.ticket()) : 0);
-
-  // persistent: one workgroup per compute unit takes tiles from the XCD-aware queue until none is left
-  while (b >= 0) {
-  int tm, tn;
-  map_tile(b, a.tiles_v, tiles_t, tm, tn);
 
   TileLoader LA, LB;
   LA.init(a.W, a.w_rows, a.v0 + tm * BM, a.ldw, 0u, tid);
@@ -223,11 +239,7 @@ __global__ __launch_bounds__(NTHREADS) void lmhead_dlogits_kernel(DlogitsArgs a)
   f32x4 acc[GM][GN];
   zero_acc(acc);
   mainloop(LA, LB, a.K / BK, g_smem, acc);
-  // claim the next tile: issued behind the main loop's loads (memory operations return in order) and
-  // picked up after the exponentials.  (Left uninitialised on the other threads on purpose: a merged
-  // value would make the compiler wait for the atomic right here.)
-  unsigned ticket;
-  if (tid == 0) ticket = Q.ticket();
+  after_loop();
 
   const int v_base = a.v0 + tm * BM + wm * WROWS;     // global vocab index
   const bool ragged = (a.v0 + tm * BM + BM > a.V);
@@ -284,7 +296,7 @@ __global__ __launch_bounds__(NTHREADS) void lmhead_dlogits_kernel(DlogitsArgs a)
       *reinterpret_cast<uint2*>(st + tok_l * EPI_STRIDE + v_l * 2) = two;
     }
   }
-  if (tid == 0) claim[0] = Q.resolve(ticket);       // before this tile's stores, whose completion it would wait for
+  before_stores();
   __syncthreads();
   {
     const int chunk = tid & 31, r0 = tid >> 5;
@@ -336,10 +348,20 @@ __global__ __launch_bounds__(NTHREADS) void lmhead_dlogits_kernel(DlogitsArgs a)
       __builtin_nontemporal_store(v, reinterpret_cast<i32x4*>(dst + (size_t)row * a.ld_t));
     }
   }
-  b = __builtin_amdgcn_readfirstlane(claim[0]);
-  // every wavefront is done with the staging area before the next tile's loads land in it
-  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-  }   // while (b >= 0)
+}
+
+__global__ __launch_bounds__(NTHREADS) void lmhead_dlogits_kernel(DlogitsArgs a) {
+  const Ctl ctl = *a.ctl;
+  const int tiles_t = min(a.tiles_t, ctl.n_pad / BN);   // live token tiles: known only on the device
+  TileQueue Q;
+  Q.init(a.queue, a.tiles_v * tiles_t, 0);
+  volatile int* claim = reinterpret_cast<volatile int*>(g_smem + CLAIM_OFF);
+  // persistent: one workgroup per compute unit takes tiles from the XCD-aware queue until none is left
+  drain_queue(Q, true, claim, [&](int b, auto&& after_loop, auto&& before_stores) {
+    int tm, tn;
+    map_tile(b, a.tiles_v, tiles_t, tm, tn);
+    dlogits_tile(a, tm, tn, after_loop, before_stores);
+  });
 }
 
 // ------------------------------------------------------------------------------------
@@ -385,48 +407,57 @@ __device__ __forceinline__ void store_tile(const StoreArgs& a, int tm, int tn, i
   }
 }
 
-constexpr int STORE_CLAIM_OFF = 2 * STAGE_BYTES;
-constexpr int STORE_LDS_BYTES = STORE_CLAIM_OFF + 16;
+// The run-time extents of a store contraction (the padded active-token count is known only on the device).
+struct StoreShape {
+  int m_lim, tiles_m, K, ks, total;
+  __device__ __forceinline__ void init(const StoreArgs& a, const Ctl& ctl) {
+    m_lim = a.m_from_ctl ? min(a.M, ctl.n_pad) : a.M;
+    tiles_m = min(a.tiles_m, (m_lim + BM - 1) / BM);
+    K = a.k_from_ctl ? ctl.n_pad : a.K;
+    ks = (a.split_k && a.m_from_ctl) ? dh_split(ctl.n_pad, a.M, a.tiles_n, K / BK) : 1;
+    total = tiles_m * ks * a.tiles_n;
+  }
+};
+
+template <class AfterLoop, class BeforeStores>
+__device__ __forceinline__ void gemm_store_tile(StoreArgs a, const StoreShape& sh, int n_pad, int b, AfterLoop&& after_loop,
+                                                BeforeStores&& before_stores) {
+  const int tid = threadIdx.x;
+  int tm, tn;
+  map_tile_interleaved(b, sh.tiles_m * sh.ks, a.tiles_n, tm, tn);
+  const int part = tm / sh.tiles_m;                    // 0 unless the contraction is split
+  tm -= part * sh.tiles_m;
+  const int s0 = (int)((long long)part * (sh.K / BK) / sh.ks), s1 = (int)((long long)(part + 1) * (sh.K / BK) / sh.ks);
+  const uint32_t kb = (uint32_t)s0 * BK * 2u;          // byte offset of this part's first k
+
+  // (a tile here is hundreds of stages long: the claim for the next one simply travels under the main loop)
+  after_loop();
+  TileLoader LA, LB;
+  LA.init(a.B, a.b_rows, tn * BN, a.ldb, kb, tid);     // engine rows <- n
+  LB.init(a.A, a.a_rows, tm * BM, a.lda, kb, tid);     // engine columns <- m
+  f32x4 acc[GM][GN];
+  zero_acc(acc);
+  mainloop(LA, LB, s1 - s0, g_smem, acc);
+  before_stores();
+  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");   // the claim is visible behind this barrier
+  a.C = static_cast<char*>(a.C) + (size_t)part * n_pad * a.ldc * (a.out_bf16 ? 2 : 4);
+  if (a.out_bf16)
+    store_tile<__bf16>(a, tm, tn, sh.m_lim, acc);
+  else
+    store_tile<float>(a, tm, tn, sh.m_lim, acc);
+}
 
 __global__ __launch_bounds__(NTHREADS) void gemm_store_kernel(StoreArgs a) {
   const Ctl ctl = *a.ctl;
-  const int m_lim = a.m_from_ctl ? min(a.M, ctl.n_pad) : a.M;
-  const int tiles_m = min(a.tiles_m, (m_lim + BM - 1) / BM);
-  const int K = a.k_from_ctl ? ctl.n_pad : a.K;
-  const int ks = (a.split_k && a.m_from_ctl) ? dh_split(ctl.n_pad, a.M, a.tiles_n, K / BK) : 1;
-  const int tid = threadIdx.x;
+  StoreShape sh;
+  sh.init(a, ctl);
   TileQueue Q;
-  Q.init(a.queue, tiles_m * ks * a.tiles_n, 1);
-  volatile int* claim = reinterpret_cast<volatile int*>(g_smem + STORE_CLAIM_OFF);
-  int b = queue_broadcast(claim, tid == 0 ? Q.resolve(Q.ticket()) : 0);
-  char* const C0 = static_cast<char*>(a.C);
-
+  Q.init(a.queue, sh.total, 1);
+  volatile int* claim = reinterpret_cast<volatile int*>(g_smem + CLAIM_OFF);
   // persistent: one workgroup per compute unit takes tiles from the XCD-aware queue until none is left
-  while (b >= 0) {
-    int tm, tn;
-    map_tile_interleaved(b, tiles_m * ks, a.tiles_n, tm, tn);
-    const int part = tm / tiles_m;                     // 0 unless the contraction is split
-    tm -= part * tiles_m;
-    const int s0 = (int)((long long)part * (K / BK) / ks), s1 = (int)((long long)(part + 1) * (K / BK) / ks);
-    const uint32_t kb = (uint32_t)s0 * BK * 2u;        // byte offset of this part's first k
-
-    // the claim for the next tile travels under the main loop (a tile here is hundreds of stages long)
-    unsigned ticket;
-    if (tid == 0) ticket = Q.ticket();
-    TileLoader LA, LB;
-    LA.init(a.B, a.b_rows, tn * BN, a.ldb, kb, tid);     // engine rows <- n
-    LB.init(a.A, a.a_rows, tm * BM, a.lda, kb, tid);     // engine columns <- m
-    f32x4 acc[GM][GN];
-    zero_acc(acc);
-    mainloop(LA, LB, s1 - s0, g_smem, acc);
-    const int b_next = queue_broadcast(claim, tid == 0 ? Q.resolve(ticket) : 0);
-    a.C = C0 + (size_t)part * ctl.n_pad * a.ldc * (a.out_bf16 ? 2 : 4);
-    if (a.out_bf16)
-      store_tile<__bf16>(a, tm, tn, m_lim, acc);
-    else
-      store_tile<float>(a, tm, tn, m_lim, acc);
-    b = b_next;
-  }
+  drain_queue(Q, true, claim, [&](int b, auto&& after_loop, auto&& before_stores) {
+    gemm_store_tile(a, sh, ctl.n_pad, b, after_loop, before_stores);
+  });
 }
 
 // ---- host-side launchers -------------------------------------------------------------
@@ -438,9 +469,9 @@ hipError_t init_gemm_kernels() {
   if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(lmhead_fwd_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
                                FWD_LDS_BYTES)) != hipSuccess) return e;
   if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(lmhead_dlogits_kernel),
-                               hipFuncAttributeMaxDynamicSharedMemorySize, DLOGITS_LDS_BYTES)) != hipSuccess) return e;
+                               hipFuncAttributeMaxDynamicSharedMemorySize, PERSISTENT_LDS_BYTES)) != hipSuccess) return e;
   if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_store_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                               STORE_LDS_BYTES)) != hipSuccess) return e;
+                               PERSISTENT_LDS_BYTES)) != hipSuccess) return e;
   int dev = 0, cus = 0;
   if ((e = hipGetDevice(&dev)) != hipSuccess) return e;
   if ((e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev)) != hipSuccess) return e;
@@ -456,11 +487,11 @@ void launch_lmhead_fwd(const FwdArgs& a, hipStream_t s) {
   hipLaunchKernelGGL(lmhead_fwd_kernel, dim3(persistent_grid(a.tiles_v, a.tiles_t)), dim3(NTHREADS), FWD_LDS_BYTES, s, a);
 }
 void launch_lmhead_dlogits(const DlogitsArgs& a, hipStream_t s) {
-  hipLaunchKernelGGL(lmhead_dlogits_kernel, dim3(persistent_grid(a.tiles_v, a.tiles_t)), dim3(NTHREADS), DLOGITS_LDS_BYTES, s, a);
+  hipLaunchKernelGGL(lmhead_dlogits_kernel, dim3(persistent_grid(a.tiles_v, a.tiles_t)), dim3(NTHREADS), PERSISTENT_LDS_BYTES, s, a);
 }
 void launch_gemm_store(const StoreArgs& a, hipStream_t s) {
   // (a split contraction's parts share the row extent: parts x live rows never exceed tiles_m tiles)
-  hipLaunchKernelGGL(gemm_store_kernel, dim3(persistent_grid(a.tiles_m, a.tiles_n)), dim3(NTHREADS), STORE_LDS_BYTES, s, a);
+  hipLaunchKernelGGL(gemm_store_kernel, dim3(persistent_grid(a.tiles_m, a.tiles_n)), dim3(NTHREADS), PERSISTENT_LDS_BYTES, s, a);
 }
 
 }  // namespace pg
