@@ -128,6 +128,16 @@ def aux_stage_times(B, torch, dev, rewards, valid, out, loss_mask, old_logp, rol
         e1.record()
         torch.cuda.synchronize()
         res[name] = e0.elapsed_time(e1) / reps * 1e3
+    # what a plain device-to-device copy of the same [T, d] sustains on this machine (the practical ceiling of a
+    # streaming kernel: read + write)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    dx_buf.copy_(H)
+    e0.record()
+    for _ in range(reps):
+        dx_buf.copy_(H)
+    e1.record()
+    torch.cuda.synchronize()
+    res["plain_copy_GBps"] = 2 * H.numel() * H.element_size() / (e0.elapsed_time(e1) / reps * 1e-3) / 1e9
     nbytes = H.numel() * H.element_size()
     res["pg_rmsnorm_fwd_GBps"] = 2 * nbytes / (res["pg_rmsnorm_fwd"] * 1e-6) / 1e9       # x read, h written
     res["pg_rmsnorm_bwd_GBps"] = 3 * nbytes / (res["pg_rmsnorm_bwd"] * 1e-6) / 1e9       # x, dh read, dx written
