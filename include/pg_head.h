@@ -42,7 +42,10 @@
  *     capture: run one call eagerly, or pg_init(), before capturing.
  *   - H is [T,d] row-major, W is [V,d] row-major (LM-head weight, no bias), y[t] is
  *     the token whose log-prob row t predicts (the caller has already shifted).
- *     dtype 0: H, W, dH are bf16 (fp32 accumulation); dtype 1: H, W, dH are fp32.
+ *     dtype 0: H, W, dH are bf16 (fp32 accumulation; the logit gradient dS is rounded to bf16 before
+ *     the two backward contractions).  dtype 1: H, W, dH are fp32; every contraction then runs on
+ *     operands split into a bf16 value plus a bf16 remainder (H, W and dS alike), the product of two
+ *     remainders dropped: about 16 mantissa bits per product, at three times the matrix work.
  *   - Shapes: d must be a multiple of 64, 1 <= d, 1 <= V <= 2^30, 0 <= T < 2^23, and 256 rows of
  *     any operand (256 x d, x 3 for fp32 inputs) must stay below 4 GiB; otherwise
  *     PG_ERR_UNSUPPORTED_SHAPE.  Operands as a whole may be of any size.

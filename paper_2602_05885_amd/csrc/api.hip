@@ -66,6 +66,7 @@ struct Plan {
   int queue_words = 0; // tile-queue counters (8 per persistent launch)
   size_t ctl, counters, queue, flag, c_tok, a_tok, rows, pos, yc, zy, lse2, coefc, lossterm;
   size_t part_m, part_s, part_u, Hc, HcT, Wc, dS, dST, WT, dHacc, rstd_c = 0, norm_partial = 0;
+  size_t HcT_lo = 0, dS_lo = 0, dST_lo = 0, WT_lo = 0;   // fp32 heads only
   size_t total = 0;
 };
 
@@ -160,6 +161,12 @@ int32_t make_plan(int64_t T, int64_t d, int64_t V, int32_t S, const pg_params* p
     pl.dS = take((size_t)t_cap * ld_v * 2);
     pl.dST = take((size_t)vc * ld_t * 2);
     pl.WT = take((size_t)d * ld_v * 2);
+    if (pl.is_f32) {   // bf16 remainders of the four backward operands
+      pl.HcT_lo = take((size_t)d * ld_t * 2);
+      pl.dS_lo = take((size_t)t_cap * ld_v * 2);
+      pl.dST_lo = take((size_t)vc * ld_t * 2);
+      pl.WT_lo = take((size_t)d * ld_v * 2);
+    }
     pl.dHacc = take((size_t)t_cap * d * 4);
     pl.queue_words = pg::QUEUE_SET_WORDS * pg::queue_sets((int)nchunks);
   }
@@ -279,6 +286,7 @@ void run_forward(const Plan& pl, const pg_params& p, void* ws, const void* H, co
   g.H = H; g.y = y; g.d = (int)pl.d; g.t_cap = pl.t_cap; g.is_f32 = pl.is_f32;
   g.rows = at<int>(ws, pl.rows); g.Hc = at<__bf16>(ws, pl.Hc);
   g.HcT = need_HT ? at<__bf16>(ws, pl.HcT) : nullptr;
+  g.HcT_lo = need_HT && pl.is_f32 ? at<__bf16>(ws, pl.HcT_lo) : nullptr;
   g.yc = at<int>(ws, pl.yc); g.ctl = at<pg::Ctl>(ws, pl.ctl); g.ld_t = pl.ld_t;
   g.y_offset = (int)y_offset; g.V = (int)pl.V;
   if (norm) pg::launch_norm_gather(g, *norm, st);
@@ -748,7 +756,9 @@ int32_t loss_fwd_bwd(int sft, const void* H, const void* W, const int32_t* y, co
       wt = static_cast<__bf16*>(p.w_transposed) + v0;
       ld_wt = (int)wt_cache_ld(pl.V);
     }
-    if (!p.w_transposed || !p.w_transposed_valid) pg::launch_transpose_w(W, pl.is_f32, pl.V, d_i, v0, kc, ld_wt, wt, st);
+    if (!p.w_transposed || !p.w_transposed_valid) pg::launch_transpose_w(W, pl.is_f32, pl.V, d_i, d_i, v0, kc, ld_wt, wt, st);
+    if (pl.is_f32)   // the remainders W - bf16(W) are columns [d, 2d) of the split operand
+      pg::launch_transpose_w(at<__bf16>(ws, pl.Wc) + d_i, 0, pl.V, d_i, pl.kd, v0, kc, pl.ld_v, at<__bf16>(ws, pl.WT_lo), st);
 
     pg::DlogitsArgs g{};
     g.W = Wop; g.Hc = at<__bf16>(ws, pl.Hc);
@@ -758,12 +768,14 @@ int32_t loss_fwd_bwd(int sft, const void* H, const void* W, const int32_t* y, co
     g.scale = (float)(LOG2E / (double)p.temperature);
     g.yc = at<int>(ws, pl.yc); g.lse2 = at<float>(ws, pl.lse2); g.coefc = at<float>(ws, pl.coefc);
     g.dS = at<__bf16>(ws, pl.dS); g.dST = at<__bf16>(ws, pl.dST); g.ctl = ctl;
-    unsigned* const queues = at<unsigned>(ws, pl.queue) + pg::QUEUE_SET_WORDS * (1 + 3 * c);
-    g.queue = queues;
+    if (pl.is_f32) { g.dS_lo = at<__bf16>(ws, pl.dS_lo); g.dST_lo = at<__bf16>(ws, pl.dST_lo); }
+    unsigned* const queues = at<unsigned>(ws, pl.queue) + pg::QUEUE_SET_WORDS * (1 + 4 * c);
+    g.queue = queues; g.queue_lo = queues + 3 * pg::QUEUE_SET_WORDS;
     { ProfScope ps(PG_KERNEL_DLOGITS, st); pg::launch_lmhead_dlogits(g, st); }
 
     pg::StoreArgs w{};   // dW[v0 + m, :] = sum_t dS^T[m, t] H^T[:, t]
     w.A = at<__bf16>(ws, pl.dST); w.B = at<__bf16>(ws, pl.HcT);
+    if (pl.is_f32) { w.A_lo = at<__bf16>(ws, pl.dST_lo); w.B_lo = at<__bf16>(ws, pl.HcT_lo); }
     w.a_rows = pl.vc; w.b_rows = d_i;
     w.lda = pl.ld_t; w.ldb = pl.ld_t; w.M = rows_valid; w.N = d_i; w.K = pl.t_cap;
     w.tiles_m = tiles_c; w.tiles_n = (d_i + 255) / 256;
@@ -774,6 +786,7 @@ int32_t loss_fwd_bwd(int sft, const void* H, const void* W, const int32_t* y, co
 
     pg::StoreArgs h{};   // dHacc[t, :] (+)= sum_v dS[t, v] W^T[:, v]
     h.A = at<__bf16>(ws, pl.dS); h.B = wt;
+    if (pl.is_f32) { h.A_lo = at<__bf16>(ws, pl.dS_lo); h.B_lo = at<__bf16>(ws, pl.WT_lo); }
     h.a_rows = pl.t_cap; h.b_rows = d_i;
     h.lda = pl.ld_v; h.ldb = ld_wt; h.M = pl.t_cap; h.N = d_i; h.K = kc;
     h.tiles_m = pl.tiles_t; h.tiles_n = (d_i + 255) / 256;

@@ -8,9 +8,10 @@ namespace pg {
 struct Ctl;
 
 // Tile-queue counters in the workspace: one set of 8 (one per XCD) for every persistent launch of a
-// call (the forward, then recompute / dW / dH of every vocab chunk), all cleared by the pre-pass.
+// call (the forward, then recompute / dW / dH / remainder recompute of every vocab chunk), all cleared
+// by the pre-pass.
 constexpr int QUEUE_SET_WORDS = 8;
-inline int queue_sets(int nchunks) { return 1 + 3 * nchunks; }
+inline int queue_sets(int nchunks) { return 1 + 4 * nchunks; }
 
 // ---- MFMA kernels ---------------------------------------------------------------------
 struct FwdArgs {
@@ -50,13 +51,18 @@ struct DlogitsArgs {
   const float* coefc;   // [t_cap] coef / tau (0 on padding)
   __bf16* dS;           // [t_cap, ld_s]
   __bf16* dST;          // [vc, ld_t]
+  __bf16* dS_lo;        // fp32 heads: the bf16 remainders dS - bf16(dS), same two layouts; else null
+  __bf16* dST_lo;
   const Ctl* ctl;
   unsigned* queue;      // [8] tile counters of this launch's queue, zero at launch
+  unsigned* queue_lo;   // [8] the same for the launch that stores the remainders
 };
 
 struct StoreArgs {
   const void* A;        // [M, lda] bf16
   const void* B;        // [N, ldb] bf16
+  const void* A_lo;     // fp32 heads: bf16 remainders of A and B (same shapes); the contraction then adds
+  const void* B_lo;     // A B_lo and A_lo B to A B.  Both null otherwise.
   int a_rows, b_rows;   // rows that exist in A / B (loads beyond them give 0)
   int lda, ldb;
   int M, N, K;
@@ -127,13 +133,16 @@ struct GatherArgs {
   int is_f32;
   const int* rows;
   __bf16* Hc;           // [t_cap, ldh]   bf16: ldh = d;  fp32: ldh = 3d = [hi | hi | lo]
-  __bf16* HcT;          // [d, ld_t] (nullable)
+  __bf16* HcT;          // [d, ld_t] (nullable): transpose of the bf16 operand / of the hi parts
+  __bf16* HcT_lo;       // [d, ld_t] (nullable, fp32 only): transpose of the lo parts
   int ld_t;
   int* yc;              // y - y_offset where that lies in [0, V), else -1
   int y_offset, V;      // first vocab row and number of vocab rows of the weight operand
   const Ctl* ctl;
 };
 void launch_gather(const GatherArgs& a, hipStream_t s);
+// HcT[j, i] = Hc[i, j] over d columns of row stride ldh, for the live rows
+void launch_transpose_hc(const __bf16* Hc, int ldh, __bf16* HcT, const GatherArgs& g, hipStream_t s);
 
 // fp32 head weight -> [V, 3d] bf16 = [hi | lo | hi]
 void launch_split_w(const float* W, __bf16* Wc, int64_t V, int d, hipStream_t s);
@@ -172,7 +181,7 @@ struct FinishArgs {
 void launch_finish(const FinishArgs& a, hipStream_t s);
 
 // W[v0 .. v0+cols) x d  ->  WT [d, ldt] bf16 (zeros for v >= V)
-void launch_transpose_w(const void* W, int is_f32, int64_t V, int d, int v0, int cols, int ldt, __bf16* WT,
+void launch_transpose_w(const void* W, int is_f32, int64_t V, int d, int ldw, int v0, int cols, int ldt, __bf16* WT,
                         hipStream_t s);
 
 struct ScatterArgs {

@@ -227,7 +227,7 @@ __device__ __forceinline__ void drain_queue(const TileQueue& Q, bool steal, vola
   }
 }
 
-template <class AfterLoop, class BeforeStores>
+template <bool LO, class AfterLoop, class BeforeStores>
 __device__ __forceinline__ void dlogits_tile(const DlogitsArgs& a, int tm, int tn, AfterLoop&& after_loop,
                                              BeforeStores&& before_stores) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -248,6 +248,7 @@ __device__ __forceinline__ void dlogits_tile(const DlogitsArgs& a, int tm, int t
   // and one exp2 each; c = 0 gives 2^-inf = 0), the one-hot term c is added to the single element
   // that holds the sampled token (rare, wave-uniform branch), and the sign goes on with the bf16
   // packing.  pk[i][j][h] holds rows 2h, 2h+1 of this lane's 4-row group as a bf16 pair.
+  // For an fp32 head a second launch (LO) recomputes the tile and stores the remainders dS - bf16(dS).
   uint32_t pk[GM][GN][2];
 #pragma unroll
   for (int j = 0; j < GN; ++j) {
@@ -279,6 +280,10 @@ __device__ __forceinline__ void dlogits_tile(const DlogitsArgs& a, int tm, int t
         bf16x2 two;
         two[0] = (__bf16)g[2 * h];
         two[1] = (__bf16)g[2 * h + 1];
+        if constexpr (LO) {
+          two[0] = (__bf16)(g[2 * h] - (float)two[0]);
+          two[1] = (__bf16)(g[2 * h + 1] - (float)two[1]);
+        }
         pk[i][j][h] = __builtin_bit_cast(uint32_t, two) ^ sgn;
       }
     }
@@ -300,7 +305,7 @@ __device__ __forceinline__ void dlogits_tile(const DlogitsArgs& a, int tm, int t
   __syncthreads();
   {
     const int chunk = tid & 31, r0 = tid >> 5;
-    __bf16* dst = a.dS + ((size_t)tn * BN) * a.ld_s + (size_t)tm * BM + chunk * 8;
+    __bf16* dst = (LO ? a.dS_lo : a.dS) + ((size_t)tn * BN) * a.ld_s + (size_t)tm * BM + chunk * 8;
 #pragma unroll 4
     for (int ps = 0; ps < 256 / (NTHREADS / 32); ++ps) {
       const int row = r0 + ps * (NTHREADS / 32);
@@ -340,7 +345,7 @@ __device__ __forceinline__ void dlogits_tile(const DlogitsArgs& a, int tm, int t
   __syncthreads();
   {
     const int chunk = tid & 31, r0 = tid >> 5;
-    __bf16* dst = a.dST + ((size_t)tm * BM) * a.ld_t + (size_t)tn * BN + chunk * 8;
+    __bf16* dst = (LO ? a.dST_lo : a.dST) + ((size_t)tm * BM) * a.ld_t + (size_t)tn * BN + chunk * 8;
 #pragma unroll 4
     for (int ps = 0; ps < 256 / (NTHREADS / 32); ++ps) {
       const int row = r0 + ps * (NTHREADS / 32);
@@ -350,6 +355,7 @@ __device__ __forceinline__ void dlogits_tile(const DlogitsArgs& a, int tm, int t
   }
 }
 
+template <bool LO>
 __global__ __launch_bounds__(NTHREADS) void lmhead_dlogits_kernel(DlogitsArgs a) {
   const Ctl ctl = *a.ctl;
   const int tiles_t = min(a.tiles_t, ctl.n_pad / BN);   // live token tiles: known only on the device
@@ -360,7 +366,7 @@ __global__ __launch_bounds__(NTHREADS) void lmhead_dlogits_kernel(DlogitsArgs a)
   drain_queue(Q, true, claim, [&](int b, auto&& after_loop, auto&& before_stores) {
     int tm, tn;
     map_tile(b, a.tiles_v, tiles_t, tm, tn);
-    dlogits_tile(a, tm, tn, after_loop, before_stores);
+    dlogits_tile<LO>(a, tm, tn, after_loop, before_stores);
   });
 }
 
@@ -438,6 +444,15 @@ __device__ __forceinline__ void gemm_store_tile(StoreArgs a, const StoreShape& s
   f32x4 acc[GM][GN];
   zero_acc(acc);
   mainloop(LA, LB, s1 - s0, g_smem, acc);
+  if (a.A_lo) {   // split fp32 operands: add the two cross terms (the product of the remainders is dropped)
+    __syncthreads();
+    LA.init(a.B_lo, a.b_rows, tn * BN, a.ldb, kb, tid);
+    mainloop(LA, LB, s1 - s0, g_smem, acc);
+    __syncthreads();
+    LA.init(a.B, a.b_rows, tn * BN, a.ldb, kb, tid);
+    LB.init(a.A_lo, a.a_rows, tm * BM, a.lda, kb, tid);
+    mainloop(LA, LB, s1 - s0, g_smem, acc);
+  }
   before_stores();
   asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");   // the claim is visible behind this barrier
   a.C = static_cast<char*>(a.C) + (size_t)part * n_pad * a.ldc * (a.out_bf16 ? 2 : 4);
@@ -468,7 +483,9 @@ hipError_t init_gemm_kernels() {
   hipError_t e;
   if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(lmhead_fwd_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
                                FWD_LDS_BYTES)) != hipSuccess) return e;
-  if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(lmhead_dlogits_kernel),
+  if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(lmhead_dlogits_kernel<false>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, PERSISTENT_LDS_BYTES)) != hipSuccess) return e;
+  if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(lmhead_dlogits_kernel<true>),
                                hipFuncAttributeMaxDynamicSharedMemorySize, PERSISTENT_LDS_BYTES)) != hipSuccess) return e;
   if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_store_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
                                PERSISTENT_LDS_BYTES)) != hipSuccess) return e;
@@ -487,7 +504,12 @@ void launch_lmhead_fwd(const FwdArgs& a, hipStream_t s) {
   hipLaunchKernelGGL(lmhead_fwd_kernel, dim3(persistent_grid(a.tiles_v, a.tiles_t)), dim3(NTHREADS), FWD_LDS_BYTES, s, a);
 }
 void launch_lmhead_dlogits(const DlogitsArgs& a, hipStream_t s) {
-  hipLaunchKernelGGL(lmhead_dlogits_kernel, dim3(persistent_grid(a.tiles_v, a.tiles_t)), dim3(NTHREADS), PERSISTENT_LDS_BYTES, s, a);
+  hipLaunchKernelGGL(lmhead_dlogits_kernel<false>, dim3(persistent_grid(a.tiles_v, a.tiles_t)), dim3(NTHREADS), PERSISTENT_LDS_BYTES, s, a);
+  if (a.dS_lo) {   // fp32 head: the remainders, from a second pass over the same tiles with a queue of its own
+    DlogitsArgs lo = a;
+    lo.queue = a.queue_lo;
+    hipLaunchKernelGGL(lmhead_dlogits_kernel<true>, dim3(persistent_grid(a.tiles_v, a.tiles_t)), dim3(NTHREADS), PERSISTENT_LDS_BYTES, s, lo);
+  }
 }
 void launch_gemm_store(const StoreArgs& a, hipStream_t s) {
   // (a split contraction's parts share the row extent: parts x live rows never exceed tiles_m tiles)

@@ -297,6 +297,7 @@ __global__ __launch_bounds__(256) void gather_kernel(GatherArgs a) {
 }
 void launch_gather(const GatherArgs& a, hipStream_t s) {
   hipLaunchKernelGGL(gather_kernel, dim3(a.t_cap / 64, a.d / 64), dim3(256), 0, s, a);
+  if (a.HcT_lo) launch_transpose_hc(a.Hc + 2 * a.d, 3 * a.d, a.HcT_lo, a, s);
 }
 
 __global__ void split_w_kernel(const float* W, __bf16* Wc, size_t n, int d) {
@@ -316,8 +317,8 @@ void launch_split_w(const float* W, __bf16* Wc, int64_t V, int d, hipStream_t s)
   hipLaunchKernelGGL(split_w_kernel, dim3(grid), dim3(256), 0, s, W, Wc, n, d);
 }
 
-// W rows [v0, v0+cols) -> WT[j][v - v0] (bf16; fp32 weights are rounded), zeros for v >= V.
-__global__ __launch_bounds__(256) void transpose_w_kernel(const void* W, int is_f32, long long V, int d, int v0,
+// W rows [v0, v0+cols) (row stride ldw elements) -> WT[j][v - v0] (bf16; fp32 weights are rounded), zeros for v >= V.
+__global__ __launch_bounds__(256) void transpose_w_kernel(const void* W, int is_f32, long long V, int ldw, int v0,
                                                           int ldt, __bf16* WT) {
   __shared__ __attribute__((aligned(16))) uint16_t tile[64 * TT_LD];
   const int vt = blockIdx.x * 64, j0 = blockIdx.y * 64;
@@ -329,7 +330,7 @@ __global__ __launch_bounds__(256) void transpose_w_kernel(const void* W, int is_
     const long long v = (long long)v0 + vt + r;
     i32x4 x = {0, 0, 0, 0};
     if (v < V) {
-      const size_t o = (size_t)v * d + j0 + chunk * 8;
+      const size_t o = (size_t)v * ldw + j0 + chunk * 8;
       if (is_f32) {
         const float* src = reinterpret_cast<const float*>(W) + o;
         bf16x8 h;
@@ -349,9 +350,9 @@ __global__ __launch_bounds__(256) void transpose_w_kernel(const void* W, int is_
     *reinterpret_cast<i32x4*>(WT + (size_t)(j0 + jj) * ldt + vt + chunk * 8) = tt_get(tile, jj, chunk);
   }
 }
-void launch_transpose_w(const void* W, int is_f32, int64_t V, int d, int v0, int cols, int ldt, __bf16* WT,
+void launch_transpose_w(const void* W, int is_f32, int64_t V, int d, int ldw, int v0, int cols, int ldt, __bf16* WT,
                         hipStream_t s) {
-  hipLaunchKernelGGL(transpose_w_kernel, dim3(cols / 64, d / 64), dim3(256), 0, s, W, is_f32, (long long)V, d, v0,
+  hipLaunchKernelGGL(transpose_w_kernel, dim3(cols / 64, d / 64), dim3(256), 0, s, W, is_f32, (long long)V, ldw, v0,
                      ldt, WT);
 }
 
@@ -1008,7 +1009,7 @@ __global__ __launch_bounds__(256) void norm_gather_kernel(GatherArgs a, NormFuse
   }
 }
 
-// HcT[j, i] = Hc[i, j] for the first d columns (the bf16 operand, or the hi parts of a split fp32 one).
+// HcT[j, i] = Hc[i, j] for d columns of row stride ldh (the bf16 operand; the hi or the lo parts of a split fp32 one).
 __global__ __launch_bounds__(256) void transpose_hc_kernel(const __bf16* Hc, int ldh, __bf16* HcT, int ld_t, const Ctl* ctlp) {
   __shared__ __attribute__((aligned(16))) uint16_t tile[64 * TT_LD];
   const int i0 = blockIdx.x * 64, j0 = blockIdx.y * 64;
@@ -1027,12 +1028,15 @@ __global__ __launch_bounds__(256) void transpose_hc_kernel(const __bf16* Hc, int
   }
 }
 
+void launch_transpose_hc(const __bf16* Hc, int ldh, __bf16* HcT, const GatherArgs& g, hipStream_t s) {
+  hipLaunchKernelGGL(transpose_hc_kernel, dim3(g.t_cap / 64, g.d / 64), dim3(256), 0, s, Hc, ldh, HcT, g.ld_t, g.ctl);
+}
+
 void launch_norm_gather(const GatherArgs& g, const NormFuse& n, hipStream_t s) {
   if (g.is_f32) hipLaunchKernelGGL(norm_gather_kernel<true>, dim3(g.t_cap / 4), dim3(256), 0, s, g, n);
   else hipLaunchKernelGGL(norm_gather_kernel<false>, dim3(g.t_cap / 4), dim3(256), 0, s, g, n);
-  if (g.HcT)
-    hipLaunchKernelGGL(transpose_hc_kernel, dim3(g.t_cap / 64, g.d / 64), dim3(256), 0, s, g.Hc, g.is_f32 ? 3 * g.d : g.d,
-                       g.HcT, g.ld_t, g.ctl);
+  if (g.HcT) launch_transpose_hc(g.Hc, g.is_f32 ? 3 * g.d : g.d, g.HcT, g, s);
+  if (g.HcT_lo) launch_transpose_hc(g.Hc + 2 * g.d, 3 * g.d, g.HcT_lo, g, s);
 }
 
 // Backward, fused into the scatter of dH: workgroup b owns a contiguous strip of the T original rows

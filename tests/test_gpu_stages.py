@@ -259,8 +259,9 @@ def test_loss_with_fused_rmsnorm(dev, monkeypatch, dtype, mode, kind, seed):
     assert abs(float(out["loss"][0]) - ref["loss"]) <= TOL_LOSS * abs(ref["loss"])
     e_dx, e_dg, e_dw = rel_fro(np64(out["dX"]), dX_ref), rel_fro(out["dgamma"].double().cpu().numpy(), dg_ref), rel_fro(np64(out["dW"]), ref["dW"])
     print(f"[fused norm {dtype} mode {mode}] dX {e_dx:.2e} (worst block {block_rel_fro(np64(out['dX']), dX_ref):.2e}) dgamma {e_dg:.2e} dW {e_dw:.2e}")
-    assert e_dx <= TOL_GRAD and e_dg <= TOL_GRAD and e_dw <= TOL_GRAD
-    assert block_rel_fro(np64(out["dX"]), dX_ref) <= TOL_GRAD
+    tol_g = TOL_GRAD if dtype == "bf16" else 5e-5            # split operands throughout for fp32 (achieved 1e-5)
+    assert e_dx <= tol_g and e_dg <= tol_g and e_dw <= tol_g
+    assert block_rel_fro(np64(out["dX"]), dX_ref) <= tol_g
     assert np.all(np64(out["dX"])[~ref["active"]] == 0)
     for k in ("loss", "dX", "dgamma", "dW", "logp"):
         assert torch.equal(out[k], out2[k]), k                                      # fixed reduction orders
