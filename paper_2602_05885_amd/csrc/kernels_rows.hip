@@ -24,34 +24,48 @@ void launch_fill_zero_bytes(void* p, size_t nbytes, hipStream_t s) {
 }
 
 // ------------------------------------------------------------------ TRLOO (Sec. 4.2, Eq. 2, 3 and 5)
-// One thread per (prompt, turn) group; fp64 throughout.  Returns are evaluated by Horner's
-// rule from the last turn backwards; the leave-one-out mean is (sum - own) / (N - 1), the
-// group mean of the comparison baseline sum / N.
+// A segmented group reduction: one wavefront per (prompt, turn) group, its 64 lanes striding over the
+// K rollouts (the group's members lie Tmax elements apart in the [P, K, Tmax] tensors).  Every lane
+// evaluates the returns of its rollouts once, by Horner's rule from the last turn backwards, and keeps
+// them in registers (up to TRLOO_HELD per lane, i.e. K <= 64 TRLOO_HELD; beyond that they are evaluated
+// again in the second sweep); the group's sum and count are then reduced across the wavefront by a
+// butterfly of shuffles, whose order is fixed, so results repeat bit for bit.  fp64 throughout.  The
+// leave-one-out mean is (sum - own) / (N - 1), the group mean of the comparison baseline sum / N.
+constexpr int TRLOO_HELD = 4;
+
 __device__ __forceinline__ double turn_return(const float* r, int t, int Tmax, double gamma) {
   double g = 0.0;
   for (int tp = Tmax - 1; tp >= t; --tp) g = (double)r[tp] + gamma * g;
   return g;
 }
 
-__global__ void trloo_kernel(TrlooArgs a) {
-  const int g = blockIdx.x * blockDim.x + threadIdx.x;
+__global__ __launch_bounds__(256) void trloo_kernel(TrlooArgs a) {
+  const int lane = threadIdx.x & 63;
+  const int g = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);      // wavefront-uniform
   if (g >= a.P * a.Tmax) return;
   const int p = g / a.Tmax, t = g % a.Tmax;
   const double gamma = (double)a.gamma;
+  double held[TRLOO_HELD];
   double sum = 0.0;
   int n = 0;
-  for (int k = 0; k < a.K; ++k) {
+  for (int k = lane, i = 0; k < a.K; k += 64, ++i) {
     const size_t base = ((size_t)p * a.K + k) * a.Tmax;
     const double G = turn_return(a.rewards + base, t, a.Tmax, gamma);
+    if (i < TRLOO_HELD) held[i] = G;
     if (a.returns_out) a.returns_out[base + t] = G;
     if (a.valid[base + t]) { sum += G; ++n; }
   }
-  if (a.group_n_out) a.group_n_out[g] = n;
-  for (int k = 0; k < a.K; ++k) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) {
+    sum += __shfl_xor(sum, off);
+    n += __shfl_xor(n, off);
+  }
+  if (lane == 0 && a.group_n_out) a.group_n_out[g] = n;
+  for (int k = lane, i = 0; k < a.K; k += 64, ++i) {
     const size_t base = ((size_t)p * a.K + k) * a.Tmax;
     double A = 0.0;
     if (a.valid[base + t]) {
-      const double G = turn_return(a.rewards + base, t, a.Tmax, gamma);
+      const double G = i < TRLOO_HELD ? held[i] : turn_return(a.rewards + base, t, a.Tmax, gamma);
       if (a.group_mean) A = G - sum / (double)n;                    // Eq. (3); n >= 1 here
       else if (n >= 2) A = G - (sum - G) / (double)(n - 1);         // Eq. (5)
     }
@@ -59,8 +73,8 @@ __global__ void trloo_kernel(TrlooArgs a) {
   }
 }
 void launch_trloo(const TrlooArgs& a, hipStream_t s) {
-  const int n = a.P * a.Tmax;
-  hipLaunchKernelGGL(trloo_kernel, dim3((n + 63) / 64), dim3(64), 0, s, a);
+  const int n = a.P * a.Tmax;                                       // groups, 4 per workgroup
+  hipLaunchKernelGGL(trloo_kernel, dim3((n + 3) / 4), dim3(256), 0, s, a);
 }
 
 // ------------------------------------------------------------------ pre-pass

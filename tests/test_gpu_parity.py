@@ -31,7 +31,9 @@ def oracle_logp(Hn, Wn, yn, tau):
 # ------------------------------------------------------------------------------------ TRLOO
 @pytest.mark.parametrize("P,K,Tm,gamma,seed", [(4, 4, 2, 1.0, 0), (16, 8, 3, 1.0, 1), (4, 16, 4, 1.0, 2),
                                                 (32, 16, 2, 1.0, 3), (3, 5, 7, 0.9, 4), (2, 1, 3, 1.0, 5),
-                                                (1, 2, 1, 0.0, 6)])
+                                                (1, 2, 1, 0.0, 6),
+                                                (2, 100, 3, 0.9, 7),      # rollouts beyond one wavefront's 64 lanes
+                                                (2, 300, 2, 1.0, 8)])     # ... and beyond the returns a lane holds
 def test_trloo_parity(dev, P, K, Tm, gamma, seed):
     rng = np.random.default_rng(seed)
     correct = rng.random((P, K, Tm)) < 0.5

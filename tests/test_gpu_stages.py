@@ -71,7 +71,8 @@ def test_sft_accumulate_override_and_empty(dev):
 
 
 # ------------------------------------------------------------------------------------ GRPO
-@pytest.mark.parametrize("P,K,Tm,gamma,seed", [(4, 4, 2, 1.0, 0), (16, 8, 3, 1.0, 1), (3, 5, 7, 0.9, 4), (2, 1, 3, 0.0, 5)])
+@pytest.mark.parametrize("P,K,Tm,gamma,seed", [(4, 4, 2, 1.0, 0), (16, 8, 3, 1.0, 1), (3, 5, 7, 0.9, 4), (2, 1, 3, 0.0, 5),
+                                                (2, 130, 2, 0.9, 6)])
 def test_grpo_parity(dev, P, K, Tm, gamma, seed):
     rng = np.random.default_rng(seed)
     correct = rng.random((P, K, Tm)) < 0.5
