@@ -235,7 +235,7 @@ def main():
     ap.add_argument("--vocab-shards", type=int, default=2, help="number of vocab shards for --workload shard")
     ap.add_argument("--no-others", dest="others", action="store_false",
                     help="skip the secondary workloads that the default run times after the headline "
-                         "(other_workloads: Sec. 5.1's rejection rule, backward from states, forward-only 128k rows)")
+                         "(other_workloads: Sec. 5.1's rejection rule, backward from states, fused RMS normalisation, forward-only 128k rows)")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="also run three plain device-to-device copies of this size (the known-size reference "
                          "that hardware-counter byte counts are scaled by)")
@@ -458,6 +458,28 @@ def main():
         loss_entry("backward_from_states", f"configs[{args.config}], trloo_advantage + pg_loss_shard_bwd on the whole head from the "
                    "softmax states of pg_head_shard_fwd (valid while the weights are those of the recompute)", step_bwd, 3.0)
         del states, dH32, out_b
+
+        # RMS normalisation in front of the head: fused into the loss call against the three separate calls
+        gamma = torch.ones(d, dtype=H.dtype, device=dev)
+        ws_n = B.alloc_workspace(T, d, V, S, prm, B.CALL_LOSS_FWD_BWD_NORMED, dev)
+        Hn, dXn = torch.empty_like(H), torch.empty_like(H)
+
+        def step_fused():
+            B.trloo_advantage(rewards, valid, 1.0, want_returns=False, want_group_n=False)
+            return B.pg_loss_fwd_bwd_normed(H, gamma, 1e-6, W, y, loss_mask, cu, adv_flat, seg_sample, old_logp, rollout_logp,
+                                            prm, ws_n, dW=dW, out=outbuf)
+
+        def step_separate():
+            B.trloo_advantage(rewards, valid, 1.0, want_returns=False, want_group_n=False)
+            B.pg_rmsnorm_fwd(H, gamma, 1e-6, want_rstd=False, out=Hn)
+            o = B.pg_loss_fwd_bwd(Hn, W, y, loss_mask, cu, adv_flat, seg_sample, old_logp, rollout_logp, prm, ws, dW=dW, out=outbuf)
+            B.pg_rmsnorm_bwd(H, gamma, o["dH"], 1e-6, out=dXn)
+            return o
+        loss_entry("with_rmsnorm_fused", f"configs[{args.config}] with the RMS normalisation of the hidden states in front of the head: "
+                   "trloo_advantage + pg_loss_fwd_bwd_normed (normalisation and its backward inside the call)", step_fused, 4.0)
+        loss_entry("with_rmsnorm_separate_calls", "the same as trloo_advantage + pg_rmsnorm_fwd + pg_loss_fwd_bwd + pg_rmsnorm_bwd",
+                   step_separate, 4.0)
+        del ws_n, Hn, dXn, gamma
 
     cpu = cpu_baseline(spec, args.cpu_rows) if args.cpu_rows > 0 and args.workload == "pg" else None
     aux = (aux_stage_times(B, torch, dev, rewards, valid, out, loss_mask, old_logp, rollout_logp, dW, H)
