@@ -47,7 +47,8 @@
  *     operands split into a bf16 value plus a bf16 remainder (H, W and dS alike), the product of two
  *     remainders dropped: about 16 mantissa bits per product, at three times the matrix work.
  *   - Shapes: d must be a multiple of 64, 1 <= d, 1 <= V <= 2^30, 0 <= T < 2^23, and 256 rows of
- *     any operand (256 x d, x 3 for fp32 inputs) must stay below 4 GiB; otherwise
+ *     any operand (256 x d, x 3 for fp32 inputs) must stay below 4 GiB, and ceil(T/256) x ceil(V/256),
+ *     the number of 256 x 256 logits tiles, below 2^28; otherwise
  *     PG_ERR_UNSUPPORTED_SHAPE.  Operands as a whole may be of any size.
  *     H, W, dH, dW and workspace must be 16-byte aligned.
  *   - y[t] outside [0,V) on an active row is not detected: that row's log-prob is

@@ -105,6 +105,9 @@ int32_t make_plan(int64_t T, int64_t d, int64_t V, int32_t S, const pg_params* p
   // a tile's 256 operand rows are addressed through one 32-bit buffer range
   if ((uint64_t)kd * 2 * 256 >= FOUR_GIB) return fail(PG_ERR_UNSUPPORTED_SHAPE, "d=%lld: 256 operand rows reach 4 GiB", (long long)d);
   if ((uint64_t)(t_cap + 64) * 2 * 256 >= FOUR_GIB) return fail(PG_ERR_UNSUPPORTED_SHAPE, "T=%lld: 256 rows of a [*, T] scratch matrix reach 4 GiB", (long long)T);
+  // tile indices and queue tickets are 32-bit, with 3 bits of a ticket naming the XCD
+  if (tiles_v * (t_cap / 256) >= (1ll << 28))
+    return fail(PG_ERR_UNSUPPORTED_SHAPE, "T=%lld x V=%lld: more than 2^28 logits tiles", (long long)T, (long long)V);
   pl.t_cap = (int)t_cap; pl.kd = (int)kd; pl.tiles_v = (int)tiles_v; pl.tiles_t = (int)(t_cap / 256);
 
   size_t off = 0;

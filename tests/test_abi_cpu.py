@@ -49,6 +49,7 @@ def test_workspace_query_and_shape_errors():
     assert B.pg_workspace_bytes(2048, 5120, 151936, 0, B.Params(dtype=1), 1) > 4 << 30  # fp32 head: 4.7 GB split operand
     assert B.pg_workspace_bytes(1 << 23, 64, 1000, 1, P, 0) == 0 and "4 GiB" in B.pg_last_error()
     assert B.pg_workspace_bytes(8, 1 << 23, 1000, 0, P, 1) == 0 and "4 GiB" in B.pg_last_error()
+    assert B.pg_workspace_bytes(1 << 22, 64, 1 << 26, 0, P, 0) == 0 and "logits tiles" in B.pg_last_error()
     assert B.pg_workspace_bytes(1024, 64, 1000, 1, P, 5) == 0
     assert B.pg_workspace_bytes(0, 64, 1000, 0, P, 1) > 0          # empty microbatch is legal
 
