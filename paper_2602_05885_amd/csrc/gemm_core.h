@@ -84,7 +84,12 @@ __host__ __device__ inline int grid_for_tiles(int tiles_m, int tiles_n) {
   return ((total + 7) / 8) * 8;
 }
 
-__device__ __forceinline__ bool map_tile(int bid, int tiles_m, int tiles_n, int& tm, int& tn) {
+// (host-callable too, like the queue's share() below: a host test sweeps them over tile counts and checks
+// that every tile is handed out exactly once)
+__host__ __device__ inline int imin(int a, int b) { return a < b ? a : b; }
+__host__ __device__ inline int imax(int a, int b) { return a > b ? a : b; }
+
+__host__ __device__ inline bool map_tile(int bid, int tiles_m, int tiles_n, int& tm, int& tn) {
   const int total = tiles_m * tiles_n;   // may be smaller than what the grid was sized for
   const int per = (total + 7) / 8;
   const int xcd = bid & 7, q = bid >> 3;
@@ -92,10 +97,10 @@ __device__ __forceinline__ bool map_tile(int bid, int tiles_m, int tiles_n, int&
   if (q >= per || t >= total) return false;
   const int panel_tiles = SB_N * tiles_m;
   const int p = t / panel_tiles;
-  const int w = min(SB_N, tiles_n - p * SB_N);
+  const int w = imin(SB_N, tiles_n - p * SB_N);
   const int idx = t - p * panel_tiles;
   const int mg = idx / (SB_M * w);
-  const int rig = min(SB_M, tiles_m - mg * SB_M);
+  const int rig = imin(SB_M, tiles_m - mg * SB_M);
   const int rem = idx - mg * SB_M * w;
   tm = mg * SB_M + rem % rig;
   tn = p * SB_N + rem / rig;
@@ -108,7 +113,7 @@ __device__ __forceinline__ bool map_tile(int bid, int tiles_m, int tiles_n, int&
 // The last (< 256) tiles are split evenly.  Pays when the n-panel (B rows x K) is too large to
 // stay cached while an XCD walks the whole M extent on its own: measured +1..3 % on the dW and
 // dH contractions, -1.5 % on the logits contraction (whose token panels do stay cached).
-__device__ __forceinline__ bool map_tile_interleaved(int bid, int tiles_m, int tiles_n, int& tm, int& tn) {
+__host__ __device__ inline bool map_tile_interleaved(int bid, int tiles_m, int tiles_n, int& tm, int& tn) {
   const int total = tiles_m * tiles_n;
   const int full = (total / 256) * 256;
   const int xcd = bid & 7, q = bid >> 3;
@@ -122,10 +127,10 @@ __device__ __forceinline__ bool map_tile_interleaved(int bid, int tiles_m, int t
   }
   const int panel_tiles = SB_N * tiles_m;
   const int p = t / panel_tiles;
-  const int w = min(SB_N, tiles_n - p * SB_N);
+  const int w = imin(SB_N, tiles_n - p * SB_N);
   const int idx = t - p * panel_tiles;
   const int mg = idx / (SB_M * w);
-  const int rig = min(SB_M, tiles_m - mg * SB_M);
+  const int rig = imin(SB_M, tiles_m - mg * SB_M);
   const int rem = idx - mg * SB_M * w;
   tm = mg * SB_M + rem % rig;
   tn = p * SB_N + rem / rig;
@@ -481,16 +486,16 @@ struct TileQueue {
     home = (int)(x & 7u);
   }
   // n_y: how many workgroup indices b = 8 i + y map to a tile
-  __device__ __forceinline__ int share(int y) const {
+  __host__ __device__ inline int share(int y) const {
     if (!interleaved) {
       const int per = (total + 7) / 8;
-      return min(max(total - y * per, 0), per);
+      return imin(imax(total - y * per, 0), per);
     }
     const int full = (total / 256) * 256, rem = total - full, per = (rem + 7) / 8;
-    return full / 8 + min(max(rem - y * per, 0), per);
+    return full / 8 + imin(imax(rem - y * per, 0), per);
   }
   // the workgroup index that map_tile / map_tile_interleaved would have seen for entry i of XCD y
-  static __device__ __forceinline__ int encode(int y, int i) { return (i << 3) | y; }
+  static __host__ __device__ inline int encode(int y, int i) { return (i << 3) | y; }
 
   // Issues the claim on the home share; the ticket is resolved later, so that the atomic's latency
   // hides behind whatever runs in between.  (atomicInc with the largest bound is an add of one; unlike
