@@ -47,8 +47,9 @@ def build(verbose: bool = True) -> str:
         print(" ".join(cmd), flush=True)
     subprocess.run(cmd, check=True)
     # stand-alone measurement tools (their failure must not fail the product build): the tile engine's main
-    # loop alone, and the persistent form of the forward kernel next to the library's
-    for tool in ("tile_bench", "stream_bench"):
+    # loop alone, the persistent form of the forward kernel next to the one-workgroup-per-tile form, and the
+    # in-kernel timeline of a vocab chunk's three launches
+    for tool in ("tile_bench", "stream_bench", "tail_bench"):
         cmd = [cc, *[f for f in FLAGS if f != "-fPIC"], os.path.join(CSRC, tool + ".hip"), "-o", os.path.join(PKG, tool)]
         if verbose:
             print(" ".join(cmd), flush=True)
