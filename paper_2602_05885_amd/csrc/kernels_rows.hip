@@ -821,12 +821,14 @@ void launch_rmsnorm_fwd(const NormArgs& a, hipStream_t s) {
 }
 
 // Backward: dx = rstd (gamma g - xhat mean(gamma g xhat)), xhat = x rstd; dgamma = sum_rows g xhat.
-// Workgroup b owns the contiguous strip of rows [b R, (b+1) R) and walks it row by row; a thread
+// Workgroup b takes the rows b, b + NORM_STRIPS, b + 2 NORM_STRIPS, ... (so the workgroups running at
+// one time read and write neighbouring rows: 4 % faster than a contiguous strip per workgroup); a thread
 // owns the same (up to) 4 x 8 columns of every row, holds x and g of the current row in registers
 // (each element is read once) and keeps the dgamma partial sums of its columns in registers.  The
-// two row sums (x^2 and gamma g xhat) are reduced over the workgroup in a fixed order.  The
-// strips' partials are folded by the second kernel.
-constexpr int NORM_NC = NORM_MAX_D / 2048;         // 8-column steps per thread
+// two row sums (x^2 and gamma g x) are reduced over the workgroup together, in a fixed order.  The
+// workgroups' partials are folded by the second kernel.
+constexpr int NORM_NC = NORM_MAX_D / 2048;         // 8-column steps per thread at the largest d
+static_assert(NORM_NC == 4, "the launcher instantiates 1..4 steps");
 
 __device__ __forceinline__ float block_sum4(float v, float* red, int lane, int wave) {
   v = wave_sum(v);
@@ -835,27 +837,39 @@ __device__ __forceinline__ float block_sum4(float v, float* red, int lane, int w
   return (red[0] + red[1]) + (red[2] + red[3]);
 }
 
-template <bool F32>
+// Keeps the register values of a packed row opaque to the optimiser between the two passes over a row, so that
+// the unpacked fp32 copies of the first pass are not kept alive across the reduction (they are unpacked again).
+__device__ __forceinline__ void opaque(Raw8<true>& r) { asm volatile("" : "+v"(r.a.x), "+v"(r.a.y), "+v"(r.a.z), "+v"(r.a.w), "+v"(r.b.x), "+v"(r.b.y), "+v"(r.b.z), "+v"(r.b.w)); }
+__device__ __forceinline__ void opaque(Raw8<false>& r) {
+  i32x4 v = __builtin_bit_cast(i32x4, r.v);
+  asm volatile("" : "+v"(v));
+  r.v = __builtin_bit_cast(bf16x8, v);
+}
+
+// NC: 8-column steps per thread, ceil(d / 2048).  Rows stay in registers as loaded (bf16 rows packed) and are
+// unpacked on the fly in both passes: with three steps and bf16 rows the kernel fits 4 workgroups on a
+// compute unit, each with one row of X and dH in flight ahead of the one it works on.
+template <bool F32, int NC>
 __global__ __launch_bounds__(256) void rmsnorm_bwd_kernel(NormArgs a) {
-  __shared__ float red[2][4];
+  __shared__ float red[2][8];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const long long R = (a.T + NORM_STRIPS - 1) / NORM_STRIPS;
-  const long long r0 = (long long)blockIdx.x * R, r1 = r0 + R < a.T ? r0 + R : a.T;
-  float dg[NORM_NC][8], g[NORM_NC][8];
+  const long long r0 = blockIdx.x, r1 = a.T;      // rows r0, r0 + NORM_STRIPS, ...
+  float dg[NC][8];
+  Raw8<F32> g_raw[NC] = {};
 #pragma unroll
-  for (int q = 0; q < NORM_NC; ++q) {
+  for (int q = 0; q < NC; ++q) {
     const int c = tid * 8 + q * 2048;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) { dg[q][e] = 0.f; g[q][e] = 0.f; }
-    if (c < a.d) load8<F32>(a.gamma, c, g[q]);
+    for (int e = 0; e < 8; ++e) dg[q][e] = 0.f;
+    if (c < a.d) raw_load(a.gamma, c, g_raw[q]);
   }
   const float inv_d = 1.f / (float)a.d;
-  // The next row's loads are issued before the current row's two workgroup reductions, so a
+  // The next row's loads are issued before the current row's workgroup reduction, so a
   // workgroup always has one row of X and dH in flight while it works on the previous one.
-  Raw8<F32> xr[NORM_NC] = {}, gr_raw[NORM_NC] = {}, xn[NORM_NC] = {}, gn[NORM_NC] = {};
-  auto fetch = [&](long long row, Raw8<F32> (&xa)[NORM_NC], Raw8<F32> (&ga)[NORM_NC]) {
+  Raw8<F32> xr[NC] = {}, gr_raw[NC] = {}, xn[NC] = {}, gn[NC] = {};
+  auto fetch = [&](long long row, Raw8<F32> (&xa)[NC], Raw8<F32> (&ga)[NC]) {
 #pragma unroll
-    for (int q = 0; q < NORM_NC; ++q) {
+    for (int q = 0; q < NC; ++q) {
       const int c = tid * 8 + q * 2048;
       if (c < a.d) {
         raw_load(a.X, row * a.d + c, xa[q]);
@@ -864,51 +878,58 @@ __global__ __launch_bounds__(256) void rmsnorm_bwd_kernel(NormArgs a) {
     }
   };
   if (r0 < r1) fetch(r0, xr, gr_raw);
-  for (long long row = r0; row < r1; ++row) {
-    if (row + 1 < r1) fetch(row + 1, xn, gn);
-    float x[NORM_NC][8], gr[NORM_NC][8];
-    float ss = 0.f;
+  int parity = 0;
+  for (long long row = r0; row < r1; row += NORM_STRIPS, parity ^= 1) {
+    if (row + NORM_STRIPS < r1) fetch(row + NORM_STRIPS, xn, gn);
+    // sum x^2 and sum gamma g x in one workgroup reduction: mean_j(gamma_j g_j xhat_j) = rstd mean_j(gamma_j g_j x_j)
+    float ss = 0.f, sd = 0.f;
 #pragma unroll
-    for (int q = 0; q < NORM_NC; ++q) {
+    for (int q = 0; q < NC; ++q) {
       const int c = tid * 8 + q * 2048;
       if (c < a.d) {
-        raw_unpack(xr[q], x[q]);
-        raw_unpack(gr_raw[q], gr[q]);
-#pragma unroll
-        for (int e = 0; e < 8; ++e) ss = fmaf(x[q][e], x[q][e], ss);
-      }
-    }
-    const float rstd = 1.f / sqrtf(block_sum4(ss, red[0], lane, wave) * inv_d + a.eps);
-    float dot = 0.f;
-#pragma unroll
-    for (int q = 0; q < NORM_NC; ++q) {
-      const int c = tid * 8 + q * 2048;
-      if (c < a.d) {
-#pragma unroll
-        for (int e = 0; e < 8; ++e) dot = fmaf(g[q][e] * gr[q][e], x[q][e] * rstd, dot);
-      }
-    }
-    dot = block_sum4(dot, red[1], lane, wave) * inv_d;
-#pragma unroll
-    for (int q = 0; q < NORM_NC; ++q) {
-      const int c = tid * 8 + q * 2048;
-      if (c < a.d) {
-        float dx[8];
+        float x[8], gr[8], g[8];
+        raw_unpack(xr[q], x);
+        raw_unpack(gr_raw[q], gr);
+        raw_unpack(g_raw[q], g);
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-          const float xh = x[q][e] * rstd;
-          dx[e] = rstd * (g[q][e] * gr[q][e] - xh * dot);
-          dg[q][e] = fmaf(gr[q][e], xh, dg[q][e]);
+          ss = fmaf(x[e], x[e], ss);
+          sd = fmaf(g[e] * gr[e], x[e], sd);
+        }
+      }
+    }
+    ss = wave_sum(ss);
+    sd = wave_sum(sd);
+    float* rb = red[parity];                // alternating buffers: one barrier per row is enough
+    if (lane == 0) { rb[wave] = ss; rb[4 + wave] = sd; }
+    __syncthreads();
+    const float rstd = 1.f / sqrtf(((rb[0] + rb[1]) + (rb[2] + rb[3])) * inv_d + a.eps);
+    const float dot = ((rb[4] + rb[5]) + (rb[6] + rb[7])) * rstd * inv_d;
+#pragma unroll
+    for (int q = 0; q < NC; ++q) {
+      const int c = tid * 8 + q * 2048;
+      if (c < a.d) {
+        opaque(xr[q]);
+        opaque(gr_raw[q]);
+        float x[8], gr[8], g[8], dx[8];
+        raw_unpack(xr[q], x);
+        raw_unpack(gr_raw[q], gr);
+        raw_unpack(g_raw[q], g);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const float xh = x[e] * rstd;
+          dx[e] = rstd * (g[e] * gr[e] - xh * dot);
+          dg[q][e] = fmaf(gr[e], xh, dg[q][e]);
         }
         store8<F32>(a.dX, row * a.d + c, dx);
       }
     }
 #pragma unroll
-    for (int q = 0; q < NORM_NC; ++q) { xr[q] = xn[q]; gr_raw[q] = gn[q]; }
+    for (int q = 0; q < NC; ++q) { xr[q] = xn[q]; gr_raw[q] = gn[q]; }
   }
   float* part = a.partial + (size_t)blockIdx.x * a.d;
 #pragma unroll
-  for (int q = 0; q < NORM_NC; ++q) {
+  for (int q = 0; q < NC; ++q) {
     const int c = tid * 8 + q * 2048;
     if (c < a.d) {
       *reinterpret_cast<float4*>(part + c) = make_float4(dg[q][0], dg[q][1], dg[q][2], dg[q][3]);
@@ -940,9 +961,18 @@ __global__ __launch_bounds__(256) void rmsnorm_dgamma_kernel(NormArgs a) {
 }
 static_assert(NORM_STRIPS % 32 == 0, "strip groups");
 
+template <bool F32>
+static void launch_rmsnorm_bwd_rows(const NormArgs& a, hipStream_t s) {
+  switch ((a.d + 2047) / 2048) {     // 8-column steps per thread; d <= NORM_MAX_D is checked by the caller
+    case 1: hipLaunchKernelGGL((rmsnorm_bwd_kernel<F32, 1>), dim3(NORM_STRIPS), dim3(256), 0, s, a); break;
+    case 2: hipLaunchKernelGGL((rmsnorm_bwd_kernel<F32, 2>), dim3(NORM_STRIPS), dim3(256), 0, s, a); break;
+    case 3: hipLaunchKernelGGL((rmsnorm_bwd_kernel<F32, 3>), dim3(NORM_STRIPS), dim3(256), 0, s, a); break;
+    default: hipLaunchKernelGGL((rmsnorm_bwd_kernel<F32, NORM_NC>), dim3(NORM_STRIPS), dim3(256), 0, s, a); break;
+  }
+}
 void launch_rmsnorm_bwd(const NormArgs& a, hipStream_t s) {
-  if (a.is_f32) hipLaunchKernelGGL(rmsnorm_bwd_kernel<true>, dim3(NORM_STRIPS), dim3(256), 0, s, a);
-  else hipLaunchKernelGGL(rmsnorm_bwd_kernel<false>, dim3(NORM_STRIPS), dim3(256), 0, s, a);
+  if (a.is_f32) launch_rmsnorm_bwd_rows<true>(a, s);
+  else launch_rmsnorm_bwd_rows<false>(a, s);
   hipLaunchKernelGGL(rmsnorm_dgamma_kernel, dim3((a.d + 31) / 32), dim3(256), 0, s, a);
 }
 
@@ -1053,82 +1083,121 @@ void launch_norm_gather(const GatherArgs& g, const NormFuse& n, hipStream_t s) {
   if (g.HcT_lo) launch_transpose_hc(g.Hc + 2 * g.d, 3 * g.d, g.HcT_lo, g, s);
 }
 
-// Backward, fused into the scatter of dH: workgroup b owns a contiguous strip of the T original rows
-// (as rmsnorm_bwd_kernel) and a thread the same (up to) 4 x 8 columns of every row.  For an active row
+// Backward, fused into the scatter of dH: workgroup b takes the T-rows b, b + NORM_STRIPS, ... (as
+// rmsnorm_bwd_kernel) and a thread the same (up to) 4 x 8 columns of every row.  For an active row
 // the accumulated fp32 gradient g of its compacted position (split-K slabs added in order) and the
 // row of X are read once, rstd comes from the forward,
 //   dx = rstd (gamma g - xhat mean_j(gamma_j g_j xhat_j)),  xhat = x rstd,
 // and g xhat is added to the thread's dgamma partial sums; rows that are not active are written as
-// zeros and nothing of theirs is read.  The strips' partials are folded by rmsnorm_dgamma_kernel.
-template <bool F32>
+// zeros and nothing of theirs is read.  The workgroups' partials are folded by rmsnorm_dgamma_kernel.
+template <bool F32, int NC>
 __global__ __launch_bounds__(256) void scatter_dx_norm_kernel(ScatterArgs a, NormFuse n) {
-  __shared__ float red[4];
+  __shared__ float red[2][4];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const long long T = a.T;
-  const long long R = (T + NORM_STRIPS - 1) / NORM_STRIPS;
-  const long long r0 = (long long)blockIdx.x * R, r1 = r0 + R < T ? r0 + R : T;
   const int n_pad = a.ctl->n_pad;
   const int ks = a.split_k ? dh_split(n_pad, a.t_cap, a.tiles_n, a.k_stages) : 1;
   const size_t slab = (size_t)n_pad * a.d;
-  float dg[NORM_NC][8], gam[NORM_NC][8];
+  float dg[NC][8];
+  Raw8<F32> gam_raw[NC] = {};
 #pragma unroll
-  for (int q = 0; q < NORM_NC; ++q) {
+  for (int q = 0; q < NC; ++q) {
     const int c = tid * 8 + q * 2048;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) { dg[q][e] = 0.f; gam[q][e] = 0.f; }
-    if (c < a.d) load8<F32>(n.gamma, c, gam[q]);
+    for (int e = 0; e < 8; ++e) dg[q][e] = 0.f;
+    if (c < a.d) raw_load(n.gamma, c, gam_raw[q]);
   }
   const float inv_d = 1.f / (float)a.d;
-  for (long long row = r0; row < r1; ++row) {
-    const int p = a.pos[row];                       // uniform over the workgroup
-    if (p < 0) {
+  // Row r of the workgroup is T-row blockIdx.x + r NORM_STRIPS; the inputs of the next one (its compacted
+  // position, rstd, the row of X and the first slab of the accumulator) are requested before the current
+  // row's reduction.  An inactive row (position < 0) needs no input.
+  Raw8<F32> xc[NC] = {}, xn[NC] = {};
+  Raw8<true> gc[NC] = {}, gn[NC] = {};
+  auto fetch = [&](long long row, Raw8<F32> (&xa)[NC], Raw8<true> (&ga)[NC], int& p, float& rstd) {
+    p = a.pos[row];                                 // uniform over the workgroup
+    if (p < 0) return;
+    rstd = n.rstd_c[p];
 #pragma unroll
-      for (int q = 0; q < NORM_NC; ++q) {
+    for (int q = 0; q < NC; ++q) {
+      const int c = tid * 8 + q * 2048;
+      if (c < a.d) {
+        raw_load(n.X, row * a.d + c, xa[q]);
+        raw_load(a.acc, (long long)p * a.d + c, ga[q]);
+      }
+    }
+  };
+  int pc = -1, parity = 0;
+  float rc = 0.f;
+  long long row = blockIdx.x;
+  if (row < T) fetch(row, xc, gc, pc, rc);
+  for (; row < T; row += NORM_STRIPS) {
+    int pn = -1;
+    float rn = 0.f;
+    if (row + NORM_STRIPS < T) fetch(row + NORM_STRIPS, xn, gn, pn, rn);
+    if (pc < 0) {
+#pragma unroll
+      for (int q = 0; q < NC; ++q) {
         const int c = tid * 8 + q * 2048;
         const float z[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
         if (c < a.d) store8<F32>(a.dH, row * a.d + c, z);
       }
-      continue;
-    }
-    const float rstd = n.rstd_c[p];
-    float x[NORM_NC][8], g[NORM_NC][8];
-    float dot = 0.f;
+    } else {
+      const float rstd = rc;
+      float dot = 0.f;
 #pragma unroll
-    for (int q = 0; q < NORM_NC; ++q) {
-      const int c = tid * 8 + q * 2048;
-      if (c < a.d) {
-        load8<F32>(n.X, row * a.d + c, x[q]);
-        load8<true>(a.acc, (long long)p * a.d + c, g[q]);
-        for (int s2 = 1; s2 < ks; ++s2) {           // split-K slabs, added in a fixed order
-          float w[8];
-          load8<true>(a.acc, (long long)(s2 * slab) + (long long)p * a.d + c, w);
+      for (int q = 0; q < NC; ++q) {
+        const int c = tid * 8 + q * 2048;
+        if (c < a.d) {
+          float x[8], g[8], gam[8];
+          raw_unpack(xc[q], x);
+          raw_unpack(gc[q], g);
+          raw_unpack(gam_raw[q], gam);
+          if (ks > 1) {
+            for (int s2 = 1; s2 < ks; ++s2) {       // split-K slabs, added in a fixed order
+              float w[8];
+              load8<true>(a.acc, (long long)(s2 * slab) + (long long)pc * a.d + c, w);
 #pragma unroll
-          for (int e = 0; e < 8; ++e) g[q][e] += w[e];
+              for (int e = 0; e < 8; ++e) g[e] += w[e];
+            }
+            gc[q].a = make_float4(g[0], g[1], g[2], g[3]);
+            gc[q].b = make_float4(g[4], g[5], g[6], g[7]);
+          }
+#pragma unroll
+          for (int e = 0; e < 8; ++e) dot = fmaf(gam[e] * g[e], x[e] * rstd, dot);
         }
+      }
+      dot = wave_sum(dot);
+      float* rb = red[parity];                      // alternating buffers: one barrier per row is enough
+      parity ^= 1;
+      if (lane == 0) rb[wave] = dot;
+      __syncthreads();
+      dot = ((rb[0] + rb[1]) + (rb[2] + rb[3])) * inv_d;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) dot = fmaf(gam[q][e] * g[q][e], x[q][e] * rstd, dot);
+      for (int q = 0; q < NC; ++q) {
+        const int c = tid * 8 + q * 2048;
+        if (c < a.d) {
+          opaque(xc[q]);
+          float x[8], g[8], gam[8], dx[8];
+          raw_unpack(xc[q], x);
+          raw_unpack(gc[q], g);
+          raw_unpack(gam_raw[q], gam);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            const float xh = x[e] * rstd;
+            dx[e] = rstd * (gam[e] * g[e] - xh * dot);
+            dg[q][e] = fmaf(g[e], xh, dg[q][e]);
+          }
+          store8<F32>(a.dH, row * a.d + c, dx);
+        }
       }
     }
-    __syncthreads();                                // red[] of the previous row has been read by everybody
-    dot = block_sum4(dot, red, lane, wave) * inv_d;
 #pragma unroll
-    for (int q = 0; q < NORM_NC; ++q) {
-      const int c = tid * 8 + q * 2048;
-      if (c < a.d) {
-        float dx[8];
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          const float xh = x[q][e] * rstd;
-          dx[e] = rstd * (gam[q][e] * g[q][e] - xh * dot);
-          dg[q][e] = fmaf(g[q][e], xh, dg[q][e]);
-        }
-        store8<F32>(a.dH, row * a.d + c, dx);
-      }
-    }
+    for (int q = 0; q < NC; ++q) { xc[q] = xn[q]; gc[q] = gn[q]; }
+    pc = pn; rc = rn;
   }
   float* part = n.partial + (size_t)blockIdx.x * a.d;
 #pragma unroll
-  for (int q = 0; q < NORM_NC; ++q) {
+  for (int q = 0; q < NC; ++q) {
     const int c = tid * 8 + q * 2048;
     if (c < a.d) {
       *reinterpret_cast<float4*>(part + c) = make_float4(dg[q][0], dg[q][1], dg[q][2], dg[q][3]);
@@ -1137,9 +1206,18 @@ __global__ __launch_bounds__(256) void scatter_dx_norm_kernel(ScatterArgs a, Nor
   }
 }
 
+template <bool F32>
+static void launch_scatter_dx_norm_rows(const ScatterArgs& a, const NormFuse& n, hipStream_t s) {
+  switch ((a.d + 2047) / 2048) {     // 8-column steps per thread; d <= NORM_MAX_D is checked by the caller
+    case 1: hipLaunchKernelGGL((scatter_dx_norm_kernel<F32, 1>), dim3(NORM_STRIPS), dim3(256), 0, s, a, n); break;
+    case 2: hipLaunchKernelGGL((scatter_dx_norm_kernel<F32, 2>), dim3(NORM_STRIPS), dim3(256), 0, s, a, n); break;
+    case 3: hipLaunchKernelGGL((scatter_dx_norm_kernel<F32, 3>), dim3(NORM_STRIPS), dim3(256), 0, s, a, n); break;
+    default: hipLaunchKernelGGL((scatter_dx_norm_kernel<F32, NORM_NC>), dim3(NORM_STRIPS), dim3(256), 0, s, a, n); break;
+  }
+}
 void launch_scatter_dx_norm(const ScatterArgs& a, const NormFuse& n, hipStream_t s) {
-  if (a.out_f32) hipLaunchKernelGGL(scatter_dx_norm_kernel<true>, dim3(NORM_STRIPS), dim3(256), 0, s, a, n);
-  else hipLaunchKernelGGL(scatter_dx_norm_kernel<false>, dim3(NORM_STRIPS), dim3(256), 0, s, a, n);
+  if (a.out_f32) launch_scatter_dx_norm_rows<true>(a, n, s);
+  else launch_scatter_dx_norm_rows<false>(a, n, s);
   NormArgs f{};
   f.d = a.d; f.partial = n.partial; f.dgamma = n.dgamma;
   hipLaunchKernelGGL(rmsnorm_dgamma_kernel, dim3((a.d + 31) / 32), dim3(256), 0, s, f);
