@@ -112,8 +112,9 @@ typedef struct pg_params {
                             and the indices are used as they are (an index outside the tables then reads
                             memory that is not the caller's: undefined) */
   void* w_transposed;    /* optional, loss calls only: DEVICE buffer of pg_w_transposed_bytes(d, V) bytes that
-                            caches the transposed head weight the dH contraction reads.  NULL: the transpose
-                            is rebuilt in the workspace on every call */
+                            caches the transposed head weight the dH contraction reads (for fp32 heads its bf16
+                            values; their remainders are rebuilt in the workspace on every call).  NULL: the
+                            transpose is rebuilt in the workspace on every call */
   int32_t w_transposed_valid; /* 0: this call fills w_transposed from W; 1: it already holds the transpose of
                             this very W (filled by an earlier call, W unchanged since: e.g. the further
                             microbatches of one optimizer step) and the call skips the transposition */

@@ -778,7 +778,7 @@ int32_t loss_fwd_bwd(int sft, const void* H, const void* W, const int32_t* y, co
 
     pg::StoreArgs w{};   // dW[v0 + m, :] = sum_t dS^T[m, t] H^T[:, t]
     w.A = at<__bf16>(ws, pl.dST); w.B = at<__bf16>(ws, pl.HcT);
-    if (pl.is_f32) { w.A_lo = at<__bf16>(ws, pl.dST_lo); w.B_lo = at<__bf16>(ws, pl.HcT_lo); }
+    if (pl.is_f32) { w.A_lo = at<__bf16>(ws, pl.dST_lo); w.B_lo = at<__bf16>(ws, pl.HcT_lo); w.ldb_lo = pl.ld_t; }
     w.a_rows = pl.vc; w.b_rows = d_i;
     w.lda = pl.ld_t; w.ldb = pl.ld_t; w.M = rows_valid; w.N = d_i; w.K = pl.t_cap;
     w.tiles_m = tiles_c; w.tiles_n = (d_i + 255) / 256;
@@ -789,7 +789,7 @@ int32_t loss_fwd_bwd(int sft, const void* H, const void* W, const int32_t* y, co
 
     pg::StoreArgs h{};   // dHacc[t, :] (+)= sum_v dS[t, v] W^T[:, v]
     h.A = at<__bf16>(ws, pl.dS); h.B = wt;
-    if (pl.is_f32) { h.A_lo = at<__bf16>(ws, pl.dS_lo); h.B_lo = at<__bf16>(ws, pl.WT_lo); }
+    if (pl.is_f32) { h.A_lo = at<__bf16>(ws, pl.dS_lo); h.B_lo = at<__bf16>(ws, pl.WT_lo); h.ldb_lo = pl.ld_v; }
     h.a_rows = pl.t_cap; h.b_rows = d_i;
     h.lda = pl.ld_v; h.ldb = ld_wt; h.M = pl.t_cap; h.N = d_i; h.K = kc;
     h.tiles_m = pl.tiles_t; h.tiles_n = (d_i + 255) / 256;

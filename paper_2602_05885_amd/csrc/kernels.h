@@ -61,8 +61,9 @@ struct DlogitsArgs {
 struct StoreArgs {
   const void* A;        // [M, lda] bf16
   const void* B;        // [N, ldb] bf16
-  const void* A_lo;     // fp32 heads: bf16 remainders of A and B (same shapes); the contraction then adds
-  const void* B_lo;     // A B_lo and A_lo B to A B.  Both null otherwise.
+  const void* A_lo;     // fp32 heads: bf16 remainders of A and B (same shapes; A_lo with A's leading dimension,
+  const void* B_lo;     // B_lo with ldb_lo); the contraction then adds A B_lo and A_lo B to A B.  Both null otherwise.
+  int ldb_lo;
   int a_rows, b_rows;   // rows that exist in A / B (loads beyond them give 0)
   int lda, ldb;
   int M, N, K;

@@ -446,7 +446,7 @@ __device__ __forceinline__ void gemm_store_tile(StoreArgs a, const StoreShape& s
   mainloop(LA, LB, s1 - s0, g_smem, acc);
   if (a.A_lo) {   // split fp32 operands: add the two cross terms (the product of the remainders is dropped)
     __syncthreads();
-    LA.init(a.B_lo, a.b_rows, tn * BN, a.ldb, kb, tid);
+    LA.init(a.B_lo, a.b_rows, tn * BN, a.ldb_lo, kb, tid);
     mainloop(LA, LB, s1 - s0, g_smem, acc);
     __syncthreads();
     LA.init(a.B, a.b_rows, tn * BN, a.ldb, kb, tid);

@@ -340,10 +340,13 @@ def test_loss_very_few_active_rows_eight_parts(dev):
     _compare(out, ref)
 
 
-def test_loss_w_transposed_cache(dev, monkeypatch):
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_loss_w_transposed_cache(dev, monkeypatch, dtype):
     """The optional W^T cache: a call that fills it and a call that trusts it give the bits of a call without it
-    (several vocab chunks, ragged vocabulary); a stale cache is really what the dH contraction reads."""
-    spec = synth.small_spec(d=192, V=2100, seed=611)
+    (several vocab chunks, ragged vocabulary); a stale cache is really what the dH contraction reads.  For an
+    fp32 head the cache holds the bf16 values of W^T and the remainders are rebuilt on every call."""
+    spec = synth.small_spec(d=192, V=2100, seed=611, dtype=dtype, unit_rms=(dtype == "bf16"))
+    dt = 0 if dtype == "bf16" else 1
     batch, tin, nin = build_loss_case(spec, dev, oracle_logp, "token", on_policy=False)
     T, d, V, S = batch.T, spec.d, spec.V, batch.S
     monkeypatch.setenv("PG_HEAD_DS_BUDGET_BYTES", str((T + 255) // 256 * 256 * 2 * 256 * 3))
@@ -357,18 +360,22 @@ def test_loss_w_transposed_cache(dev, monkeypatch):
                                 tin["seg_sample"], tin["old"], tin["rollout"], prm, ws)
         torch.cuda.synchronize()
         return out
-    plain = run(B.Params(mismatch_mode=2))
-    fill = run(B.Params(mismatch_mode=2, w_transposed=cache, w_transposed_valid=0))
-    trust = run(B.Params(mismatch_mode=2, w_transposed=cache, w_transposed_valid=1))
+    plain = run(B.Params(dtype=dt, mismatch_mode=2))
+    fill = run(B.Params(dtype=dt, mismatch_mode=2, w_transposed=cache, w_transposed_valid=0))
+    trust = run(B.Params(dtype=dt, mismatch_mode=2, w_transposed=cache, w_transposed_valid=1))
     for k in ("loss", "dH", "dW", "logp", "entropy", "counters"):
         assert torch.equal(fill[k], plain[k]) and torch.equal(trust[k], plain[k]), k
     cache.zero_()                                   # a cache that does not hold W^T: dH = dS 0 = 0, dW untouched
-    stale = run(B.Params(mismatch_mode=2, w_transposed=cache, w_transposed_valid=1))
-    assert not stale["dH"].any() and torch.equal(stale["dW"], plain["dW"])
+    stale = run(B.Params(dtype=dt, mismatch_mode=2, w_transposed=cache, w_transposed_valid=1))
+    assert torch.equal(stale["dW"], plain["dW"])
+    if dtype == "bf16":
+        assert not stale["dH"].any()
+    else:                                           # what is left is dS times the remainders W - bf16(W)
+        assert 0 < np.linalg.norm(np64(stale["dH"])) < 2e-2 * np.linalg.norm(np64(plain["dH"]))
     with pytest.raises(ValueError):
         B.pg_loss_fwd_bwd(tin["H"], tin["W"], tin["y"], tin["loss_mask"], tin["cu"], adv.reshape(-1), tin["seg_sample"],
-                          tin["old"], tin["rollout"], B.Params(mismatch_mode=2, w_transposed=cache[:64]),
-                          B.alloc_workspace(T, d, V, S, B.Params(), B.CALL_LOSS_FWD_BWD, dev))
+                          tin["old"], tin["rollout"], B.Params(dtype=dt, mismatch_mode=2, w_transposed=cache[:64]),
+                          B.alloc_workspace(T, d, V, S, B.Params(dtype=dt), B.CALL_LOSS_FWD_BWD, dev))
 
 
 def test_loss_all_masked_and_all_rejected(dev):
