@@ -301,20 +301,25 @@ def test_loss_f32_multichunk_with_truncation(dev, monkeypatch):
     _compare(out, ref, logp_tol=2e-4, grad_tol=5e-5)
 
 
-@pytest.mark.parametrize("budget_tiles,d", [(None, 128), (4, 128), (None, 512)])
-def test_loss_few_active_rows_split_contraction(dev, monkeypatch, budget_tiles, d):
+@pytest.mark.parametrize("budget_tiles,d,dtype", [(None, 128, "bf16"), (4, 128, "bf16"), (None, 512, "bf16"), (4, 128, "f32")])
+def test_loss_few_active_rows_split_contraction(dev, monkeypatch, budget_tiles, d, dtype):
     """Most samples rejected by the geometric window: the active rows fill a fraction of the padded row
     capacity, so the dH contraction is cut along the vocabulary into parts that accumulate side by side
-    (one chunk; several chunks whose last one is too short to be cut; several column tiles)."""
-    spec = synth.small_spec(seed=8080, d=d, V=4200, P=4, K=6, Tmax=3, len_lo=40, len_hi=120)
-    prm = B.Params(mismatch_mode=1)
+    (one chunk; several chunks whose last one is too short to be cut; several column tiles; an fp32 head,
+    whose parts each add their two remainder terms)."""
+    spec = synth.small_spec(seed=8080, d=d, V=4200, P=4, K=6, Tmax=3, len_lo=40, len_hi=120, dtype=dtype,
+                            unit_rms=(dtype == "bf16"))
+    prm = B.Params(dtype=0 if dtype == "bf16" else 1, mismatch_mode=1)
     out, ref, batch = _run_loss(dev, spec, prm, "window", on_policy=False, monkeypatch=monkeypatch,
                                 budget_tiles=budget_tiles)
     n_active = int(ref["counters"][0])
     t_cap = (batch.T + 255) // 256 * 256
     n_pad = (n_active + 255) // 256 * 256
     assert 0 < n_active and 2 * n_pad <= t_cap, (n_active, t_cap)       # room for at least two parts
-    _compare(out, ref)
+    if dtype == "bf16":
+        _compare(out, ref)
+    else:
+        _compare(out, ref, logp_tol=2e-4, grad_tol=5e-5)
     out2, _, _ = _run_loss(dev, spec, prm, "window", on_policy=False, monkeypatch=monkeypatch, budget_tiles=budget_tiles)
     assert torch.equal(out["dH"], out2["dH"]) and torch.equal(out["dW"], out2["dW"])      # fixed summation order
 

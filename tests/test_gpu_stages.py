@@ -215,13 +215,17 @@ def test_rmsnorm_feeds_the_head(dev):
     assert rel_fro(dg.double().cpu().numpy(), dg_ref) <= TOL_GRAD
 
 
-@pytest.mark.parametrize("dtype,mode,kind,seed", [("bf16", 2, "token", 71), ("bf16", 1, "window", 72), ("f32", 0, "none", 73)])
-def test_loss_with_fused_rmsnorm(dev, monkeypatch, dtype, mode, kind, seed):
+@pytest.mark.parametrize("dtype,mode,kind,seed,few", [("bf16", 2, "token", 71, False), ("bf16", 1, "window", 72, False),
+                                                      ("f32", 0, "none", 73, False), ("bf16", 1, "window", 8080, True)])
+def test_loss_with_fused_rmsnorm(dev, monkeypatch, dtype, mode, kind, seed, few):
     """pg_loss_fwd_bwd_normed (normalisation applied while the rows are compacted, its backward while dH is
     scattered) against the oracle's chain rmsnorm_fwd -> pg_loss_fwd_bwd -> rmsnorm_bwd, several vocab chunks,
     masked and rejected rows; and against the separate calls of the library (same kernels around the head)."""
     from tests._cases import segment_offsets, ratio_targets, block_rel_fro
-    spec = synth.small_spec(seed=seed, d=192, V=2300, dtype=dtype, P=3, K=4, Tmax=3)
+    if few:     # most samples rejected: the dH accumulator holds several split-K slabs that the fused backward adds up
+        spec = synth.small_spec(seed=seed, d=128, V=4200, dtype=dtype, P=4, K=6, Tmax=3, len_lo=40, len_hi=120)
+    else:
+        spec = synth.small_spec(seed=seed, d=192, V=2300, dtype=dtype, P=3, K=4, Tmax=3)
     batch = synth.make_batch(spec)
     T, d, V, S = batch.T, spec.d, spec.V, batch.S
     monkeypatch.setenv("PG_HEAD_DS_BUDGET_BYTES", str(((T + 255) // 256 * 256) * 2 * 256 * 3))
@@ -255,6 +259,8 @@ def test_loss_with_fused_rmsnorm(dev, monkeypatch, dtype, mode, kind, seed):
     tol_lp = TOL_LOGP if dtype == "bf16" else 2e-4
     assert np.array_equal(out["counters"].cpu().numpy(), ref["counters"])
     assert 0 < ref["counters"][0] < T
+    if few:
+        assert 2 * ((int(ref["counters"][0]) + 255) // 256 * 256) <= (T + 255) // 256 * 256      # room for two parts
     assert np.abs(out["logp"].cpu().numpy() - ref["logp"]).max() <= tol_lp
     assert np.abs(out["entropy"].cpu().numpy() - ref["entropy"]).max() <= tol_lp
     assert abs(float(out["loss"][0]) - ref["loss"]) <= TOL_LOSS * abs(ref["loss"])
