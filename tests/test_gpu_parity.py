@@ -519,6 +519,19 @@ def test_loss_random_shapes(dev, seed, monkeypatch):
     prm = B.Params(dtype=0 if spec.dtype == "bf16" else 1, temperature=spec.temperature, mismatch_mode=mode,
                    clip_eps_lo=0.2, clip_eps_hi=0.2, dW_dtype=int(rng.integers(0, 2)),
                    norm_override=float(rng.choice([0.0, 0.0, 777.0])))
-    out, ref, batch = _run_loss(dev, spec, prm, kind, on_policy=bool(rng.integers(0, 2)), monkeypatch=monkeypatch,
-                                budget_tiles=int(rng.integers(1, 6)))
-    _compare(out, ref, TOL_LOGP if spec.dtype == "bf16" else 2e-4)
+    on_policy, budget, accumulate = bool(rng.integers(0, 2)), int(rng.integers(1, 6)), bool(rng.integers(0, 2))
+    prm.accumulate_dW = int(accumulate)
+    out, ref, batch = _run_loss(dev, spec, prm, kind, on_policy=on_policy, monkeypatch=monkeypatch, budget_tiles=budget,
+                                accumulate=accumulate)
+    if spec.dtype == "bf16" or prm.dW_dtype:       # (a bf16 dW rounds an fp32 head's gradient like any other)
+        _compare(out, ref, TOL_LOGP if spec.dtype == "bf16" else 2e-4)
+    else:
+        _compare(out, ref, 2e-4, grad_tol=5e-5)
+    # the same call with the W^T cache, filled by it and then trusted, gives the same bits
+    cache = B.alloc_w_transposed(spec.d, spec.V, dev)
+    for valid in (0, 1):
+        prm.w_transposed, prm.w_transposed_valid = cache, valid
+        again, _, _ = _run_loss(dev, spec, prm, kind, on_policy=on_policy, monkeypatch=monkeypatch, budget_tiles=budget,
+                                accumulate=accumulate)
+        for k in ("loss", "dH", "dW", "logp", "entropy", "counters"):
+            assert torch.equal(again[k], out[k]), (valid, k)
