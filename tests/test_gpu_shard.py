@@ -149,6 +149,14 @@ def test_shard_loss_backward(dev, monkeypatch, mode, kind, tau, cuts, dtype):
             assert np.linalg.norm(np64(out["dW"]) - ref["dW"]) <= TOL_GRAD * np.linalg.norm(full["dW"]) / np.sqrt(V)
             assert np.linalg.norm(dH - ref["dH"]) <= TOL_GRAD * np.linalg.norm(full["dH"])
         dH_sum += dH
+        # the shard's own W^T cache (filled by the call, then trusted): the same bits
+        prm_c = B.Params(dtype=prm.dtype, mismatch_mode=mode, temperature=tau, w_transposed=B.alloc_w_transposed(d, b - a, dev))
+        for valid in (0, 1):
+            prm_c.w_transposed_valid = valid
+            again = B.pg_loss_shard_bwd(tin["H"], Wsh, tin["y"], tin["loss_mask"], tin["cu"], adv.reshape(-1), tin["seg_sample"],
+                                        tin["old"], tin["rollout"], merged, a, prm_c, ws, dH_f32=True)
+            torch.cuda.synchronize()
+            assert torch.equal(again["dH"], out["dH"]) and torch.equal(again["dW"], out["dW"]), ((a, b), valid)
     assert rel_fro(dH_sum, full["dH"]) <= TOL_GRAD
 
 

@@ -47,6 +47,13 @@ def test_sft_parity(dev, T, d, V, dtype, tau, seed, mask_frac, monkeypatch):
     assert np.all(np64(out["dH"])[mask == 0] == 0)
     cnt = out["counters"].cpu().numpy()
     assert cnt[0] == ref["n"] and cnt[6] == ref["n"] and not cnt[1:6].any()
+    # with the W^T cache (filled by the call, then trusted): the same bits
+    prm.w_transposed = B.alloc_w_transposed(d, V, dev)
+    for valid in (0, 1):
+        prm.w_transposed_valid = valid
+        again = B.pg_sft_fwd_bwd(H, W, y, torch.from_numpy(mask).to(dev), prm, ws)
+        torch.cuda.synchronize()
+        assert torch.equal(again["dH"], out["dH"]) and torch.equal(again["dW"], out["dW"]) and torch.equal(again["loss"], out["loss"])
 
 
 def test_sft_accumulate_override_and_empty(dev):
