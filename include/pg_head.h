@@ -40,6 +40,9 @@
  *     left behind is neither returned nor cleared.  pg_last_error() gives a thread-local message.
  *   - The first call on a device sets kernel attributes and must not happen inside a stream
  *     capture: run one call eagerly, or pg_init(), before capturing.
+ *   - A workspace belongs to one call at a time: it holds the call's intermediate results and the
+ *     tile counters of its kernels.  Calls that may overlap (different streams or threads) need
+ *     workspaces of their own; calls ordered on one stream may share one.
  *   - H is [T,d] row-major, W is [V,d] row-major (LM-head weight, no bias), y[t] is
  *     the token whose log-prob row t predicts (the caller has already shifted).
  *     dtype 0: H, W, dH are bf16 (fp32 accumulation; the logit gradient dS is rounded to bf16 before
