@@ -41,15 +41,10 @@ uint64_t ds_budget() {
   return DS_BUDGET;
 }
 
-// Scratch leading dimensions (multiples of 64 elements = 128 bytes) are made an odd number of
-// 128-byte lines, so that the rows of a tile spread over the memory channels instead of
-// landing on a few of them (power-of-two strides measured 3 % slower).
-inline int64_t pad_ld(int64_t n) { return ((n / 64) % 2 == 0) ? n + 64 : n; }
-
 inline size_t align_up(size_t x) { return (x + ALIGN - 1) / ALIGN * ALIGN; }
 
 // Leading dimension of the caller-owned W^T cache [d, ld]: the vocabulary rounded up to whole tiles.
-inline int64_t wt_cache_ld(int64_t V) { return pad_ld((V + 255) / 256 * 256); }
+inline int64_t wt_cache_ld(int64_t V) { return pg::pad_ld((V + 255) / 256 * 256); }
 
 struct Plan {
   int64_t T = 0, d = 0, V = 0;
@@ -155,7 +150,7 @@ int32_t make_plan(int64_t T, int64_t d, int64_t V, int32_t S, const pg_params* p
     }
     const int64_t nchunks = (tiles_v + chunk_tiles - 1) / chunk_tiles;
     const int64_t vc = chunk_tiles * 256;
-    const int64_t ld_v = pad_ld(vc), ld_t = pad_ld(t_cap);
+    const int64_t ld_v = pg::pad_ld(vc), ld_t = pg::pad_ld(t_cap);
     if ((uint64_t)ld_v * 2 * 256 >= FOUR_GIB || (uint64_t)ld_t * 2 * 256 >= FOUR_GIB)
       return fail(PG_ERR_UNSUPPORTED_SHAPE, "256 rows of a backward scratch matrix reach 4 GiB");
     pl.nchunks = (int)nchunks; pl.chunk_tiles = (int)chunk_tiles; pl.vc = (int)vc;
@@ -772,6 +767,10 @@ int32_t loss_fwd_bwd(int sft, const void* H, const void* W, const int32_t* y, co
     g.yc = at<int>(ws, pl.yc); g.lse2 = at<float>(ws, pl.lse2); g.coefc = at<float>(ws, pl.coefc);
     g.dS = at<__bf16>(ws, pl.dS); g.dST = at<__bf16>(ws, pl.dST); g.ctl = ctl;
     if (pl.is_f32) { g.dS_lo = at<__bf16>(ws, pl.dS_lo); g.dST_lo = at<__bf16>(ws, pl.dST_lo); }
+    pg::Rechunk rc{};
+    rc.enabled = pl.nchunks > 1; rc.chunk = c; rc.tiles_v_all = pl.tiles_v; rc.ld_s_all = (int)pg::pad_ld((int64_t)pl.tiles_v * 256);
+    rc.cap_s = (long long)pl.t_cap * pl.ld_v; rc.cap_t = (long long)pl.vc * pl.ld_t;
+    g.rc = rc;
     unsigned* const queues = at<unsigned>(ws, pl.queue) + pg::QUEUE_SET_WORDS * (1 + 4 * c);
     g.queue = queues; g.queue_lo = queues + 3 * pg::QUEUE_SET_WORDS;
     { ProfScope ps(PG_KERNEL_DLOGITS, st); pg::launch_lmhead_dlogits(g, st); }
@@ -785,6 +784,7 @@ int32_t loss_fwd_bwd(int sft, const void* H, const void* W, const int32_t* y, co
     w.C = static_cast<char*>(dW) + (size_t)v0 * pl.d * dw_elem; w.ldc = d_i;
     w.accumulate = p.accumulate_dW; w.out_bf16 = p.dW_dtype; w.k_from_ctl = 1; w.m_from_ctl = 0; w.ctl = ctl;
     w.queue = queues + pg::QUEUE_SET_WORDS;
+    w.rc = rc; w.rc_role = 1; w.v0 = v0;
     { ProfScope ps(PG_KERNEL_DW, st); pg::launch_gemm_store(w, st); }
 
     pg::StoreArgs h{};   // dHacc[t, :] (+)= sum_v dS[t, v] W^T[:, v]
@@ -796,6 +796,7 @@ int32_t loss_fwd_bwd(int sft, const void* H, const void* W, const int32_t* y, co
     h.C = at<float>(ws, pl.dHacc); h.ldc = d_i;
     h.accumulate = c > 0; h.out_bf16 = 0; h.k_from_ctl = 0; h.m_from_ctl = 1; h.split_k = 1; h.ctl = ctl;
     h.queue = queues + 2 * pg::QUEUE_SET_WORDS;
+    h.rc = rc; h.rc_role = 2; h.v0 = v0;
     { ProfScope ps(PG_KERNEL_DH, st); pg::launch_gemm_store(h, st); }
   }
 

@@ -13,6 +13,33 @@ struct Ctl;
 constexpr int QUEUE_SET_WORDS = 8;
 inline int queue_sets(int nchunks) { return 1 + 4 * nchunks; }
 
+// Scratch leading dimensions (multiples of 64 elements = 128 bytes) are made an odd number of
+// 128-byte lines, so that the rows of a tile spread over the memory channels instead of
+// landing on a few of them (power-of-two strides measured 3 % slower).
+__host__ __device__ inline long long pad_ld(long long n) { return ((n / 64) % 2 == 0) ? n + 64 : n; }
+
+// Few active rows (most samples rejected: known only on the device).  The chunk scratch is sized for
+// t_cap rows; when the rows that are really active are so few that dS of the WHOLE vocabulary fits it, the
+// first chunk's recompute launch covers the whole vocabulary (the same buffers, laid out as
+// [n_pad, ld_s_all] and [V_pad, pad_ld(n_pad)]: 14 rounds of tiles in one launch instead of seven launches
+// of 2.1 rounds at the 14B head with 1536 rows) and the later chunks' recompute launches return at once;
+// the dW and dH launches keep their chunks and read their rows of the wide dS^T, their columns of the wide
+// dS.  Every kernel takes the decision from the same device-side values, and a tile's arithmetic does not
+// depend on it.
+struct Rechunk {
+  int enabled;          // the backward was planned in more than one vocab chunk
+  int chunk;            // this launch's chunk
+  int tiles_v_all;      // 256-row vocab tiles of the whole head
+  int ld_s_all;         // pad_ld(256 tiles_v_all)
+  long long cap_s;      // elements of the dS scratch
+  long long cap_t;      // elements of the dS^T scratch
+};
+__device__ inline bool rechunk_all(const Rechunk& r, int n_pad, int& ld_t_all) {
+  ld_t_all = (int)pad_ld(n_pad);
+  return r.enabled && n_pad > 0 && (long long)n_pad * r.ld_s_all <= r.cap_s &&
+         (long long)r.tiles_v_all * 256 * ld_t_all <= r.cap_t;
+}
+
 // ---- MFMA kernels ---------------------------------------------------------------------
 struct FwdArgs {
   const void* W;        // [V, ldw] bf16
@@ -56,6 +83,7 @@ struct DlogitsArgs {
   const Ctl* ctl;
   unsigned* queue;      // [8] tile counters of this launch's queue, zero at launch
   unsigned* queue_lo;   // [8] the same for the launch that stores the remainders
+  Rechunk rc;
 };
 
 struct StoreArgs {
@@ -77,6 +105,9 @@ struct StoreArgs {
   int split_k;          // with m_from_ctl: cut K into dh_split() parts, part p writes rows p n_pad + m
   const Ctl* ctl;
   unsigned* queue;      // [8] tile counters of this launch's queue, zero at launch
+  Rechunk rc;           // see there; rc_role 0: not a chunked launch, 1: dW of a chunk, 2: dH of a chunk
+  int rc_role;
+  int v0;               // first vocab row of the chunk: its rows of the whole-vocabulary dS^T, its columns of dS
 };
 
 hipError_t init_gemm_kernels();

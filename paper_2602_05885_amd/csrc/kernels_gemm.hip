@@ -358,6 +358,11 @@ __device__ __forceinline__ void dlogits_tile(const DlogitsArgs& a, int tm, int t
 template <bool LO>
 __global__ __launch_bounds__(NTHREADS) void lmhead_dlogits_kernel(DlogitsArgs a) {
   const Ctl ctl = *a.ctl;
+  int ld_t_all;
+  if (rechunk_all(a.rc, ctl.n_pad, ld_t_all)) {         // few active rows: the first chunk's launch covers the vocabulary
+    if (a.rc.chunk > 0) return;
+    a.v0 = 0; a.tiles_v = a.rc.tiles_v_all; a.ld_s = a.rc.ld_s_all; a.ld_t = ld_t_all;
+  }
   const int tiles_t = min(a.tiles_t, ctl.n_pad / BN);   // live token tiles: known only on the device
   TileQueue Q;
   Q.init(a.queue, a.tiles_v * tiles_t, 0);
@@ -464,6 +469,18 @@ __device__ __forceinline__ void gemm_store_tile(StoreArgs a, const StoreShape& s
 
 __global__ __launch_bounds__(NTHREADS) void gemm_store_kernel(StoreArgs a) {
   const Ctl ctl = *a.ctl;
+  int ld_t_all;
+  if (a.rc_role && rechunk_all(a.rc, ctl.n_pad, ld_t_all)) {   // few active rows, see Rechunk
+    if (a.rc_role == 1) {          // dW: this chunk's rows of the dS^T that spans the whole vocabulary
+      a.A = static_cast<const char*>(a.A) + (size_t)a.v0 * ld_t_all * 2;
+      if (a.A_lo) a.A_lo = static_cast<const char*>(a.A_lo) + (size_t)a.v0 * ld_t_all * 2;
+      a.lda = ld_t_all;
+    } else {                       // dH: this chunk's columns of the dS rows that span the whole vocabulary
+      a.A = static_cast<const char*>(a.A) + (size_t)a.v0 * 2;
+      if (a.A_lo) a.A_lo = static_cast<const char*>(a.A_lo) + (size_t)a.v0 * 2;
+      a.lda = a.rc.ld_s_all;
+    }
+  }
   StoreShape sh;
   sh.init(a, ctl);
   TileQueue Q;
