@@ -46,8 +46,8 @@ def measured_mfma_only_tflops():
 # summarised in profiles/gemm_store_kernel_hbm_traffic.md (mean over a step's 14 launches, each
 # counter scaled by what it reads for a plain 1 GiB copy).  Valid only for the kernel sources the
 # counters were taken with: the digest below is of csrc/gemm_core.h + csrc/kernels_gemm.hip.
-TRAFFIC_GEMM_STORE = {"read_bytes": 5876038.7 * 1024 * 2.000, "write_bytes": 546987.1 * 1024 * 1.000,
-                      "sources_sha256": "c937d818352df223de933a9183e2a49676b3aeada81e65fb7c5a1d0a03fc9340"}
+TRAFFIC_GEMM_STORE = {"read_bytes": 5873740.1 * 1024 * 2.000, "write_bytes": 547145.8 * 1024 * 1.000,
+                      "sources_sha256": "b723ddea9561855eacbc87e3419af6609ef3501b8bad89cd1a341ee4c90ba681"}
 
 
 def kernel_sources_digest() -> str:
