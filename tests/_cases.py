@@ -84,3 +84,17 @@ def block_rel_fro(a, b, rows=256):
     err = np.array([np.linalg.norm(a[i * rows:(i + 1) * rows] - b[i * rows:(i + 1) * rows]) for i in range(n)])
     floor = 1e-3 * (den.mean() if den.size and den.mean() > 0 else 1.0)
     return float((err / np.maximum(den, floor)).max()) if n else 0.0
+
+
+def pad_ld(n: int) -> int:
+    """Leading dimension the library gives a scratch matrix with n columns (an odd number of 128-byte lines)."""
+    return n + 64 if (n // 64) % 2 == 0 else n
+
+
+def recompute_covers_vocabulary(T: int, V: int, n_pad: int, chunk_rows: int) -> bool:
+    """The library's device-side rule for few active rows, restated for the tests: dS of the whole vocabulary fits
+    the chunk scratch (sized for t_cap rows and chunk_rows columns) at n_pad rows, in both orientations."""
+    t_cap, v_pad = (T + 255) // 256 * 256, (V + 255) // 256 * 256
+    if chunk_rows >= v_pad or n_pad <= 0:
+        return False                                  # one chunk anyway / nothing to do
+    return n_pad * pad_ld(v_pad) <= t_cap * pad_ld(chunk_rows) and v_pad * pad_ld(n_pad) <= chunk_rows * pad_ld(t_cap)

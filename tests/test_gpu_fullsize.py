@@ -309,6 +309,9 @@ def test_full_geometric_rejection_few_rows_split_contraction(full_case):
     parts = dh_split_parts(n_pad, t_cap, (d + 255) // 256, vc // 64)
     print(f"[fullsize] geometric rejection keeps {n_act} rows (padded {n_pad}): dH contraction in {parts} parts", flush=True)
     assert parts >= 2
+    # ... and the recompute of the whole vocabulary runs in the first chunk's launch
+    from tests._cases import recompute_covers_vocabulary
+    assert vc < V and recompute_covers_vocabulary(T, V, n_pad, vc)
     # per-row outputs against the oracle on sampled active rows; inactive rows are zero
     act = np.nonzero(active)[0]
     rows = np.sort(rng.choice(act, 24, replace=False))

@@ -324,12 +324,19 @@ def test_loss_few_active_rows_split_contraction(dev, monkeypatch, budget_tiles, 
     assert torch.equal(out["dH"], out2["dH"]) and torch.equal(out["dW"], out2["dW"])      # fixed summation order
 
 
-def test_loss_very_few_active_rows_eight_parts(dev):
-    """Four samples of 58 kept by their keep flags: the dH contraction runs in its maximum of eight parts."""
-    spec = synth.small_spec(seed=8081, d=128, V=4200, P=4, K=6, Tmax=3, len_lo=40, len_hi=120)
-    prm = B.Params(mismatch_mode=2)
+@pytest.mark.parametrize("budget_tiles,dtype", [(None, "bf16"), (3, "bf16"), (5, "f32")])
+def test_loss_very_few_active_rows(dev, monkeypatch, budget_tiles, dtype):
+    """Four samples of 58 kept by their keep flags.  In one vocab chunk the dH contraction runs in its maximum of
+    eight parts; planned in several chunks, the rows are so few that the recompute of the whole vocabulary runs in
+    the first chunk's launch and dW / dH read the wide layout of dS (bf16 and fp32 heads)."""
+    from tests._cases import recompute_covers_vocabulary
+    spec = synth.small_spec(seed=8081, d=128, V=4200, P=4, K=6, Tmax=3, len_lo=40, len_hi=120, dtype=dtype,
+                            unit_rms=(dtype == "bf16"))
+    prm = B.Params(dtype=0 if dtype == "bf16" else 1, mismatch_mode=2)
     batch, tin, nin = build_loss_case(spec, dev, oracle_logp, "token", on_policy=False)
     T, d, V, S = batch.T, spec.d, spec.V, batch.S
+    if budget_tiles is not None:
+        monkeypatch.setenv("PG_HEAD_DS_BUDGET_BYTES", str((T + 255) // 256 * 256 * 2 * 256 * budget_tiles))
     keep = np.zeros(spec.P * spec.K * spec.Tmax, np.uint8)
     keep[nin["seg_sample"][[3, 17, 30, 44]]] = 1
     adv, _, _ = B.trloo_advantage(tin["rewards"], tin["valid"], 1.0)
@@ -342,7 +349,15 @@ def test_loss_very_few_active_rows_eight_parts(dev):
                             nin["old"], nin["rollout"], O.Params(mismatch_mode=2), seg_keep=keep[nin["seg_sample"]])
     n_pad = (int(ref["counters"][0]) + 255) // 256 * 256
     assert 0 < n_pad and 8 * n_pad <= (T + 255) // 256 * 256
-    _compare(out, ref)
+    chunk_rows = B.pg_backward_chunk_rows(T, d, V, S, prm)
+    if budget_tiles is None:
+        assert chunk_rows >= V
+    else:
+        assert chunk_rows == 256 * budget_tiles and recompute_covers_vocabulary(T, V, n_pad, chunk_rows)
+    if dtype == "bf16":
+        _compare(out, ref)
+    else:
+        _compare(out, ref, logp_tol=2e-4, grad_tol=5e-5)
 
 
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
